@@ -1,0 +1,137 @@
+"""CPU oracle for batched top-k maximum-inner-product retrieval (ctypes front of
+``ann_oracle.c``).
+
+TEST INFRASTRUCTURE ONLY: imported by ``tests/``, ``__graft_entry__.smoke()``
+and the ``cpu_baseline`` leg of ``bench.py``; never by the product package, and
+it imports nothing from it.  All arrays are host numpy arrays; fp16 / bf16
+inputs are passed as their raw 16-bit patterns (``uint16`` or ``float16``), so
+the oracle sees exactly the bits the GPU reads.
+
+Paper passages: exact vs approximate retrieval, Section 2.1 "Retrieval
+Mechanism"; candidate list with best and worst element and the natural stop,
+Section 3.3; search range = candidate-list size, up to 32 neighbours per node,
+Appendix B.3.  Recall of an approximate result is measured against exact
+retrieval (Appendix B.2 quotes such recall values without a formula; the usual
+definition is used: mean over queries of |approx ids ∩ exact ids| / k).
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from typing import Optional, Tuple
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "ann_oracle.c")
+_LIB = os.path.join(_HERE, "libann_oracle.so")
+
+F16, BF16, F32 = 0, 1, 2
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile ann_oracle.c with gcc into oracle/libann_oracle.so."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        subprocess.check_call(["gcc", "-O2", "-fopenmp", "-fPIC", "-shared", "-std=c11",
+                               "-Wall", "-Wextra", "-o", _LIB, _SRC, "-lm"])
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        lib = ctypes.CDLL(_LIB)
+        c = ctypes
+        lib.oracle_threads.restype = c.c_int
+        lib.oracle_threads.argtypes = [c.c_int]
+        lib.oracle_score.restype = c.c_double
+        lib.oracle_score.argtypes = [c.c_void_p, c.c_int32, c.c_int, c.c_int64, c.c_void_p, c.c_int32]
+        lib.oracle_flat_search.restype = c.c_int
+        lib.oracle_flat_search.argtypes = [c.c_void_p, c.c_int64, c.c_int32, c.c_int, c.c_void_p,
+                                           c.c_int32, c.c_int32, c.c_void_p, c.c_void_p, c.c_void_p, c.c_int]
+        lib.oracle_graph_search.restype = c.c_int
+        lib.oracle_graph_search.argtypes = [c.c_void_p, c.c_int64, c.c_int32, c.c_int, c.c_void_p, c.c_int32,
+                                            c.c_int32, c.c_void_p, c.c_int32, c.c_int32, c.c_int32,
+                                            c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_int]
+        _lib = lib
+    return _lib
+
+
+def _code(a: np.ndarray, dtype: Optional[str]) -> int:
+    if dtype is not None:
+        return {"f16": F16, "bf16": BF16, "f32": F32}[dtype]
+    if a.dtype == np.float16:
+        return F16
+    if a.dtype == np.float32:
+        return F32
+    raise ValueError("pass dtype='bf16' (or 'f16') for raw uint16 storage")
+
+
+def _prep(corpus, queries, dtype):
+    corpus = np.ascontiguousarray(corpus)
+    queries = np.ascontiguousarray(queries)
+    if corpus.ndim != 2 or queries.ndim != 2 or corpus.shape[1] != queries.shape[1]:
+        raise ValueError("corpus [N,d] and queries [B,d] expected")
+    if corpus.dtype.itemsize != queries.dtype.itemsize:
+        raise ValueError("corpus and queries must share the storage type")
+    return corpus, queries, _code(corpus, dtype)
+
+
+def threads(n: int = 0) -> int:
+    return _load().oracle_threads(n)
+
+
+def score(corpus, queries, b: int, row: int, dtype: Optional[str] = None) -> float:
+    corpus, queries, code = _prep(corpus, queries, dtype)
+    return _load().oracle_score(corpus.ctypes.data, corpus.shape[1], code, row, queries.ctypes.data, b)
+
+
+def flat_search(corpus, queries, k: int, *, dtype: Optional[str] = None,
+                n_threads: int = 0) -> Tuple[np.ndarray, np.ndarray, np.ndarray]:
+    """Exact top-k.  Returns (ids int32 [B,k], scores fp32 [B,k], scores fp64 [B,k])."""
+    corpus, queries, code = _prep(corpus, queries, dtype)
+    N, d = corpus.shape
+    B = queries.shape[0]
+    ids = np.empty((B, k), np.int32)
+    sc = np.empty((B, k), np.float32)
+    sc64 = np.empty((B, k), np.float64)
+    rc = _load().oracle_flat_search(corpus.ctypes.data, N, d, code, queries.ctypes.data, B, k,
+                                    ids.ctypes.data, sc.ctypes.data, sc64.ctypes.data, n_threads)
+    if rc != 0:
+        raise ValueError("oracle_flat_search: bad arguments")
+    return ids, sc, sc64
+
+
+def graph_search(corpus, graph, entry: int, queries, k: int, ef: int, *, dtype: Optional[str] = None,
+                 n_threads: int = 0):
+    """Best-first graph search.  Returns (ids, scores fp32, scores fp64, n_dist, n_expand)."""
+    corpus, queries, code = _prep(corpus, queries, dtype)
+    graph = np.ascontiguousarray(graph, dtype=np.int32)
+    N, d = corpus.shape
+    if graph.ndim != 2 or graph.shape[0] != N:
+        raise ValueError("graph [N,R] expected")
+    B = queries.shape[0]
+    ids = np.empty((B, k), np.int32)
+    sc = np.empty((B, k), np.float32)
+    sc64 = np.empty((B, k), np.float64)
+    nd = np.empty(B, np.int64)
+    ne = np.empty(B, np.int64)
+    rc = _load().oracle_graph_search(corpus.ctypes.data, N, d, code, graph.ctypes.data, graph.shape[1],
+                                     entry, queries.ctypes.data, B, k, ef, ids.ctypes.data,
+                                     sc.ctypes.data, sc64.ctypes.data, nd.ctypes.data, ne.ctypes.data,
+                                     n_threads)
+    if rc != 0:
+        raise ValueError("oracle_graph_search: bad arguments")
+    return ids, sc, sc64, nd, ne
+
+
+def recall_at_k(approx_ids: np.ndarray, exact_ids: np.ndarray) -> float:
+    """Mean over queries of |approx ∩ exact| / k; padding ids (-1) never match."""
+    B, k = exact_ids.shape
+    hit = 0
+    for b in range(B):
+        hit += len(set(int(i) for i in approx_ids[b] if i >= 0) & set(int(i) for i in exact_ids[b]))
+    return hit / (B * k)

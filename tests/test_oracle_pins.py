@@ -1,0 +1,290 @@
+"""Pins for the CPU oracle: it is checked against things other than itself —
+closed forms, library routines on special cases, a hand trace, a second
+set-based formulation of the beam search, and invariants — chosen so that a
+dropped term, a wrong sign or index, a transposed operand or a wrong tie rule
+fails at least one of them.  No GPU, no product code."""
+import os
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+rng = np.random.default_rng(1234)
+
+
+def unit_rows(n, d, dtype=np.float32):
+    x = rng.standard_normal((n, d)).astype(np.float32)
+    x /= np.linalg.norm(x, axis=1, keepdims=True)
+    return x.astype(dtype)
+
+
+# ---------------------------------------------------------------- storage decoding
+
+def test_half_decode_all_bit_patterns():
+    """Every fp16 bit pattern, scored against q = [1], must decode exactly as numpy does."""
+    bits = np.arange(65536, dtype=np.uint16)
+    corpus = bits.view(np.float16).reshape(-1, 1)
+    q = np.array([[1.0]], np.float16)
+    want = corpus.astype(np.float64)[:, 0]
+    for row in list(range(0, 65536, 257)) + [0, 1, 0x3ff, 0x400, 0x7bff, 0x8000, 0x8001, 0xfbff, 0x3c00]:
+        if np.isnan(want[row]) or np.isinf(want[row]):
+            continue
+        assert oracle.score(corpus, q, 0, row) == want[row], hex(row)
+
+
+def test_bf16_decode_matches_torch():
+    t = torch.randn(4096).to(torch.bfloat16)
+    bits = t.view(torch.int16).numpy().view(np.uint16).reshape(-1, 1)
+    q = torch.ones(1, 1, dtype=torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    want = t.double().numpy()
+    for row in range(0, 4096, 37):
+        assert oracle.score(bits, q, 0, row, dtype="bf16") == want[row]
+
+
+def test_accumulates_in_double():
+    """1 + 2^-30 - 1 is 2^-30 in double and 0 in fp32."""
+    corpus = np.array([[1.0, 2.0 ** -30, -1.0]], np.float32)
+    q = np.ones((1, 3), np.float32)
+    assert oracle.score(corpus, q, 0, 0) == 2.0 ** -30
+    _, _, s64 = oracle.flat_search(corpus, q, 1)
+    assert s64[0, 0] == 2.0 ** -30
+
+
+# ---------------------------------------------------------------- exact retrieval
+
+def test_flat_closed_form_basis_corpus():
+    """Corpus = signed, scaled basis vectors: score(n) = c_n * q[perm[n]], so the
+    exact top-k is known without any dot product.  Catches transposed operands,
+    wrong row strides and a wrong sign of the order."""
+    d = 24
+    perm = rng.permutation(d)
+    coef = rng.uniform(0.5, 2.0, d).astype(np.float32) * rng.choice([-1.0, 1.0], d).astype(np.float32)
+    corpus = np.zeros((d, d), np.float32)
+    corpus[np.arange(d), perm] = coef
+    q = rng.standard_normal((5, d)).astype(np.float32)
+    ids, sc, sc64 = oracle.flat_search(corpus, q, 6)
+    for b in range(5):
+        closed = coef.astype(np.float64) * q[b, perm].astype(np.float64)
+        want = sorted(range(d), key=lambda n: (-closed[n], n))[:6]
+        assert ids[b].tolist() == want
+        assert np.array_equal(sc64[b], closed[want])
+        assert np.array_equal(sc[b], closed[want].astype(np.float32))
+
+
+@pytest.mark.parametrize("dtype", [np.float32, np.float16])
+def test_flat_matches_numpy_matmul_lexsort(dtype):
+    corpus = unit_rows(700, 40, dtype)
+    q = unit_rows(9, 40, dtype)
+    k = 12
+    ids, sc, sc64 = oracle.flat_search(corpus, q, k)
+    S = q.astype(np.float64) @ corpus.astype(np.float64).T
+    for b in range(q.shape[0]):
+        order = np.lexsort((np.arange(700), -S[b]))[:k]
+        assert ids[b].tolist() == order.tolist()
+        np.testing.assert_allclose(sc64[b], S[b, order], rtol=0, atol=1e-14)
+        assert np.all(np.diff(sc64[b]) <= 0)
+    # k = 1 is the arg-max
+    ids1, _, _ = oracle.flat_search(corpus, q, 1)
+    assert ids1[:, 0].tolist() == np.argmax(S, axis=1).tolist()
+    # k = N returns a permutation of all rows
+    idsN, _, _ = oracle.flat_search(corpus, q[:2], 700)
+    assert sorted(idsN[0].tolist()) == list(range(700))
+
+
+def test_flat_ties_go_to_lower_id():
+    corpus = unit_rows(50, 16)
+    corpus[37] = corpus[5]
+    corpus[44] = corpus[5]
+    q = corpus[5:6].copy()
+    ids, _, sc64 = oracle.flat_search(corpus, q, 4)
+    assert ids[0, :3].tolist() == [5, 37, 44]
+    assert sc64[0, 0] == sc64[0, 1] == sc64[0, 2]
+
+
+def test_flat_rejects_bad_arguments():
+    corpus = unit_rows(10, 8)
+    with pytest.raises(ValueError):
+        oracle.flat_search(corpus, corpus[:2], 11)
+    with pytest.raises(ValueError):
+        oracle.flat_search(corpus, corpus[:2], 0)
+
+
+# ---------------------------------------------------------------- graph retrieval
+
+def read_trace():
+    values, cases, exact = None, [], None
+    for line in open(os.path.join(GOLDEN, "path_graph_trace.txt")):
+        line = line.strip()
+        if not line or line.startswith("#"):
+            continue
+        if line.startswith("values"):
+            values = [float(t) for t in line.split()[1:]]
+        elif line.startswith("case"):
+            a, b, c = line[4:].split("|")
+            ef, k = (int(t) for t in a.split())
+            nd, ne = (int(t) for t in c.split())
+            cases.append((ef, k, [int(t) for t in b.split()], nd, ne))
+        elif line.startswith("exact3"):
+            exact = [int(t) for t in line.split("|")[1].split()]
+    return values, cases, exact
+
+
+def path_graph(n):
+    g = np.full((n, 2), -1, np.int32)
+    g[1:, 0] = np.arange(n - 1)
+    g[:-1, 1] = np.arange(1, n)
+    return g
+
+
+def test_graph_hand_trace():
+    values, cases, exact = read_trace()
+    corpus = np.array(values, np.float32).reshape(-1, 1)
+    q = np.ones((1, 1), np.float32)
+    g = path_graph(len(values))
+    for ef, k, want_ids, want_nd, want_ne in cases:
+        ids, sc, _, nd, ne = oracle.graph_search(corpus, g, 0, q, k, ef)
+        assert ids[0].tolist() == want_ids, (ef, ids)
+        assert (int(nd[0]), int(ne[0])) == (want_nd, want_ne), ef
+        assert sc[0].tolist() == [np.float32(values[i]) for i in want_ids]
+    ids, _, _ = oracle.flat_search(corpus, q, 3)
+    assert ids[0].tolist() == exact
+    g_ids = oracle.graph_search(corpus, g, 0, q, 3, 3)[0]
+    assert oracle.recall_at_k(g_ids, ids) == pytest.approx(2 / 3)
+
+
+def beam_search_by_sets(S, graph, entry, k, ef):
+    """Second formulation: after every scored node the list is *recomputed* as the
+    best ef of everything scored so far; expanded nodes are a set of ids."""
+    N, R = graph.shape
+    key = lambda v: (-S[v], v)
+    seen = {entry}
+    expanded = set()
+    n_expand = 0
+    while True:
+        L = sorted(seen, key=key)[:ef]
+        todo = [v for v in L if v not in expanded]
+        if not todo:
+            break
+        p = todo[0]
+        expanded.add(p)
+        n_expand += 1
+        for v in graph[p]:
+            v = int(v)
+            if 0 <= v < N:
+                seen.add(v)
+    L = sorted(seen, key=key)[:ef]
+    return L[:k], len(seen), n_expand
+
+
+def random_graph(n, R, p_empty=0.1):
+    g = rng.integers(0, n, size=(n, R)).astype(np.int32)
+    g[rng.random((n, R)) < p_empty] = -1
+    return g
+
+
+@pytest.mark.parametrize("ef", [1, 2, 5, 16, 64])
+def test_graph_matches_set_formulation(ef):
+    n, d, R = 48, 12, 4
+    corpus = unit_rows(n, d)
+    q = unit_rows(6, d)
+    g = random_graph(n, R)
+    g[3, 0] = n + 5          # out-of-range id must be skipped
+    g[7, 1] = 7              # self loop
+    g[9, 2] = g[9, 3]        # duplicate in a row
+    S = q.astype(np.float64) @ corpus.astype(np.float64).T
+    k = min(ef, 3)
+    ids, _, sc64, nd, ne = oracle.graph_search(corpus, g, 11, q, k, ef)
+    for b in range(q.shape[0]):
+        want, n_seen, n_exp = beam_search_by_sets(S[b], g, 11, k, ef)
+        got = [i for i in ids[b].tolist() if i >= 0]
+        assert got == want, (b, ef)
+        assert int(nd[b]) == n_seen and int(ne[b]) == n_exp
+        assert int(nd[b]) <= 1 + R * int(ne[b])
+        np.testing.assert_allclose(sc64[b, :len(got)], S[b, got], atol=1e-14)
+
+
+def connected_graph(n, R):
+    g = random_graph(n, R)
+    i = np.arange(n, dtype=np.int32)
+    return np.concatenate([g, ((i + 1) % n)[:, None], ((i - 1) % n)[:, None]], 1).astype(np.int32)
+
+
+def test_graph_with_ef_at_least_n_on_connected_graph_is_exact():
+    n, d = 300, 24
+    corpus = unit_rows(n, d, np.float16)
+    q = unit_rows(10, d, np.float16)
+    g = connected_graph(n, 6)
+    f_ids, f_sc, f_sc64 = oracle.flat_search(corpus, q, 10)
+    for ef in (n, n + 17):
+        ids, sc, sc64, nd, ne = oracle.graph_search(corpus, g, 123, q, 10, ef)
+        assert np.array_equal(ids, f_ids)
+        assert np.array_equal(sc64, f_sc64)
+        assert np.all(nd == n) and np.all(ne == n)
+
+
+def test_graph_complete_graph_any_ef_is_exact():
+    n, d = 40, 8
+    corpus = unit_rows(n, d)
+    q = unit_rows(7, d)
+    g = np.array([[j for j in range(n) if j != i] for i in range(n)], np.int32)
+    f_ids, _, _ = oracle.flat_search(corpus, q, 5)
+    for ef in (5, 9, 40):
+        ids = oracle.graph_search(corpus, g, 0, q, 5, ef)[0]
+        assert np.array_equal(ids, f_ids)
+
+
+def test_graph_invariants_and_padding():
+    n, d, R = 200, 16, 5
+    corpus = unit_rows(n, d)
+    q = unit_rows(12, d)
+    g = random_graph(n, R, 0.2)
+    # two islands: nodes < 60 only point below 60, the rest only at or above 60
+    g[:60] = np.where(g[:60] >= 0, g[:60] % 60, -1)
+    g[60:] = np.where(g[60:] >= 0, 60 + g[60:] % (n - 60), -1)
+    f_ids, _, f64 = oracle.flat_search(corpus, q, 8)
+    ids, sc, sc64, nd, ne = oracle.graph_search(corpus, g, 5, q, 8, 32)
+    for b in range(q.shape[0]):
+        got = [i for i in ids[b].tolist() if i >= 0]
+        assert len(set(got)) == len(got)
+        assert all(i < 60 for i in got)                       # stays in the entry's island
+        assert np.all(np.diff(sc64[b, :len(got)]) <= 0)
+        assert np.all(sc64[b, :len(got)] <= f64[b, :len(got)] + 1e-15)   # rank-wise bound
+    # a sink entry: only the entry itself is reachable, the rest is padding
+    g2 = g.copy()
+    g2[5] = -1
+    ids, sc, _, nd, ne = oracle.graph_search(corpus, g2, 5, q[:2], 4, 8)
+    assert ids.tolist() == [[5, -1, -1, -1]] * 2
+    assert np.all(np.isneginf(sc[:, 1:])) and np.all(nd == 1) and np.all(ne == 1)
+
+
+def test_graph_tie_rule_prefers_lower_id():
+    """Two identical vectors: the lower id is listed first and expanded first."""
+    corpus = unit_rows(6, 4)
+    corpus[4] = corpus[2]
+    q = corpus[2:3].copy()
+    g = np.array([[4, 2], [-1, -1], [1, -1], [-1, -1], [3, -1], [-1, -1]], np.int32)
+    # from 0: scores 4 then 2 (equal scores). ef=2 keeps both, order must be [2, 4].
+    ids, _, _, nd, ne = oracle.graph_search(corpus, g, 0, q, 2, 2)
+    assert ids[0].tolist() == [2, 4]
+    # with ef = 1 node 4 is listed first (0 dropped), then 2 is scored with an equal
+    # score and the lower id, so it precedes 4 and replaces it
+    ids, _, _, _, _ = oracle.graph_search(corpus, g, 0, q, 1, 1)
+    assert ids[0].tolist() == [2]
+
+
+def test_graph_rejects_bad_arguments():
+    corpus = unit_rows(10, 8)
+    g = random_graph(10, 3)
+    with pytest.raises(ValueError):
+        oracle.graph_search(corpus, g, 0, corpus[:1], 4, 3)      # ef < k
+    with pytest.raises(ValueError):
+        oracle.graph_search(corpus, g, 10, corpus[:1], 1, 4)     # entry out of range
+
+
+def test_recall_definition():
+    exact = np.array([[1, 2, 3], [4, 5, 6]], np.int32)
+    approx = np.array([[3, 9, 1], [-1, -1, 4]], np.int32)
+    assert oracle.recall_at_k(approx, exact) == pytest.approx(3 / 6)
