@@ -1,0 +1,147 @@
+/*
+ * ann.h — C ABI of the MI355X retrieval library (libann.so).
+ *
+ * The retrieval step a search agent calls between reasoning steps: batched
+ * top-k maximum-inner-product search of query embeddings over a passage
+ * embedding corpus, in the two forms the paper contrasts (Section 2.1,
+ * "Retrieval Mechanism"; Section 2.2.1; Appendix B.3):
+ *
+ *   - exact retrieval ("ENN", full recall): every corpus vector is scored;
+ *   - approximate graph retrieval ("ANN"): best-first search over a proximity
+ *     graph with a candidate list whose size `ef` (the paper's "search range",
+ *     efSearch) trades recall against cost (Section 2.2.1), refined until no
+ *     unexpanded candidate is left (the natural stop of Section 3.3).
+ *
+ * Conventions common to every entry point
+ *   - All data pointers are DEVICE pointers owned by the caller; nothing is
+ *     retained after a call returns except the record made by
+ *     ann_register_corpus.  `stream` is a hipStream_t (NULL = default stream).
+ *     Work is only enqueued: results are valid once the caller has
+ *     synchronised `stream`.  No entry point synchronises the device except
+ *     when the library-owned workspace has to grow (first call, or a larger
+ *     B*k than any call before on this device).
+ *   - corpus  [N, d] row-major, contiguous, 16-byte aligned base.
+ *     queries [B, d] row-major, same element type as the corpus.
+ *     graph   [N, R] row-major int32; a slot < 0 or >= N is empty and skipped.
+ *     ids     [B, k] int32 out; scores [B, k] float out.
+ *   - Element types: ANN_F16 (IEEE binary16), ANN_BF16, ANN_F32.  d must be a
+ *     multiple of 8 for the 16-bit types and of 4 for ANN_F32.
+ *   - score(q, x) = sum_j q_j * x_j, accumulated in fp32 (products of two
+ *     16-bit values are exact in fp32).  Larger is better.
+ *   - Order: (s, id) precedes (s', id') iff s > s' or (s == s' and id < id').
+ *     Row b of ids/scores holds the first k entries in that order.  When fewer
+ *     than k entries exist (graph search that reaches fewer than k nodes) the
+ *     tail is id = -1, score = -inf.  Same inputs give bitwise-same outputs.
+ *   - Scores that are NaN are never returned.
+ *   - Return value: ANN_OK, or a negative ANN_ERR_* code, in which case
+ *     nothing was enqueued and no output was written.  ann_last_error() gives
+ *     a message for the calling thread's last failure.
+ */
+#ifndef ANN_H
+#define ANN_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define ANN_OK                  0
+#define ANN_ERR_INVALID        -1   /* null pointer, size out of range, k > N, ef < k, ... */
+#define ANN_ERR_ALIGNMENT      -2   /* d not a multiple of 8 (4 for fp32) or base not 16-B aligned */
+#define ANN_ERR_UNKNOWN_CORPUS -3   /* ann_graph_search on a corpus pointer never registered */
+#define ANN_ERR_LAUNCH         -4   /* HIP reported an error when a kernel was enqueued */
+#define ANN_ERR_NOMEM          -5   /* the device workspace could not be allocated */
+
+#define ANN_F16   0
+#define ANN_BF16  1
+#define ANN_F32   2
+
+#define ANN_K_MAX    16      /* largest k of the flat search */
+#define ANN_EF_MAX   4096    /* largest candidate list of the graph search (k <= ef) */
+#define ANN_R_MAX    256     /* largest graph out-degree */
+#define ANN_D_MAX    4096    /* largest embedding dimension */
+
+/* Library version as major*10000 + minor*100 + patch. */
+int ann_version(void);
+
+/* Message for the last error returned to the calling thread ("" if none). */
+const char *ann_last_error(void);
+
+/*
+ * Exact top-k retrieval (Section 2.1: exact nearest neighbour search; the
+ * "vLLM_ENN" configuration of Section 4.1 / Appendix B.3).
+ *
+ *   corpus  device, [N, d] of `dtype`      N >= 1, N < 2^31
+ *   queries device, [B, d] of `dtype`      B >= 1
+ *   k       1 <= k <= min(N, ANN_K_MAX)
+ *   ids     device, [B, k] int32  (written)
+ *   scores  device, [B, k] float  (written)
+ *
+ * Every corpus row is scored against every query; the score matrix is never
+ * materialised.  Uses the library workspace of the current device
+ * (B * P * k * 8 bytes, P = number of corpus slabs, at most 2048).
+ */
+int ann_flat_search_typed(const void *corpus, int64_t N, int32_t d, int32_t dtype,
+                          const void *queries, int32_t B, int32_t k,
+                          int32_t *ids, float *scores, void *stream);
+
+/* Same, for a corpus of the default element type (ANN_F16 unless changed by
+ * ann_set_default_dtype). */
+int ann_flat_search(const void *corpus, int64_t N, int32_t d,
+                    const void *queries, int32_t B, int32_t k,
+                    int32_t *ids, float *scores, void *stream);
+
+/*
+ * Approximate retrieval by best-first search over a proximity graph (Section
+ * 2.1: graph-based ANN; Section 3.3: a candidate list with a best and a worst
+ * element that is refined iteratively; Appendix B.3: at most 32 neighbours per
+ * node, search range efSearch).
+ *
+ * Per query: visited = {entry}; list L = [(score(entry), entry)].  Repeat:
+ * take the first unexpanded element p of L (the best one, ties to the lower
+ * id); stop when there is none; mark it expanded; for every slot of graph row
+ * p in slot order, skip empty / out-of-range / already scored ids, score the
+ * rest and put each into L when L has fewer than ef entries or it precedes
+ * L's last element; L keeps its best ef entries.  Output: the first k of L.
+ *
+ *   corpus  device, [N, d] of `dtype`
+ *   graph   device, [N, R] int32, 1 <= R <= ANN_R_MAX
+ *   entry   node id in [0, N), by value, shared by all queries
+ *   k, ef   1 <= k <= ef <= ANN_EF_MAX
+ *
+ * One workgroup serves one query; candidate list and visited filter live in
+ * LDS, so no workspace is used.
+ */
+int ann_graph_search_typed(const void *corpus, int64_t N, int32_t d, int32_t dtype,
+                           const int32_t *graph, int32_t R, int32_t entry,
+                           const void *queries, int32_t B, int32_t k, int32_t ef,
+                           int32_t *ids, float *scores, void *stream);
+
+/* Same with (N, d, dtype) looked up from a previous ann_register_corpus(corpus,...).
+ * Returns ANN_ERR_UNKNOWN_CORPUS if `corpus` was never registered. */
+int ann_graph_search(const void *corpus, const int32_t *graph, int32_t R, int32_t entry,
+                     const void *queries, int32_t B, int32_t k, int32_t ef,
+                     int32_t *ids, float *scores, void *stream);
+
+/* Remember the shape and element type of a corpus so that ann_graph_search can
+ * be called with the short argument list.  Re-registering a pointer replaces
+ * its record.  The library never dereferences or frees the pointer here. */
+int ann_register_corpus(const void *corpus, int64_t N, int32_t d, int32_t dtype);
+
+/* Forget a registered corpus (no error if it is unknown). */
+int ann_unregister_corpus(const void *corpus);
+
+/* Element type assumed by ann_flat_search (process-wide; default ANN_F16). */
+int ann_set_default_dtype(int32_t dtype);
+
+/* Bytes of device workspace a flat search of this shape needs. */
+int64_t ann_flat_workspace_bytes(int64_t N, int32_t d, int32_t dtype, int32_t B, int32_t k);
+
+/* Release the library-owned workspace of the current device (synchronises it). */
+int ann_release_workspace(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ANN_H */

@@ -1,0 +1,185 @@
+"""ctypes binding of libann.so: the same entry points as include/ann.h, taking
+torch device tensors.  Argument marshalling only — shapes, pointers, the current
+HIP stream; every step of the search runs in the library's kernels.  There is no
+fallback: if the library is missing or a call fails, an exception is raised."""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Tuple
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libann.so")
+
+ANN_OK, ANN_ERR_INVALID, ANN_ERR_ALIGNMENT, ANN_ERR_UNKNOWN_CORPUS, ANN_ERR_LAUNCH, ANN_ERR_NOMEM = 0, -1, -2, -3, -4, -5
+ANN_F16, ANN_BF16, ANN_F32 = 0, 1, 2
+ANN_K_MAX, ANN_EF_MAX, ANN_R_MAX, ANN_D_MAX = 16, 4096, 256, 4096
+
+_DTYPES = {torch.float16: ANN_F16, torch.bfloat16: ANN_BF16, torch.float32: ANN_F32}
+
+EXPORTS = ("ann_version", "ann_last_error", "ann_flat_search_typed", "ann_flat_search",
+           "ann_graph_search_typed", "ann_graph_search", "ann_register_corpus", "ann_unregister_corpus",
+           "ann_set_default_dtype", "ann_flat_workspace_bytes", "ann_release_workspace")
+
+
+class AnnError(RuntimeError):
+    def __init__(self, code: int, message: str):
+        super().__init__(f"libann error {code}: {message}")
+        self.code = code
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """The loaded library; raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(
+                f"{LIB_PATH} is missing: build it with `python -m paper_2505_12065_amd.build` "
+                "(or __graft_entry__.build()); there is no fallback path")
+        L = ctypes.CDLL(LIB_PATH)
+        c = ctypes
+        vp, i32, i64 = c.c_void_p, c.c_int32, c.c_int64
+        L.ann_version.restype = c.c_int
+        L.ann_last_error.restype = c.c_char_p
+        L.ann_flat_search_typed.argtypes = [vp, i64, i32, i32, vp, i32, i32, vp, vp, vp]
+        L.ann_flat_search.argtypes = [vp, i64, i32, vp, i32, i32, vp, vp, vp]
+        L.ann_graph_search_typed.argtypes = [vp, i64, i32, i32, vp, i32, i32, vp, i32, i32, i32, vp, vp, vp]
+        L.ann_graph_search.argtypes = [vp, vp, i32, i32, vp, i32, i32, i32, vp, vp, vp]
+        L.ann_register_corpus.argtypes = [vp, i64, i32, i32]
+        L.ann_unregister_corpus.argtypes = [vp]
+        L.ann_set_default_dtype.argtypes = [i32]
+        L.ann_flat_workspace_bytes.argtypes = [i64, i32, i32, i32, i32]
+        L.ann_flat_workspace_bytes.restype = i64
+        for name in EXPORTS:
+            if name not in ("ann_last_error", "ann_flat_workspace_bytes"):
+                getattr(L, name).restype = c.c_int
+        _lib = L
+    return _lib
+
+
+def _check(rc: int) -> None:
+    if rc != ANN_OK:
+        raise AnnError(rc, lib().ann_last_error().decode())
+
+
+def _stream(stream) -> int:
+    if stream is None:
+        return torch.cuda.current_stream().cuda_stream
+    return stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream)
+
+
+def _outputs(B: int, k: int, device, ids, scores):
+    if ids is None:
+        ids = torch.empty(B, k, dtype=torch.int32, device=device)
+    if scores is None:
+        scores = torch.empty(B, k, dtype=torch.float32, device=device)
+    if ids.shape != (B, k) or ids.dtype != torch.int32 or not ids.is_contiguous() or not ids.is_cuda:
+        raise ValueError("ids must be a contiguous int32 [B, k] device tensor")
+    if scores.shape != (B, k) or scores.dtype != torch.float32 or not scores.is_contiguous() or not scores.is_cuda:
+        raise ValueError("scores must be a contiguous float32 [B, k] device tensor")
+    return ids, scores
+
+
+def _matrix(t: torch.Tensor, name: str) -> torch.Tensor:
+    if t.dim() != 2 or not t.is_cuda or not t.is_contiguous() or t.dtype not in _DTYPES:
+        raise ValueError(f"{name} must be a contiguous 2-D fp16/bf16/fp32 device tensor")
+    return t
+
+
+def ann_version() -> int:
+    return lib().ann_version()
+
+
+def ann_last_error() -> str:
+    return lib().ann_last_error().decode()
+
+
+def ann_flat_search_typed(corpus: torch.Tensor, queries: torch.Tensor, k: int, *, ids=None, scores=None,
+                          stream=None) -> Tuple[torch.Tensor, torch.Tensor]:
+    """Exact top-k of every query over the corpus; element type taken from the tensors."""
+    _matrix(corpus, "corpus"), _matrix(queries, "queries")
+    if queries.dtype != corpus.dtype or queries.shape[1] != corpus.shape[1]:
+        raise ValueError("queries must have the corpus' element type and dimension")
+    (N, d), B = corpus.shape, queries.shape[0]
+    ids, scores = _outputs(B, k, corpus.device, ids, scores)
+    with torch.cuda.device(corpus.device):
+        _check(lib().ann_flat_search_typed(corpus.data_ptr(), N, d, _DTYPES[corpus.dtype], queries.data_ptr(), B, k,
+                                           ids.data_ptr(), scores.data_ptr(), _stream(stream)))
+    return ids, scores
+
+
+def ann_flat_search(corpus: torch.Tensor, queries: torch.Tensor, k: int, *, ids=None, scores=None,
+                    stream=None) -> Tuple[torch.Tensor, torch.Tensor]:
+    """Exact top-k through the short entry point, which assumes the library's default
+    element type (fp16 unless ann_set_default_dtype changed it)."""
+    _matrix(corpus, "corpus"), _matrix(queries, "queries")
+    if queries.dtype != corpus.dtype or queries.shape[1] != corpus.shape[1]:
+        raise ValueError("queries must have the corpus' element type and dimension")
+    (N, d), B = corpus.shape, queries.shape[0]
+    ids, scores = _outputs(B, k, corpus.device, ids, scores)
+    with torch.cuda.device(corpus.device):
+        _check(lib().ann_flat_search(corpus.data_ptr(), N, d, queries.data_ptr(), B, k, ids.data_ptr(),
+                                     scores.data_ptr(), _stream(stream)))
+    return ids, scores
+
+
+def _graph(graph: torch.Tensor, N: int) -> torch.Tensor:
+    if graph.dim() != 2 or graph.dtype != torch.int32 or not graph.is_cuda or not graph.is_contiguous() \
+            or graph.shape[0] != N:
+        raise ValueError("graph must be a contiguous int32 [N, R] device tensor")
+    return graph
+
+
+def ann_graph_search_typed(corpus: torch.Tensor, graph: torch.Tensor, entry: int, queries: torch.Tensor, k: int,
+                           ef: int, *, ids=None, scores=None, stream=None) -> Tuple[torch.Tensor, torch.Tensor]:
+    """Best-first graph search with a candidate list of ef entries."""
+    _matrix(corpus, "corpus"), _matrix(queries, "queries")
+    if queries.dtype != corpus.dtype or queries.shape[1] != corpus.shape[1]:
+        raise ValueError("queries must have the corpus' element type and dimension")
+    (N, d), B = corpus.shape, queries.shape[0]
+    _graph(graph, N)
+    ids, scores = _outputs(B, k, corpus.device, ids, scores)
+    with torch.cuda.device(corpus.device):
+        _check(lib().ann_graph_search_typed(corpus.data_ptr(), N, d, _DTYPES[corpus.dtype], graph.data_ptr(),
+                                            graph.shape[1], int(entry), queries.data_ptr(), B, k, ef,
+                                            ids.data_ptr(), scores.data_ptr(), _stream(stream)))
+    return ids, scores
+
+
+def ann_graph_search(corpus: torch.Tensor, graph: torch.Tensor, entry: int, queries: torch.Tensor, k: int, ef: int,
+                     *, ids=None, scores=None, stream=None) -> Tuple[torch.Tensor, torch.Tensor]:
+    """Graph search through the short entry point: the corpus must have been registered."""
+    _matrix(queries, "queries")
+    B = queries.shape[0]
+    ids, scores = _outputs(B, k, queries.device, ids, scores)
+    with torch.cuda.device(queries.device):
+        _check(lib().ann_graph_search(corpus.data_ptr(), graph.data_ptr(), graph.shape[1], int(entry),
+                                      queries.data_ptr(), B, k, ef, ids.data_ptr(), scores.data_ptr(),
+                                      _stream(stream)))
+    return ids, scores
+
+
+def ann_register_corpus(corpus: torch.Tensor) -> None:
+    _matrix(corpus, "corpus")
+    _check(lib().ann_register_corpus(corpus.data_ptr(), corpus.shape[0], corpus.shape[1], _DTYPES[corpus.dtype]))
+
+
+def ann_unregister_corpus(corpus: torch.Tensor) -> None:
+    _check(lib().ann_unregister_corpus(corpus.data_ptr()))
+
+
+def ann_set_default_dtype(dtype: torch.dtype) -> None:
+    _check(lib().ann_set_default_dtype(_DTYPES[dtype]))
+
+
+def ann_flat_workspace_bytes(N: int, d: int, dtype: torch.dtype, B: int, k: int) -> int:
+    return int(lib().ann_flat_workspace_bytes(N, d, _DTYPES[dtype], B, k))
+
+
+def ann_release_workspace() -> None:
+    _check(lib().ann_release_workspace())

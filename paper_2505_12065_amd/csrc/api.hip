@@ -1,0 +1,257 @@
+// libann.so — host side of the C ABI declared in include/ann.h: argument checks,
+// launch geometry, the per-device workspace and the corpus registry.  All compute
+// runs in the kernels reached through launch.hpp.
+#include <hip/hip_runtime.h>
+
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <mutex>
+#include <string>
+#include <unordered_map>
+
+#include "../../include/ann.h"
+#include "launch.hpp"
+
+using namespace ann;
+
+namespace {
+
+thread_local std::string g_last_error;
+
+int fail(int code, const char *fmt, ...) {
+    char buf[512];
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(buf, sizeof buf, fmt, ap);
+    va_end(ap);
+    g_last_error = buf;
+    return code;
+}
+
+constexpr int P_MAX = 2048;
+
+struct DeviceState {
+    int cus = 0;
+    void *ws = nullptr;
+    size_t ws_bytes = 0;
+};
+
+std::mutex g_mu;
+std::unordered_map<int, DeviceState> g_dev;
+struct CorpusInfo { int64_t N; int32_t d; int32_t dtype; };
+std::unordered_map<const void *, CorpusInfo> g_corpora;
+int g_default_dtype = ANN_F16;
+
+int device_state(DeviceState **out) {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return fail(ANN_ERR_LAUNCH, "no HIP device is current");
+    DeviceState &st = g_dev[dev];
+    if (st.cus == 0) {
+        if (hipDeviceGetAttribute(&st.cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || st.cus <= 0)
+            return fail(ANN_ERR_LAUNCH, "cannot query the compute-unit count of device %d", dev);
+    }
+    *out = &st;
+    return ANN_OK;
+}
+
+int ensure_workspace(DeviceState *st, size_t bytes) {
+    if (st->ws_bytes >= bytes) return ANN_OK;
+    if (st->ws) (void)hipFree(st->ws);           // synchronises the device: no kernel still uses it
+    st->ws = nullptr;
+    st->ws_bytes = 0;
+    size_t want = bytes + bytes / 4;
+    if (hipMalloc(&st->ws, want) != hipSuccess) {
+        (void)hipGetLastError();
+        return fail(ANN_ERR_NOMEM, "cannot allocate %zu bytes of device workspace", want);
+    }
+    st->ws_bytes = want;
+    return ANN_OK;
+}
+
+int check_launch(const char *what, hipError_t e) {
+    if (e != hipSuccess) {
+        (void)hipGetLastError();
+        return fail(ANN_ERR_LAUNCH, "%s: %s", what, hipGetErrorString(e));
+    }
+    return ANN_OK;
+}
+
+int elem_bytes(int dtype) { return dtype == ANN_F32 ? 4 : 2; }
+
+int check_common(const void *corpus, int64_t N, int32_t d, int32_t dtype, const void *queries, int32_t B,
+                 int32_t k, const void *ids, const void *scores) {
+    if (dtype != ANN_F16 && dtype != ANN_BF16 && dtype != ANN_F32)
+        return fail(ANN_ERR_INVALID, "unknown element type %d", dtype);
+    if (!corpus || !queries || !ids || !scores) return fail(ANN_ERR_INVALID, "null pointer argument");
+    if (N < 1 || N > INT32_MAX) return fail(ANN_ERR_INVALID, "N = %lld out of range", (long long)N);
+    if (B < 1) return fail(ANN_ERR_INVALID, "B = %d out of range", B);
+    if (d < 1 || d > ANN_D_MAX) return fail(ANN_ERR_INVALID, "d = %d out of range [1, %d]", d, ANN_D_MAX);
+    if (k < 1 || k > N) return fail(ANN_ERR_INVALID, "k = %d out of range [1, N]", k);
+    if ((d * elem_bytes(dtype)) % 16 != 0)
+        return fail(ANN_ERR_ALIGNMENT, "d = %d: a row must be a whole number of 16-byte chunks", d);
+    if ((reinterpret_cast<uintptr_t>(corpus) | reinterpret_cast<uintptr_t>(queries)) & 15)
+        return fail(ANN_ERR_ALIGNMENT, "corpus and queries must be 16-byte aligned");
+    if ((reinterpret_cast<uintptr_t>(ids) | reinterpret_cast<uintptr_t>(scores)) & 3)
+        return fail(ANN_ERR_ALIGNMENT, "ids and scores must be 4-byte aligned");
+    return ANN_OK;
+}
+
+int kp_of(int k) { return k <= 4 ? 4 : 16; }
+
+// ---- flat: launch geometry ---------------------------------------------------------------
+struct FlatPlan {
+    int kp, P, nqg_max;
+    size_t ws_bytes;
+};
+
+FlatPlan flat_plan(int cus, int64_t N, int d, int dtype, int B, int k) {
+    FlatPlan pl;
+    pl.kp = kp_of(k);
+    if (dtype == ANN_F32) {
+        const int64_t groups = (N + 7) / 8;
+        int64_t P = (groups + 3) / 4;
+        const int64_t cap = (int64_t)cus * 4;
+        pl.P = (int)(P < cap ? P : cap);
+        pl.nqg_max = 0;
+    } else {
+        const int steps = (d + 31) / 32;
+        int nqg_max = (int)((LDS_MAX - 16 * 1024) / ((size_t)steps * WAVE * 16));
+        pl.nqg_max = nqg_max > 4 ? 4 : nqg_max;
+        const int nqg = B > 16 * pl.nqg_max ? pl.nqg_max : (B + 15) / 16;
+        const size_t lds = stream_lds_bytes(nqg, steps, STREAM_THREADS / WAVE, pl.kp);
+        int occ = (int)(LDS_MAX / lds);
+        occ = occ < 1 ? 1 : (occ > 2 ? 2 : occ);
+        const int64_t tiles = (N + 15) / 16;
+        int64_t P = (tiles + STREAM_THREADS / WAVE - 1) / (STREAM_THREADS / WAVE);
+        const int64_t cap = (int64_t)cus * occ;
+        pl.P = (int)(P < cap ? P : cap);
+    }
+    if (pl.P > P_MAX) pl.P = P_MAX;
+    if (pl.P < 1) pl.P = 1;
+    pl.ws_bytes = (size_t)B * pl.P * pl.kp * sizeof(Cand);
+    return pl;
+}
+
+int flat_search_run(const FlatPlan &pl, const void *X, int64_t N, int d, int dtype, const void *Q, int B, int k,
+                    int32_t *ids, float *scores, Cand *partial, hipStream_t stream) {
+    if (dtype == ANN_F32) {
+        hipError_t e = launch_flat_f32(pl.kp, static_cast<const float *>(X), N, d, static_cast<const float *>(Q), B,
+                                       partial, pl.P, stream);
+        if (int rc = check_launch("flat_f32_kernel", e)) return rc;
+    } else {
+        for (int q0 = 0; q0 < B; q0 += 16 * pl.nqg_max) {
+            const int left = B - q0;
+            const int nqg = left > 16 * pl.nqg_max ? pl.nqg_max : (left + 15) / 16;
+            hipError_t e = dtype == ANN_F16
+                               ? launch_flat_stream_f16(nqg, pl.kp, X, N, d, Q, B, q0, partial, pl.P, stream)
+                               : launch_flat_stream_bf16(nqg, pl.kp, X, N, d, Q, B, q0, partial, pl.P, stream);
+            if (int rc = check_launch("flat_stream_kernel", e)) return rc;
+        }
+    }
+    return check_launch("flat_merge_kernel", launch_flat_merge(pl.kp, partial, pl.P, B, k, ids, scores, stream));
+}
+
+}  // namespace
+
+extern "C" {
+
+int ann_version(void) { return 100; }
+
+const char *ann_last_error(void) { return g_last_error.c_str(); }
+
+int ann_set_default_dtype(int32_t dtype) {
+    if (dtype != ANN_F16 && dtype != ANN_BF16 && dtype != ANN_F32)
+        return fail(ANN_ERR_INVALID, "unknown element type %d", dtype);
+    std::lock_guard<std::mutex> lock(g_mu);
+    g_default_dtype = dtype;
+    return ANN_OK;
+}
+
+int ann_register_corpus(const void *corpus, int64_t N, int32_t d, int32_t dtype) {
+    if (!corpus || N < 1 || N > INT32_MAX || d < 1 || d > ANN_D_MAX ||
+        (dtype != ANN_F16 && dtype != ANN_BF16 && dtype != ANN_F32))
+        return fail(ANN_ERR_INVALID, "ann_register_corpus: bad shape or element type");
+    std::lock_guard<std::mutex> lock(g_mu);
+    g_corpora[corpus] = CorpusInfo{N, d, dtype};
+    return ANN_OK;
+}
+
+int ann_unregister_corpus(const void *corpus) {
+    std::lock_guard<std::mutex> lock(g_mu);
+    g_corpora.erase(corpus);
+    return ANN_OK;
+}
+
+int64_t ann_flat_workspace_bytes(int64_t N, int32_t d, int32_t dtype, int32_t B, int32_t k) {
+    if (N < 1 || d < 1 || d > ANN_D_MAX || B < 1 || k < 1 || k > ANN_K_MAX) return ANN_ERR_INVALID;
+    std::lock_guard<std::mutex> lock(g_mu);
+    DeviceState *st = nullptr;
+    int cus = 256;
+    if (device_state(&st) == ANN_OK) cus = st->cus;
+    return (int64_t)flat_plan(cus, N, d, dtype, B, k).ws_bytes;
+}
+
+int ann_release_workspace(void) {
+    std::lock_guard<std::mutex> lock(g_mu);
+    DeviceState *st = nullptr;
+    if (int rc = device_state(&st)) return rc;
+    if (st->ws) (void)hipFree(st->ws);
+    st->ws = nullptr;
+    st->ws_bytes = 0;
+    return ANN_OK;
+}
+
+int ann_flat_search_typed(const void *corpus, int64_t N, int32_t d, int32_t dtype, const void *queries,
+                          int32_t B, int32_t k, int32_t *ids, float *scores, void *stream) {
+    if (int rc = check_common(corpus, N, d, dtype, queries, B, k, ids, scores)) return rc;
+    if (k > ANN_K_MAX) return fail(ANN_ERR_INVALID, "k = %d exceeds ANN_K_MAX = %d", k, ANN_K_MAX);
+    std::lock_guard<std::mutex> lock(g_mu);
+    DeviceState *st = nullptr;
+    if (int rc = device_state(&st)) return rc;
+    const FlatPlan pl = flat_plan(st->cus, N, d, dtype, B, k);
+    if (dtype != ANN_F32 && pl.nqg_max < 1) return fail(ANN_ERR_INVALID, "d = %d too large for LDS", d);
+    if (int rc = ensure_workspace(st, pl.ws_bytes)) return rc;
+    Cand *partial = static_cast<Cand *>(st->ws);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    return flat_search_run(pl, corpus, N, d, dtype, queries, B, k, ids, scores, partial, s);
+}
+
+int ann_flat_search(const void *corpus, int64_t N, int32_t d, const void *queries, int32_t B, int32_t k,
+                    int32_t *ids, float *scores, void *stream) {
+    return ann_flat_search_typed(corpus, N, d, g_default_dtype, queries, B, k, ids, scores, stream);
+}
+
+int ann_graph_search_typed(const void *corpus, int64_t N, int32_t d, int32_t dtype, const int32_t *graph,
+                           int32_t R, int32_t entry, const void *queries, int32_t B, int32_t k, int32_t ef,
+                           int32_t *ids, float *scores, void *stream) {
+    if (!graph) return fail(ANN_ERR_INVALID, "null graph pointer");
+    if (R < 1 || R > ANN_R_MAX) return fail(ANN_ERR_INVALID, "R = %d out of range [1, %d]", R, ANN_R_MAX);
+    if (ef < 1 || ef > ANN_EF_MAX) return fail(ANN_ERR_INVALID, "ef = %d out of range [1, %d]", ef, ANN_EF_MAX);
+    if (int rc = check_common(corpus, N, d, dtype, queries, B, k, ids, scores)) return rc;
+    if (k > ef) return fail(ANN_ERR_INVALID, "ef = %d is smaller than k = %d", ef, k);
+    if (entry < 0 || entry >= N) return fail(ANN_ERR_INVALID, "entry = %d is not a node id", entry);
+    if (reinterpret_cast<uintptr_t>(graph) & 3) return fail(ANN_ERR_ALIGNMENT, "graph must be 4-byte aligned");
+    const GraphLds L = graph_lds_layout(d, elem_bytes(dtype), R, ef);
+    if (L.total > LDS_MAX) return fail(ANN_ERR_INVALID, "d = %d, ef = %d need %u bytes of LDS", d, ef, L.total);
+    std::lock_guard<std::mutex> lock(g_mu);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    return check_launch("graph_search_kernel",
+                        launch_graph_search(dtype, corpus, N, d, graph, R, entry, queries, B, k, ef, ids, scores, L, s));
+}
+
+int ann_graph_search(const void *corpus, const int32_t *graph, int32_t R, int32_t entry, const void *queries,
+                     int32_t B, int32_t k, int32_t ef, int32_t *ids, float *scores, void *stream) {
+    CorpusInfo info;
+    {
+        std::lock_guard<std::mutex> lock(g_mu);
+        auto it = g_corpora.find(corpus);
+        if (it == g_corpora.end())
+            return fail(ANN_ERR_UNKNOWN_CORPUS, "corpus %p was never passed to ann_register_corpus", corpus);
+        info = it->second;
+    }
+    return ann_graph_search_typed(corpus, info.N, info.d, info.dtype, graph, R, entry, queries, B, k, ef, ids,
+                                  scores, stream);
+}
+
+}  // extern "C"

@@ -1,0 +1,243 @@
+// Exact (flat) retrieval kernels: every corpus row is scored against every query
+// and the k best per query are kept (Section 2.1 of the paper: exact nearest
+// neighbour retrieval; the score matrix is never written to memory).
+//
+//   flat_stream_kernel  16-bit corpora, up to 64 queries per pass: the corpus is
+//                       streamed from HBM exactly once straight into MFMA operand
+//                       registers; queries sit in LDS in MFMA fragment order.
+//   flat_f32_kernel     fp32 corpora: vector FMA, 8 lanes per row.
+//   flat_merge_kernel   per query: the k best of all slabs' partial lists.
+//
+// Every kernel keeps, per lane, a sorted register list of the KP >= k best
+// pairs it has seen; lists are merged lane -> wave -> workgroup -> grid under
+// the same total order, so the result does not depend on how rows were split.
+#pragma once
+
+#include "common.hpp"
+
+namespace ann {
+
+// Corpus rows are the M side of a 16x16x32 MFMA, queries the N side: a lane ends
+// up with one query (lane % 16) and four rows (4*(lane/16) + i) per tile of 16 rows.
+//   X        [N, d] 16-bit           Q  [B, d] 16-bit (queries q0 .. q0+NQG*16 are used)
+//   partial  [B, P, KP] pairs, P = gridDim.x
+template <class T, int NQG, int KP, bool DFULL>
+__global__ __launch_bounds__(512) void flat_stream_kernel(const void *__restrict__ X, int64_t N, int d,
+                                                          const void *__restrict__ Q, int B, int q0,
+                                                          Cand *__restrict__ partial) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    u4 *qf = reinterpret_cast<u4 *>(smem);            // [NQG][steps][64]
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, nwaves = blockDim.x >> 6;
+    const int steps = (d + 31) >> 5;
+    const int P = gridDim.x;
+
+    // queries -> LDS, already in B-operand order: fragment (g, s) holds for lane l
+    // the 8 values k = 32 s + 8 (l / 16) .. of query q0 + 16 g + l % 16
+    for (int idx = tid; idx < NQG * steps * WAVE; idx += blockDim.x) {
+        const int l = idx & 63, s = (idx >> 6) % steps, g = (idx >> 6) / steps;
+        const int q = q0 + g * 16 + (l & 15), kb = s * 32 + (l >> 4) * 8;
+        u4 v = zero_chunk();
+        if (q < B && kb < d) v = load_chunk(static_cast<const char *>(Q) + ((size_t)q * d + kb) * 2);
+        qf[idx] = v;
+    }
+    __syncthreads();
+
+    TopList<KP> best[NQG];
+    float thr[NQG];
+#pragma unroll
+    for (int g = 0; g < NQG; ++g) { best[g].init(); thr[g] = -INFINITY; }
+
+    const int64_t ntiles = (N + 15) >> 4;
+    const int kofs = (lane >> 4) * 8;                 // this lane's k offset inside a 32-wide step
+    for (int64_t tile = (int64_t)blockIdx.x * nwaves + wave; tile < ntiles; tile += (int64_t)P * nwaves) {
+        int64_t row = tile * 16 + (lane & 15);
+        if (row >= N) row = N - 1;                    // tail tile: re-read the last row, masked below
+        const char *rp = static_cast<const char *>(X) + ((size_t)row * d + kofs) * 2;
+        f4 acc[NQG];
+#pragma unroll
+        for (int g = 0; g < NQG; ++g) acc[g] = f4{0.f, 0.f, 0.f, 0.f};
+
+        int s = 0;
+        for (; s + 8 <= steps; s += 8) {
+            u4 a[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                if (DFULL || (s + u) * 32 + kofs < d) a[u] = load_chunk(rp + (size_t)(s + u) * 64);
+                else a[u] = zero_chunk();
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u)
+#pragma unroll
+                for (int g = 0; g < NQG; ++g)
+                    acc[g] = mfma16<T>(a[u], qf[(g * steps + s + u) * WAVE + lane], acc[g]);
+        }
+        for (; s < steps; ++s) {
+            u4 a = zero_chunk();
+            if (DFULL || s * 32 + kofs < d) a = load_chunk(rp + (size_t)s * 64);
+#pragma unroll
+            for (int g = 0; g < NQG; ++g)
+                acc[g] = mfma16<T>(a, qf[(g * steps + s) * WAVE + lane], acc[g]);
+        }
+
+        const int64_t rbase = tile * 16 + (lane >> 4) * 4;
+        static_for<NQG>([&](auto gc) {
+            constexpr int g = decltype(gc)::value;
+            const f4 a = acc[g];
+            const float m = fmaxf(fmaxf(a[0], a[1]), fmaxf(a[2], a[3]));
+            if (__builtin_amdgcn_ballot_w64(m >= thr[g]) != 0) {        // rare after warm-up
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const int64_t r = rbase + i;
+                    if (r < N && a[i] >= thr[g] && best[g].admits(a[i], (int)r)) best[g].insert(a[i], (int)r);
+                }
+                // the KP-th best of any lane that serves the same query bounds the final
+                // KP-th best from below, so it is a safe rejection threshold for all four
+                float t = best[g].s[KP - 1];
+                t = fmaxf(t, __shfl_xor(t, 16));
+                t = fmaxf(t, __shfl_xor(t, 32));
+                thr[g] = fmaxf(thr[g], t);
+            }
+        });
+    }
+
+    // the four lanes that share a query -> one list per wave and query
+    static_for<NQG>([&](auto gc) {
+        constexpr int g = decltype(gc)::value;
+        best[g].merge_xor(16);
+        best[g].merge_xor(32);
+    });
+
+    __syncthreads();                                   // query fragments are dead from here
+    Cand *wl = reinterpret_cast<Cand *>(smem);         // [nwaves][NQG*16][KP]
+    if (lane < 16) {
+        static_for<NQG>([&](auto gc) {
+            constexpr int g = decltype(gc)::value;
+#pragma unroll
+            for (int j = 0; j < KP; ++j)
+                wl[((size_t)wave * NQG * 16 + g * 16 + lane) * KP + j] = Cand{best[g].s[j], best[g].id[j]};
+        });
+    }
+    __syncthreads();
+    if (tid < NQG * 16 && q0 + tid < B) {
+        TopList<KP> fin;
+        fin.init();
+        for (int w = 0; w < nwaves; ++w)
+            for (int j = 0; j < KP; ++j) {
+                const Cand c = wl[((size_t)w * NQG * 16 + tid) * KP + j];
+                if (fin.admits(c.s, c.id)) fin.insert(c.s, c.id);
+            }
+        Cand *out = partial + ((size_t)(q0 + tid) * P + blockIdx.x) * KP;
+#pragma unroll
+        for (int j = 0; j < KP; ++j) out[j] = Cand{fin.s[j], fin.id[j]};
+    }
+}
+
+// fp32 corpora.  8 lanes share a row (float4 chunks c, c+8, ...), a wave covers 8
+// rows per step, 8 queries per pass live in LDS; lane c of a row group keeps the
+// list of query q0 + c.  gridDim = (P slabs, ceil(B / 8)).
+//   partial [B, P, KP]
+template <int KP>
+__global__ __launch_bounds__(256) void flat_f32_kernel(const float *__restrict__ X, int64_t N, int d,
+                                                       const float *__restrict__ Q, int B,
+                                                       Cand *__restrict__ partial) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    u4 *qs = reinterpret_cast<u4 *>(smem);            // [8][d/4]
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, nwaves = blockDim.x >> 6;
+    const int nch = d >> 2;
+    const int q0 = blockIdx.y * 8;
+    const int P = gridDim.x;
+    for (int idx = tid; idx < 8 * nch; idx += blockDim.x) {
+        const int q = q0 + idx / nch, c = idx % nch;
+        qs[idx] = q < B ? load_chunk(Q + (size_t)q * d + c * 4) : zero_chunk();
+    }
+    __syncthreads();
+
+    TopList<KP> best;
+    best.init();
+    const int r8 = lane >> 3, c8 = lane & 7;
+    const int64_t ngroups = (N + 7) >> 3;
+    for (int64_t grp = (int64_t)blockIdx.x * nwaves + wave; grp < ngroups; grp += (int64_t)P * nwaves) {
+        const int64_t row = grp * 8 + r8;
+        const int64_t rowc = row < N ? row : N - 1;
+        const float *rp = X + (size_t)rowc * d;
+        float acc[8];
+#pragma unroll
+        for (int q = 0; q < 8; ++q) acc[q] = 0.f;
+        for (int c = c8; c < nch; c += 8) {
+            const u4 x = load_chunk(rp + c * 4);
+#pragma unroll
+            for (int q = 0; q < 8; ++q) acc[q] = dot_chunk<F32>(x, qs[q * nch + c], acc[q]);
+        }
+        float mine = 0.f;
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+            float v = acc[q];
+            v += __shfl_xor(v, 1);
+            v += __shfl_xor(v, 2);
+            v += __shfl_xor(v, 4);
+            if (q == c8) mine = v;
+        }
+        if (row < N && best.admits(mine, (int)row)) best.insert(mine, (int)row);
+    }
+    best.merge_xor(8);
+    best.merge_xor(16);
+    best.merge_xor(32);
+
+    __syncthreads();
+    Cand *wl = reinterpret_cast<Cand *>(smem);         // [nwaves][8][KP]
+    if (lane < 8) {
+#pragma unroll
+        for (int j = 0; j < KP; ++j) wl[((size_t)wave * 8 + lane) * KP + j] = Cand{best.s[j], best.id[j]};
+    }
+    __syncthreads();
+    if (tid < 8 && q0 + tid < B) {
+        TopList<KP> fin;
+        fin.init();
+        for (int w = 0; w < nwaves; ++w)
+            for (int j = 0; j < KP; ++j) {
+                const Cand c = wl[((size_t)w * 8 + tid) * KP + j];
+                if (fin.admits(c.s, c.id)) fin.insert(c.s, c.id);
+            }
+        Cand *out = partial + ((size_t)(q0 + tid) * P + blockIdx.x) * KP;
+#pragma unroll
+        for (int j = 0; j < KP; ++j) out[j] = Cand{fin.s[j], fin.id[j]};
+    }
+}
+
+// One workgroup per query: the k best of its P*KP partial pairs, written in order;
+// unused tail slots become id -1 / score -inf.
+template <int KP>
+__global__ __launch_bounds__(256) void flat_merge_kernel(const Cand *__restrict__ partial, int P, int k,
+                                                         int32_t *__restrict__ ids, float *__restrict__ scores) {
+    __shared__ Cand wl[4 * KP];
+    const int q = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const Cand *in = partial + (size_t)q * P * KP;
+    TopList<KP> best;
+    best.init();
+    for (int e = tid; e < P * KP; e += 256) {
+        const Cand c = in[e];
+        if (best.admits(c.s, c.id)) best.insert(c.s, c.id);
+    }
+#pragma unroll
+    for (int m = 1; m < 64; m <<= 1) best.merge_xor(m);
+    if (lane == 0) {
+#pragma unroll
+        for (int j = 0; j < KP; ++j) wl[wave * KP + j] = Cand{best.s[j], best.id[j]};
+    }
+    __syncthreads();
+    if (tid == 0) {
+        TopList<KP> fin;
+        fin.init();
+        for (int e = 0; e < 4 * KP; ++e)
+            if (fin.admits(wl[e].s, wl[e].id)) fin.insert(wl[e].s, wl[e].id);
+#pragma unroll
+        for (int j = 0; j < KP; ++j)
+            if (j < k) {
+                const bool has = fin.id[j] != EMPTY_ID;
+                ids[(size_t)q * k + j] = has ? fin.id[j] : -1;
+                scores[(size_t)q * k + j] = has ? fin.s[j] : -INFINITY;
+            }
+    }
+}
+
+}  // namespace ann

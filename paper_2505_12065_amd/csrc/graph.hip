@@ -1,0 +1,51 @@
+// graph_search_kernel instantiations, LDS layout and launcher.
+#include "graph_kernel.hpp"
+
+namespace ann {
+
+GraphLds graph_lds_layout(int d, int elem_bytes, int R, int ef) {
+    GraphLds L;
+    auto up = [](uint32_t x) { return (x + 15u) & ~15u; };
+    uint32_t off = 0;
+    L.rp = (uint32_t)((R + ROWS_PER_PASS - 1) / ROWS_PER_PASS * ROWS_PER_PASS);
+    // cache slots: a few times the number of nodes a search scores (about 10 ef)
+    uint32_t bits = 10;
+    while ((1u << bits) < 32u * (uint32_t)ef && bits < 14) ++bits;
+    L.cache_bits = bits;
+    L.q = off; off = up(off + (uint32_t)d * elem_bytes);
+    L.ls0 = off; off = up(off + 4u * ef);
+    L.ls1 = off; off = up(off + 4u * ef);
+    L.li0 = off; off = up(off + 4u * ef);
+    L.li1 = off; off = up(off + 4u * ef);
+    L.cs = off; off = up(off + 4u * L.rp);
+    L.ci = off; off = up(off + 4u * L.rp);
+    L.cpos = off; off = up(off + 4u * L.rp);
+    L.cache = off; off = up(off + (4u << bits));
+    L.ctl = off; off = up(off + 16u);
+    L.total = off;
+    return L;
+}
+
+namespace {
+template <class T>
+hipError_t launch(const void *X, int64_t N, int d, const int32_t *graph, int R, int entry, const void *Q, int B,
+                  int k, int ef, int32_t *ids, float *scores, const GraphLds &L, hipStream_t stream) {
+    static bool big = false;
+    if (hipError_t e = allow_big_lds(reinterpret_cast<const void *>(&graph_search_kernel<T>), L.total, &big)) return e;
+    hipLaunchKernelGGL((graph_search_kernel<T>), dim3(B), dim3(GRAPH_THREADS), L.total, stream, X, N, d, graph, R,
+                       entry, Q, k, ef, ids, scores, L);
+    return hipGetLastError();
+}
+}  // namespace
+
+hipError_t launch_graph_search(int dtype, const void *X, int64_t N, int d, const int32_t *graph, int R, int entry,
+                               const void *Q, int B, int k, int ef, int32_t *ids, float *scores,
+                               const GraphLds &L, hipStream_t stream) {
+    switch (dtype) {
+    case 0: return launch<F16>(X, N, d, graph, R, entry, Q, B, k, ef, ids, scores, L, stream);
+    case 1: return launch<BF16>(X, N, d, graph, R, entry, Q, B, k, ef, ids, scores, L, stream);
+    default: return launch<F32>(X, N, d, graph, R, entry, Q, B, k, ef, ids, scores, L, stream);
+    }
+}
+
+}  // namespace ann

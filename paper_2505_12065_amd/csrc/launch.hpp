@@ -1,0 +1,47 @@
+// Host-side launchers of the kernels; one translation unit per kernel family so the
+// library builds in parallel.  Each returns the HIP status of its launch.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "common.hpp"
+
+namespace ann {
+
+constexpr size_t LDS_MAX = 160 * 1024;   // LDS of one gfx950 compute unit
+constexpr int STREAM_THREADS = 512;
+
+// A kernel that needs more than 64 KB of dynamic LDS has to be told so once.
+inline hipError_t allow_big_lds(const void *kernel, size_t bytes, bool *done) {
+    if (bytes <= 64 * 1024 || *done) return hipSuccess;
+    hipError_t e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)LDS_MAX);
+    if (e == hipSuccess) *done = true;
+    return e;
+}
+
+size_t stream_lds_bytes(int nqg, int steps, int waves, int kp);
+size_t f32_lds_bytes(int d, int waves, int kp);
+
+// dtype: 0 = fp16, 1 = bf16.  nqg in 1..4, kp in {4, 16}.
+hipError_t launch_flat_stream_f16(int nqg, int kp, const void *X, int64_t N, int d, const void *Q, int B, int q0,
+                                  Cand *partial, int P, hipStream_t stream);
+hipError_t launch_flat_stream_bf16(int nqg, int kp, const void *X, int64_t N, int d, const void *Q, int B, int q0,
+                                   Cand *partial, int P, hipStream_t stream);
+hipError_t launch_flat_f32(int kp, const float *X, int64_t N, int d, const float *Q, int B, Cand *partial, int P,
+                           hipStream_t stream);
+hipError_t launch_flat_merge(int kp, const Cand *partial, int P, int B, int k, int32_t *ids, float *scores,
+                             hipStream_t stream);
+
+struct GraphLds {
+    // byte offsets into dynamic LDS; all 16-byte aligned
+    uint32_t q, ls0, ls1, li0, li1, cs, ci, cpos, cache, ctl, total;
+    uint32_t cache_bits, rp;
+};
+GraphLds graph_lds_layout(int d, int elem_bytes, int R, int ef);
+// dtype: ANN_F16 / ANN_BF16 / ANN_F32 codes 0 / 1 / 2
+hipError_t launch_graph_search(int dtype, const void *X, int64_t N, int d, const int32_t *graph, int R, int entry,
+                               const void *Q, int B, int k, int ef, int32_t *ids, float *scores,
+                               const GraphLds &L, hipStream_t stream);
+
+}  // namespace ann

@@ -1,0 +1,249 @@
+"""GPU parity: the HIP library, called through its C ABI (via the ctypes binding),
+against the CPU oracle on the same seeded inputs.  Integer outputs (ids) must be
+identical up to the stated near-tie rule, scores within 1e-4 absolute."""
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2505_12065_amd as ann
+from paper_2505_12065_amd import synth
+from parity import TOL, compare_topk, np_dtype_name, recall, to_np
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def say(*a):
+    print(*a, flush=True)
+    sys.stdout.flush()
+
+
+def flat_both(x, q, k):
+    """x, q: cpu tensors.  Returns gpu (ids, scores) as numpy and oracle (ids, sc, sc64)."""
+    ids, sc = ann.ann_flat_search_typed(x.to(DEV), q.to(DEV), k)
+    torch.cuda.synchronize()
+    name = np_dtype_name(x)
+    o = oracle.flat_search(to_np(x), to_np(q), k, dtype=name)
+    return ids.cpu().numpy(), sc.cpu().numpy(), o
+
+
+# ------------------------------------------------------------------ configuration 0 (tiny, fp32)
+
+@pytest.fixture(scope="module")
+def cfg0():
+    c = synth.workload_corpus(0)
+    q = synth.make_queries(c, 64)
+    g = synth.knn_graph(c.x, 16)
+    return c, q, g
+
+
+def test_cfg0_flat_fp32(cfg0):
+    c, q, _ = cfg0
+    say("cfg0 flat: N=10000 d=128 fp32 B=64 k=10")
+    ids, sc, (o_ids, o_sc, o_sc64) = flat_both(c.x, q, 10)
+    strict, tolerant, n = compare_topk(ids, sc, o_ids, o_sc64, c.x.numpy(), q.numpy())
+    say(f"cfg0 flat strict={strict}/{n} tolerant={tolerant}")
+    assert strict >= n - 2
+
+
+def test_cfg0_graph_fp32(cfg0):
+    c, q, g = cfg0
+    say("cfg0 graph: 16-NN graph, entry 0, ef=32, k=10")
+    ids, sc = ann.ann_graph_search_typed(c.x.to(DEV), g.to(DEV), 0, q.to(DEV), 10, 32)
+    torch.cuda.synchronize()
+    o_ids, o_sc, o_sc64, nd, ne = oracle.graph_search(c.x.numpy(), g.numpy(), 0, q.numpy(), 10, 32)
+    strict, tolerant, n = compare_topk(ids.cpu().numpy(), sc.cpu().numpy(), o_ids, o_sc64, c.x.numpy(), q.numpy())
+    f_ids, _, _ = oracle.flat_search(c.x.numpy(), q.numpy(), 10)
+    say(f"cfg0 graph strict={strict}/{n} recall@10 gpu={recall(ids.cpu().numpy(), f_ids):.3f} "
+        f"oracle={recall(o_ids, f_ids):.3f} n_dist={nd.mean():.0f} n_expand={ne.mean():.0f}")
+    assert strict >= n - 2
+
+
+# ------------------------------------------------------------------ flat: shapes, tails, dtypes
+
+@pytest.mark.parametrize("dtype", [torch.float16, torch.bfloat16, torch.float32])
+@pytest.mark.parametrize("N,d,B,k", [
+    (16 * 37 + 5, 768, 1, 3),       # ragged last tile
+    (1, 64, 2, 1),                  # single row
+    (7, 32, 3, 7),                  # k = N, fewer rows than a tile
+    (5000, 136, 17, 10),            # d not a multiple of 32, B not a multiple of 16
+    (20000, 768, 64, 3),            # four query groups in one pass
+    (9001, 256, 70, 16),            # two passes, k = K_MAX
+    (4099, 384, 130, 5),            # the paper's embedding width
+    (3000, 1024, 33, 4),
+])
+def test_flat_shapes(dtype, N, d, B, k):
+    say(f"flat shapes: dtype={dtype} N={N} d={d} B={B} k={k}")
+    c = synth.make_corpus(N, d, min(8, N), seed=N + d, dtype=dtype, zipf_a=None, sigma=0.3)
+    q = synth.make_queries(c, B)
+    ids, sc, (o_ids, o_sc, o_sc64) = flat_both(c.x, q, k)
+    strict, tolerant, n = compare_topk(ids, sc, o_ids, o_sc64, to_np(c.x), to_np(q), dtype=np_dtype_name(c.x))
+    assert strict >= n - max(2, n // 20), (strict, n)
+
+
+def test_flat_ties_go_to_lower_id():
+    c = synth.make_corpus(4000, 128, 4, seed=5, dtype=torch.float16, zipf_a=None, sigma=0.3)
+    x = c.x.clone()
+    for dst in (77, 1999, 3998, 16, 17):
+        x[dst] = x[1000]
+    q = x[1000:1001].clone()
+    ids, sc = ann.ann_flat_search_typed(x.to(DEV), q.to(DEV), 8)
+    torch.cuda.synchronize()
+    assert ids[0, :6].tolist() == [16, 17, 77, 1000, 1999, 3998]
+    assert float(sc[0, 0]) == float(sc[0, 5])
+    o_ids, _, _ = oracle.flat_search(x.numpy(), q.numpy(), 8)
+    assert ids.cpu().numpy().tolist() == o_ids.tolist()
+
+
+def test_flat_short_entry_point_and_reuse_of_outputs():
+    c = synth.make_corpus(3000, 64, 4, seed=9, dtype=torch.float16, zipf_a=None, sigma=0.3)
+    q = synth.make_queries(c, 5)
+    xd, qd = c.x.to(DEV), q.to(DEV)
+    ids = torch.full((5, 3), -7, dtype=torch.int32, device=DEV)
+    sc = torch.zeros(5, 3, device=DEV)
+    r_ids, r_sc = ann.ann_flat_search(xd, qd, 3, ids=ids, scores=sc)
+    assert r_ids is ids and r_sc is sc
+    t_ids, t_sc = ann.ann_flat_search_typed(xd, qd, 3)
+    torch.cuda.synchronize()
+    assert torch.equal(ids, t_ids) and torch.equal(sc, t_sc)
+    # a side stream works too
+    s = torch.cuda.Stream()
+    with torch.cuda.stream(s):
+        s_ids, s_sc = ann.ann_flat_search_typed(xd, qd, 3)
+    s.synchronize()
+    assert torch.equal(s_ids, t_ids)
+
+
+def test_flat_is_deterministic():
+    c = synth.make_corpus(50_000, 768, 32, seed=21, dtype=torch.float16)
+    q = synth.make_queries(c, 48)
+    xd, qd = c.x.to(DEV), q.to(DEV)
+    a = ann.ann_flat_search_typed(xd, qd, 3)
+    b = ann.ann_flat_search_typed(xd, qd, 3)
+    torch.cuda.synchronize()
+    assert torch.equal(a[0], b[0]) and torch.equal(a[1], b[1])
+
+
+def test_error_codes_on_device():
+    x = torch.zeros(100, 64, dtype=torch.float16, device=DEV)
+    q = torch.zeros(2, 64, dtype=torch.float16, device=DEV)
+    g = torch.zeros(100, 4, dtype=torch.int32, device=DEV)
+    with pytest.raises(ann.AnnError) as e:
+        ann.ann_flat_search_typed(x, q, 101)
+    assert e.value.code == -1
+    with pytest.raises(ann.AnnError) as e:
+        ann.ann_graph_search_typed(x, g, 0, q, 5, 4)
+    assert e.value.code == -1
+    with pytest.raises(ann.AnnError) as e:
+        ann.ann_graph_search(x, g, 0, q, 1, 4)
+    assert e.value.code == -3
+    ann.ann_register_corpus(x)
+    ann.ann_graph_search(x, g, 0, q, 1, 4)
+    torch.cuda.synchronize()
+    ann.ann_unregister_corpus(x)
+
+
+# ------------------------------------------------------------------ configuration 1 (flat, fp16, d = 768)
+
+@pytest.fixture(scope="module")
+def cfg1_scaled():
+    """Configuration 1 at a tenth of its size: the oracle can do every query."""
+    c = synth.workload_corpus(1, scale=0.1)
+    q = synth.make_queries(c, 512)
+    return c, q
+
+
+@pytest.mark.parametrize("B", [1, 16, 64, 256, 512])
+def test_cfg1_scaled_flat_all_batches(cfg1_scaled, B):
+    c, q = cfg1_scaled
+    q = q[:B].contiguous()
+    say(f"cfg1/10 flat: N={c.x.shape[0]} d=768 fp16 B={B} k=3")
+    ids, sc, (o_ids, o_sc, o_sc64) = flat_both(c.x, q, 3)
+    strict, tolerant, n = compare_topk(ids, sc, o_ids, o_sc64, c.x.numpy(), q.numpy())
+    say(f"cfg1/10 B={B}: strict={strict}/{n} tolerant={tolerant}")
+    assert strict >= n - max(1, n // 50)
+
+
+# ------------------------------------------------------------------ graph: shapes and special cases
+
+@pytest.mark.parametrize("dtype", [torch.float16, torch.bfloat16, torch.float32])
+def test_graph_ef_at_least_n_on_connected_graph_is_exact(dtype):
+    c = synth.make_corpus(600, 64, 6, seed=31, dtype=dtype, zipf_a=None, sigma=0.3)
+    q = synth.make_queries(c, 9)
+    g = synth.ring_union(synth.knn_graph(c.x, 6))
+    ids, sc = ann.ann_graph_search_typed(c.x.to(DEV), g.to(DEV), 17, q.to(DEV), 10, 600)
+    torch.cuda.synchronize()
+    f_ids, _, f64 = oracle.flat_search(to_np(c.x), to_np(q), 10, dtype=np_dtype_name(c.x))
+    compare_topk(ids.cpu().numpy(), sc.cpu().numpy(), f_ids, f64, to_np(c.x), to_np(q), dtype=np_dtype_name(c.x))
+
+
+@pytest.mark.parametrize("R,ef,k", [(1, 1, 1), (3, 2, 2), (32, 8, 3), (33, 64, 10), (70, 40, 7), (16, 300, 16)])
+def test_graph_shapes(R, ef, k):
+    say(f"graph shapes: R={R} ef={ef} k={k}")
+    N, d = 5000, 136
+    c = synth.make_corpus(N, d, 10, seed=R * 100 + ef, dtype=torch.float16, zipf_a=None, sigma=0.4)
+    q = synth.make_queries(c, 21)
+    gen = torch.Generator().manual_seed(R)
+    g = synth.knn_graph(c.x, max(1, R // 2))
+    rnd = torch.randint(-1, N + 3, (N, R - g.shape[1]), generator=gen, dtype=torch.int32)   # junk ids, some invalid
+    g = torch.cat([g, rnd], 1).contiguous()
+    g[5, : min(R, 2)] = 5                                                                    # self loops
+    ids, sc = ann.ann_graph_search_typed(c.x.to(DEV), g.to(DEV), 3, q.to(DEV), k, ef)
+    torch.cuda.synchronize()
+    o_ids, o_sc, o_sc64, nd, ne = oracle.graph_search(c.x.numpy(), g.numpy(), 3, q.numpy(), k, ef)
+    strict, tolerant, n = compare_topk(ids.cpu().numpy(), sc.cpu().numpy(), o_ids, o_sc64, c.x.numpy(), q.numpy())
+    assert strict >= n - 2, (strict, n)
+
+
+def test_graph_padding_when_few_nodes_are_reachable():
+    c = synth.make_corpus(200, 64, 4, seed=2, dtype=torch.float16, zipf_a=None, sigma=0.3)
+    q = synth.make_queries(c, 4)
+    g = torch.full((200, 4), -1, dtype=torch.int32)
+    g[9, 0] = 11                      # 9 -> 11, nothing else
+    ids, sc = ann.ann_graph_search_typed(c.x.to(DEV), g.to(DEV), 9, q.to(DEV), 5, 16)
+    torch.cuda.synchronize()
+    o_ids, o_sc, _, _, _ = oracle.graph_search(c.x.numpy(), g.numpy(), 9, q.numpy(), 5, 16)
+    assert ids.cpu().numpy().tolist() == o_ids.tolist()
+    assert sorted(ids[0, :2].tolist()) == [9, 11] and ids[0, 2:].tolist() == [-1, -1, -1]
+    assert torch.isneginf(sc[:, 2:]).all()
+
+
+def test_graph_is_deterministic():
+    c = synth.make_corpus(20_000, 768, 16, seed=41, dtype=torch.float16)
+    q = synth.make_queries(c, 32)
+    g = synth.knn_graph(c.x.to(DEV), 32).contiguous()
+    xd, qd = c.x.to(DEV), q.to(DEV)
+    a = ann.ann_graph_search_typed(xd, g, 0, qd, 3, 64)
+    b = ann.ann_graph_search_typed(xd, g, 0, qd, 3, 64)
+    torch.cuda.synchronize()
+    assert torch.equal(a[0], b[0]) and torch.equal(a[1], b[1])
+
+
+# ------------------------------------------------------------------ configuration 2 (graph, fp16, d = 768)
+
+@pytest.fixture(scope="module")
+def cfg2_scaled():
+    """Configuration 2 at a tenth of its size, graph built on the GPU by the generator module."""
+    c = synth.workload_corpus(2, scale=0.1, device=DEV)
+    g = synth.knn_graph_cluster_restricted(c, 32, 8)
+    entry = synth.mean_entry(c.x)
+    q = synth.make_queries(c, 64)
+    return c, g, entry, q
+
+
+@pytest.mark.parametrize("ef", [8, 16, 32, 64, 128, 256])
+def test_cfg2_scaled_graph(cfg2_scaled, ef):
+    c, g, entry, q = cfg2_scaled
+    say(f"cfg2/10 graph: N={c.x.shape[0]} R=32 entry={entry} ef={ef} B=64 k=3")
+    ids, sc = ann.ann_graph_search_typed(c.x, g, entry, q, 3, ef)
+    torch.cuda.synchronize()
+    xn, qn, gn = c.x.cpu().numpy(), q.cpu().numpy(), g.cpu().numpy()
+    o_ids, o_sc, o_sc64, nd, ne = oracle.graph_search(xn, gn, entry, qn, 3, ef)
+    strict, tolerant, n = compare_topk(ids.cpu().numpy(), sc.cpu().numpy(), o_ids, o_sc64, xn, qn)
+    f_ids, _, _ = oracle.flat_search(xn, qn, 3)
+    say(f"cfg2/10 ef={ef}: strict={strict}/{n} recall@3 gpu={recall(ids.cpu().numpy(), f_ids):.3f} "
+        f"oracle={recall(o_ids, f_ids):.3f} n_dist={nd.mean():.0f} n_expand={ne.mean():.0f}")
+    assert strict >= n - 2
