@@ -102,13 +102,32 @@ int kp_of(int k) { return k <= 4 ? 4 : 16; }
 // ---- flat: launch geometry ---------------------------------------------------------------
 struct FlatPlan {
     int kp, P, nqg_max;
+    int wide_ntg;            // > 0: matrix-core path with this many query-tile groups
+    int sample_tiles;        // > 0: a sampling pass over the first tiles supplies starting thresholds
+    int pstride;             // slabs per query in the partial array (P, plus one for the sample)
+    size_t sample_ofs, thr_ofs;   // byte offsets of the sample lists and thresholds in the workspace
     size_t ws_bytes;
 };
+
+constexpr int WIDE_MIN_B = 65;   // smallest batch sent to the matrix-core path
 
 FlatPlan flat_plan(int cus, int64_t N, int d, int dtype, int B, int k) {
     FlatPlan pl;
     pl.kp = kp_of(k);
-    if (dtype == ANN_F32) {
+    pl.wide_ntg = 0;
+    pl.sample_tiles = 0;
+    if (dtype != ANN_F32 && B >= WIDE_MIN_B && pl.kp == 4 && d % 32 == 0) {
+        const int nt = (B + wide_query_tile(B) - 1) / wide_query_tile(B);
+        pl.wide_ntg = nt < 8 ? nt : 8;
+        int P = cus / pl.wide_ntg;
+        const int64_t mtiles = (N + 255) / 256;
+        if (P > mtiles) P = (int)mtiles;
+        pl.P = P < 1 ? 1 : P;
+        pl.nqg_max = 4;
+        // enough tiles per slab: score one tile per slab first, exactly, and start the main
+        // pass from the sample's k-th best scores (few rows then pass the threshold test)
+        if (mtiles >= 8 * (int64_t)pl.P) pl.sample_tiles = pl.P;
+    } else if (dtype == ANN_F32) {
         const int64_t groups = (N + 7) / 8;
         int64_t P = (groups + 3) / 4;
         const int64_t cap = (int64_t)cus * 4;
@@ -129,7 +148,10 @@ FlatPlan flat_plan(int cus, int64_t N, int d, int dtype, int B, int k) {
     }
     if (pl.P > P_MAX) pl.P = P_MAX;
     if (pl.P < 1) pl.P = 1;
-    pl.ws_bytes = (size_t)B * pl.P * pl.kp * sizeof(Cand);
+    pl.pstride = pl.P + (pl.sample_tiles > 0 ? 1 : 0);
+    pl.sample_ofs = (size_t)B * pl.pstride * pl.kp * sizeof(Cand);
+    pl.thr_ofs = pl.sample_ofs + (size_t)B * pl.sample_tiles * pl.kp * sizeof(Cand);
+    pl.ws_bytes = pl.thr_ofs + (pl.sample_tiles > 0 ? (size_t)B * sizeof(float) : 0);
     return pl;
 }
 
@@ -139,6 +161,21 @@ int flat_search_run(const FlatPlan &pl, const void *X, int64_t N, int d, int dty
         hipError_t e = launch_flat_f32(pl.kp, static_cast<const float *>(X), N, d, static_cast<const float *>(Q), B,
                                        partial, pl.P, stream);
         if (int rc = check_launch("flat_f32_kernel", e)) return rc;
+    } else if (pl.wide_ntg > 0) {
+        const float *thr0 = nullptr;
+        if (pl.sample_tiles > 0) {
+            Cand *sample = reinterpret_cast<Cand *>(reinterpret_cast<char *>(partial) + pl.sample_ofs);
+            float *thr = reinterpret_cast<float *>(reinterpret_cast<char *>(partial) + pl.thr_ofs);
+            hipError_t e = launch_flat_wide(dtype, true, X, (int64_t)pl.sample_tiles * 256, d, Q, B, sample,
+                                            pl.sample_tiles, pl.wide_ntg, 0, nullptr, pl.sample_tiles, 0, stream);
+            if (int rc = check_launch("flat_wide_kernel (sample)", e)) return rc;
+            e = launch_flat_sample_merge(pl.kp, sample, pl.sample_tiles, B, partial, pl.pstride, pl.P, thr, stream);
+            if (int rc = check_launch("flat_sample_merge_kernel", e)) return rc;
+            thr0 = thr;
+        }
+        hipError_t e = launch_flat_wide(dtype, false, X, N, d, Q, B, partial, pl.P, pl.wide_ntg, pl.sample_tiles,
+                                        thr0, pl.pstride, 0, stream);
+        if (int rc = check_launch("flat_wide_kernel", e)) return rc;
     } else {
         for (int q0 = 0; q0 < B; q0 += 16 * pl.nqg_max) {
             const int left = B - q0;
@@ -149,7 +186,7 @@ int flat_search_run(const FlatPlan &pl, const void *X, int64_t N, int d, int dty
             if (int rc = check_launch("flat_stream_kernel", e)) return rc;
         }
     }
-    return check_launch("flat_merge_kernel", launch_flat_merge(pl.kp, partial, pl.P, B, k, ids, scores, stream));
+    return check_launch("flat_merge_kernel", launch_flat_merge(pl.kp, partial, pl.pstride, B, k, ids, scores, stream));
 }
 
 }  // namespace

@@ -240,4 +240,28 @@ __global__ __launch_bounds__(256) void flat_merge_kernel(const Cand *__restrict_
     }
 }
 
+// One wavefront per query: the KP best of Ps sampled lists, kept as one more slab of the
+// main partial array; their KP-th best score becomes the query's starting threshold.
+template <int KP>
+__global__ __launch_bounds__(64) void flat_sample_merge_kernel(const Cand *__restrict__ src, int Ps,
+                                                               Cand *__restrict__ dst, int pstride, int pslot,
+                                                               float *__restrict__ thr) {
+    const int q = blockIdx.x, lane = threadIdx.x;
+    const Cand *in = src + (size_t)q * Ps * KP;
+    TopList<KP> best;
+    best.init();
+    for (int e = lane; e < Ps * KP; e += 64) {
+        const Cand c = in[e];
+        if (best.admits(c.s, c.id)) best.insert(c.s, c.id);
+    }
+#pragma unroll
+    for (int m = 1; m < 64; m <<= 1) best.merge_xor(m);
+    if (lane == 0) {
+        Cand *out = dst + ((size_t)q * pstride + pslot) * KP;
+#pragma unroll
+        for (int j = 0; j < KP; ++j) out[j] = Cand{best.s[j], best.id[j]};
+        thr[q] = best.id[KP - 1] != EMPTY_ID ? best.s[KP - 1] : -INFINITY;
+    }
+}
+
 }  // namespace ann

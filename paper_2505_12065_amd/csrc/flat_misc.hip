@@ -20,7 +20,7 @@ namespace {
 template <int KP>
 hipError_t launch_f32(const float *X, int64_t N, int d, const float *Q, int B, Cand *partial, int P,
                       hipStream_t stream) {
-    static bool big = false;
+    static size_t big = 0;
     const size_t lds = f32_lds_bytes(d, 4, KP);
     if (hipError_t e = allow_big_lds(reinterpret_cast<const void *>(&flat_f32_kernel<KP>), lds, &big)) return e;
     hipLaunchKernelGGL((flat_f32_kernel<KP>), dim3(P, (B + 7) / 8), dim3(256), lds, stream, X, N, d, Q, B, partial);
@@ -39,6 +39,15 @@ hipError_t launch_flat_merge(int kp, const Cand *partial, int P, int B, int k, i
         hipLaunchKernelGGL((flat_merge_kernel<4>), dim3(B), dim3(256), 0, stream, partial, P, k, ids, scores);
     else
         hipLaunchKernelGGL((flat_merge_kernel<16>), dim3(B), dim3(256), 0, stream, partial, P, k, ids, scores);
+    return hipGetLastError();
+}
+
+hipError_t launch_flat_sample_merge(int kp, const Cand *src, int Ps, int B, Cand *dst, int pstride, int pslot,
+                                    float *thr, hipStream_t stream) {
+    if (kp == 4)
+        hipLaunchKernelGGL((flat_sample_merge_kernel<4>), dim3(B), dim3(64), 0, stream, src, Ps, dst, pstride, pslot, thr);
+    else
+        hipLaunchKernelGGL((flat_sample_merge_kernel<16>), dim3(B), dim3(64), 0, stream, src, Ps, dst, pstride, pslot, thr);
     return hipGetLastError();
 }
 

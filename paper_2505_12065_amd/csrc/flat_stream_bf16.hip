@@ -8,7 +8,7 @@ namespace {
 template <int NQG, int KP>
 hipError_t launch(const void *X, int64_t N, int d, const void *Q, int B, int q0, Cand *partial, int P,
                   hipStream_t stream) {
-    static bool big[2] = {false, false};
+    static size_t big[2] = {0, 0};
     const int steps = (d + 31) / 32;
     const size_t lds = stream_lds_bytes(NQG, steps, STREAM_THREADS / WAVE, KP);
     if ((d % 32) == 0) {

@@ -30,7 +30,7 @@ namespace {
 template <class T>
 hipError_t launch(const void *X, int64_t N, int d, const int32_t *graph, int R, int entry, const void *Q, int B,
                   int k, int ef, int32_t *ids, float *scores, const GraphLds &L, hipStream_t stream) {
-    static bool big = false;
+    static size_t big = 0;
     if (hipError_t e = allow_big_lds(reinterpret_cast<const void *>(&graph_search_kernel<T>), L.total, &big)) return e;
     hipLaunchKernelGGL((graph_search_kernel<T>), dim3(B), dim3(GRAPH_THREADS), L.total, stream, X, N, d, graph, R,
                        entry, Q, k, ef, ids, scores, L);

@@ -12,11 +12,12 @@ namespace ann {
 constexpr size_t LDS_MAX = 160 * 1024;   // LDS of one gfx950 compute unit
 constexpr int STREAM_THREADS = 512;
 
-// A kernel that needs more than 64 KB of dynamic LDS has to be told so once.
-inline hipError_t allow_big_lds(const void *kernel, size_t bytes, bool *done) {
-    if (bytes <= 64 * 1024 || *done) return hipSuccess;
-    hipError_t e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)LDS_MAX);
-    if (e == hipSuccess) *done = true;
+// A kernel that needs more than 64 KB of dynamic LDS has to be told so; `granted` holds
+// the largest size already granted to that kernel.
+inline hipError_t allow_big_lds(const void *kernel, size_t bytes, size_t *granted) {
+    if (bytes <= 64 * 1024 || bytes <= *granted) return hipSuccess;
+    hipError_t e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+    if (e == hipSuccess) *granted = bytes;
     return e;
 }
 
@@ -28,6 +29,19 @@ hipError_t launch_flat_stream_f16(int nqg, int kp, const void *X, int64_t N, int
                                   Cand *partial, int P, hipStream_t stream);
 hipError_t launch_flat_stream_bf16(int nqg, int kp, const void *X, int64_t N, int d, const void *Q, int B, int q0,
                                    Cand *partial, int P, hipStream_t stream);
+// Large batches on the matrix cores (16-bit corpora, d % 32 == 0, lists of 4).
+// Query tile is wide_query_tile(B) queries; gridDim = P slabs x NTG query-tile groups;
+// rows [256 tile_begin, N) are scanned; results go to partial[(q pstride + pslot0 + slab) 4 ..).
+// select = threshold-free epilogue (sampling pass); thr_init = optional per-query lower
+// bounds of the final 4th-best score.
+int wide_query_tile(int B);
+hipError_t launch_flat_wide(int dtype, bool select, const void *X, int64_t N, int d, const void *Q, int B,
+                            Cand *partial, int P, int NTG, int64_t tile_begin, const float *thr_init, int pstride,
+                            int pslot0, hipStream_t stream);
+// Per query: merge Ps sampled lists (src[(q Ps + s) kp ..)) into dst[(q pstride + pslot) kp ..)
+// and write the kp-th best score of the merged list (-inf if it has fewer entries) to thr[q].
+hipError_t launch_flat_sample_merge(int kp, const Cand *src, int Ps, int B, Cand *dst, int pstride, int pslot,
+                                    float *thr, hipStream_t stream);
 hipError_t launch_flat_f32(int kp, const float *X, int64_t N, int d, const float *Q, int B, Cand *partial, int P,
                            hipStream_t stream);
 hipError_t launch_flat_merge(int kp, const Cand *partial, int P, int B, int k, int32_t *ids, float *scores,

@@ -74,6 +74,12 @@ def test_cfg0_graph_fp32(cfg0):
     (9001, 256, 70, 16),            # two passes, k = K_MAX
     (4099, 384, 130, 5),            # the paper's embedding width
     (3000, 1024, 33, 4),
+    (5000, 768, 100, 3),            # matrix-core path, 128-query tile, ragged corpus tile
+    (777, 64, 300, 4),              # matrix-core path, two 256-query tiles, second one ragged
+    (70001, 256, 129, 1),           # matrix-core path, many tiles per slab
+    (100, 32, 2100, 2),             # more query tiles than tile groups; corpus smaller than a tile
+    (600_001, 64, 200, 3),          # matrix-core path with the sampling pass, one query tile
+    (300_000, 32, 600, 4),          # ... three query tiles
 ])
 def test_flat_shapes(dtype, N, d, B, k):
     say(f"flat shapes: dtype={dtype} N={N} d={d} B={B} k={k}")
