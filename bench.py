@@ -1,0 +1,218 @@
+#!/usr/bin/env python3
+"""Benchmark of the retrieval hot path on one MI355X.
+
+One step = one pass of the whole hot path over one batch of synthetic queries on the
+1M x 768 fp16 clustered corpus (configurations 1 and 2 of the workload table):
+
+    flat exact search, B = 16   (streaming path, HBM bound)
+    flat exact search, B = 512  (matrix-core path, MFMA bound)
+    graph beam search, B = 512, ef = EF_STEP on the cluster-restricted 32-NN graph
+
+All inputs are resident in HBM before the timed region.  `value` is queries served per
+second over the step (16 + 512 + 512 queries per step).  The CPU oracle is timed in the
+same run on the host cores as a reported baseline, on a bounded query sample.
+
+Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+METRIC = "queries/sec at recall@3≥0.95 (graph) and flat-scan HBM GB/s / MFMA % of peak"
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
+MFMA_F16_PEAK_TFLOPS = 2500.0  # MI355X dense fp16 MFMA
+K = 3
+EF_STEP = 64
+B_SMALL, B_LARGE = 16, 512
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--no-sweep", action="store_true", help="skip the untimed per-B / per-ef report")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--calibrate", action="store_true",
+                    help="also run one plain device copy of the corpus (known size) before the steps, so that a "
+                         "counter profile of this command contains a reference kernel to scale byte counters by")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build is single-GPU only (no collectives, no sharding); run with --gpus 1",
+              file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    import paper_2505_12065_amd as ann
+    from paper_2505_12065_amd import synth
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+
+    # ---- inputs (untimed): corpus, queries, graph, entry; all device resident -------------
+    corpus = synth.workload_corpus(1, device=dev)
+    x = corpus.x
+    N, d = x.shape
+    q_all = synth.make_queries(corpus, B_LARGE)
+    q_small = q_all[:B_SMALL].contiguous()
+    graph = synth.knn_graph_cluster_restricted(corpus, 32, 8)
+    R = graph.shape[1]
+    entry = synth.mean_entry(x)
+    out = {b: (torch.empty(b, K, dtype=torch.int32, device=dev), torch.empty(b, K, device=dev))
+           for b in (B_SMALL, B_LARGE)}
+    g_ids, g_sc = torch.empty(B_LARGE, K, dtype=torch.int32, device=dev), torch.empty(B_LARGE, K, device=dev)
+
+    def leg_flat_small():
+        ann.ann_flat_search_typed(x, q_small, K, ids=out[B_SMALL][0], scores=out[B_SMALL][1])
+
+    def leg_flat_large():
+        ann.ann_flat_search_typed(x, q_all, K, ids=out[B_LARGE][0], scores=out[B_LARGE][1])
+
+    def leg_graph():
+        ann.ann_graph_search_typed(x, graph, entry, q_all, K, EF_STEP, ids=g_ids, scores=g_sc)
+
+    legs = (("flat_b16", leg_flat_small), ("flat_b512", leg_flat_large), ("graph_b512", leg_graph))
+
+    def step(events=None):
+        for i, (_, fn) in enumerate(legs):
+            if events is not None:
+                events[i][0].record()
+            fn()
+            if events is not None:
+                events[i][1].record()
+
+    if args.calibrate:
+        torch.empty_like(x).copy_(x)
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+
+    # ---- timed region: exactly `steps` steps, bracketed by synchronize ---------------------
+    ev = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in legs]
+          for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for s in range(args.steps):
+        step(ev[s])
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_per_step = wall * 1e3 / args.steps
+    leg_ms = [sum(ev[s][i][0].elapsed_time(ev[s][i][1]) for s in range(args.steps)) / args.steps
+              for i in range(len(legs))]
+    q_per_step = B_SMALL + B_LARGE + B_LARGE
+    value = q_per_step / (ms_per_step * 1e-3)
+
+    # ---- oracle side: counters for the graph roofline, parity spot check, CPU baseline ------
+    import oracle
+    xh = x.cpu().numpy()
+    qh = q_all.cpu().numpy()
+    gh = graph.cpu().numpy()
+    o_g = oracle.graph_search(xh, gh, entry, qh, K, EF_STEP)
+    n_dist, n_expand = o_g[3], o_g[4]
+    graph_bytes = float((n_dist * d * 2 + n_expand * R * 4).sum())      # algorithmic bytes of one graph leg
+    gpu_g = g_ids.cpu().numpy()
+    graph_id_match = float((gpu_g == o_g[0]).all(axis=1).mean())
+
+    flat_bytes = float(N) * d * 2
+    flat_flops = 2.0 * B_LARGE * N * d
+    rooflines = {
+        "flat_b16": {"bound": "hbm", "achieved": flat_bytes / leg_ms[0] / 1e6, "peak": HBM_PEAK_GBS, "unit": "GB/s"},
+        "flat_b512": {"bound": "mfma", "achieved": flat_flops / leg_ms[1] / 1e9, "peak": MFMA_F16_PEAK_TFLOPS,
+                      "unit": "TFLOP/s"},
+        "graph_b512": {"bound": "hbm", "achieved": graph_bytes / leg_ms[2] / 1e6, "peak": HBM_PEAK_GBS, "unit": "GB/s"},
+    }
+    for r in rooflines.values():
+        r["frac"] = r["achieved"] / r["peak"]
+        r["traffic"] = None
+    dominant = max(range(len(legs)), key=lambda i: leg_ms[i])
+    roofline = dict(rooflines[legs[dominant][0]])
+    roofline["kernel"] = {"flat_b16": "flat_stream_kernel", "flat_b512": "flat_wide_kernel",
+                          "graph_b512": "graph_search_kernel"}[legs[dominant][0]]
+    roofline["leg"] = legs[dominant][0]
+    roofline["leg_ms"] = leg_ms[dominant]
+
+    cpu_baseline = None
+    if not args.no_cpu:
+        n_flat = 16                                  # bounded sample of the flat legs
+        t = time.perf_counter()
+        o_f = oracle.flat_search(xh, qh[:n_flat], K)
+        t_flat = (time.perf_counter() - t) / n_flat
+        t = time.perf_counter()
+        oracle.graph_search(xh, gh, entry, qh, K, EF_STEP)
+        t_graph = (time.perf_counter() - t) / B_LARGE
+        cpu_step = t_flat * (B_SMALL + B_LARGE) + t_graph * B_LARGE
+        flat_match = float((out[B_LARGE][0][:n_flat].cpu().numpy() == o_f[0]).all(axis=1).mean())
+        cpu_baseline = {
+            "value": q_per_step / cpu_step, "unit": "queries/s", "cores": oracle.threads(), "kind": "oracle",
+            "sample": f"flat oracle timed on {n_flat} of the {B_SMALL + B_LARGE} flat queries "
+                      f"({t_flat * 1e3:.0f} ms/query), graph oracle on all {B_LARGE} queries at ef={EF_STEP} "
+                      f"({t_graph * 1e3:.2f} ms/query); step time extrapolated to the same 16+512+512 queries",
+            "flat_ids_equal_gpu_on_sample": flat_match,
+        }
+
+    # ---- untimed report: per-B flat rates, per-ef graph rates and recall ---------------------
+    sweep = None
+    if not args.no_sweep:
+        def timed(fn, n=10, w=2):
+            for _ in range(w):
+                fn()
+            torch.cuda.synchronize()
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            for _ in range(n):
+                fn()
+            b.record()
+            torch.cuda.synchronize()
+            return a.elapsed_time(b) / n
+
+        sweep = {"flat": [], "graph": []}
+        for B in (1, 16, 64, 256, 512):
+            qb = q_all[:B].contiguous()
+            ms = timed(lambda: ann.ann_flat_search_typed(x, qb, K))
+            sweep["flat"].append({"B": B, "ms": ms, "qps": B / ms * 1e3, "hbm_GBs": flat_bytes / ms / 1e6,
+                                  "hbm_frac": flat_bytes / ms / 1e6 / HBM_PEAK_GBS,
+                                  "mfma_TFLOPs": 2.0 * B * N * d / ms / 1e9,
+                                  "mfma_frac": 2.0 * B * N * d / ms / 1e9 / MFMA_F16_PEAK_TFLOPS})
+        exact = out[B_LARGE][0].cpu().numpy()
+        for ef in (8, 16, 32, 64, 128, 256):
+            for B in (1, 64, 512):
+                qb = q_all[:B].contiguous()
+                ms = timed(lambda: ann.ann_graph_search_typed(x, graph, entry, qb, K, ef), n=5, w=1)
+                ids, _ = ann.ann_graph_search_typed(x, graph, entry, qb, K, ef)
+                got = ids.cpu().numpy()
+                rec = float(np.mean([len(set(got[b].tolist()) & set(exact[b].tolist())) / K for b in range(B)]))
+                sweep["graph"].append({"ef": ef, "B": B, "ms": ms, "qps": B / ms * 1e3, "recall_at_3": rec})
+
+    exact = out[B_LARGE][0].cpu().numpy()
+    recall_step = float(np.mean([len(set(gpu_g[b].tolist()) & set(exact[b].tolist())) / K for b in range(B_LARGE)]))
+    result = {
+        "metric": METRIC, "value": value, "unit": "queries/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f16", "data": "synthetic",
+        "config": {"workload": "cfg1 flat + cfg2 graph: N=1,000,000 d=768 fp16 storage / fp32 accumulate, "
+                               "1024-cluster Zipf(1.1) mixture, seed 1; step = flat B=16 + flat B=512 + graph B=512",
+                   "N": N, "d": d, "k": K, "R": R, "ef": EF_STEP, "entry": int(entry),
+                   "queries_per_step": q_per_step},
+        "legs": {legs[i][0]: {"ms": leg_ms[i]} for i in range(len(legs))},
+        "graph_recall_at_3": recall_step, "graph_recall_target_met": recall_step >= 0.95,
+        "graph_ids_equal_oracle": graph_id_match,
+        "roofline": roofline, "rooflines": rooflines, "cpu_baseline": cpu_baseline, "sweep": sweep,
+    }
+    print(json.dumps(result))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())
