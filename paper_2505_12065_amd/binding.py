@@ -11,7 +11,7 @@ from typing import Optional, Tuple
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libann.so")
+LIB_PATH = os.environ.get("ANN_LIBRARY_PATH", os.path.join(_HERE, "libann.so"))
 
 ANN_OK, ANN_ERR_INVALID, ANN_ERR_ALIGNMENT, ANN_ERR_UNKNOWN_CORPUS, ANN_ERR_LAUNCH, ANN_ERR_NOMEM = 0, -1, -2, -3, -4, -5
 ANN_F16, ANN_BF16, ANN_F32 = 0, 1, 2

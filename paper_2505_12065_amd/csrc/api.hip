@@ -140,10 +140,14 @@ FlatPlan flat_plan(int cus, int64_t N, int d, int dtype, int B, int k) {
         const int nqg = B > 16 * pl.nqg_max ? pl.nqg_max : (B + 15) / 16;
         const size_t lds = stream_lds_bytes(nqg, steps, STREAM_THREADS / WAVE, pl.kp);
         int occ = (int)(LDS_MAX / lds);
-        occ = occ < 1 ? 1 : (occ > 2 ? 2 : occ);
+        occ = occ < 1 ? 1 : (occ > 2 ? 2 : occ);     // measured: more resident workgroups do not help
         const int64_t tiles = (N + 15) / 16;
-        int64_t P = (tiles + STREAM_THREADS / WAVE - 1) / (STREAM_THREADS / WAVE);
+        const int wpb = STREAM_THREADS / WAVE;
         const int64_t cap = (int64_t)cus * occ;
+        // every wave takes whole 16-row tiles in rounds; size the grid so that the last round
+        // is as full as the others instead of leaving most of the chip idle
+        const int64_t rounds = (tiles + cap * wpb - 1) / (cap * wpb);
+        int64_t P = (tiles + rounds * wpb - 1) / (rounds * wpb);
         pl.P = (int)(P < cap ? P : cap);
     }
     if (pl.P > P_MAX) pl.P = P_MAX;

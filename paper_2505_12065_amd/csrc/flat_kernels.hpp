@@ -17,6 +17,8 @@
 
 namespace ann {
 
+constexpr int STREAM_UNROLL = 8;   // 16-byte loads a lane keeps in flight (6..24 measured alike)
+
 // Corpus rows are the M side of a 16x16x32 MFMA, queries the N side: a lane ends
 // up with one query (lane % 16) and four rows (4*(lane/16) + i) per tile of 16 rows.
 //   X        [N, d] 16-bit           Q  [B, d] 16-bit (queries q0 .. q0+NQG*16 are used)
@@ -58,15 +60,15 @@ __global__ __launch_bounds__(512) void flat_stream_kernel(const void *__restrict
         for (int g = 0; g < NQG; ++g) acc[g] = f4{0.f, 0.f, 0.f, 0.f};
 
         int s = 0;
-        for (; s + 8 <= steps; s += 8) {
-            u4 a[8];
+        for (; s + STREAM_UNROLL <= steps; s += STREAM_UNROLL) {
+            u4 a[STREAM_UNROLL];
 #pragma unroll
-            for (int u = 0; u < 8; ++u) {
+            for (int u = 0; u < STREAM_UNROLL; ++u) {
                 if (DFULL || (s + u) * 32 + kofs < d) a[u] = load_chunk(rp + (size_t)(s + u) * 64);
                 else a[u] = zero_chunk();
             }
 #pragma unroll
-            for (int u = 0; u < 8; ++u)
+            for (int u = 0; u < STREAM_UNROLL; ++u)
 #pragma unroll
                 for (int g = 0; g < NQG; ++g)
                     acc[g] = mfma16<T>(a[u], qf[(g * steps + s + u) * WAVE + lane], acc[g]);

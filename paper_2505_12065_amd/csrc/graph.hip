@@ -22,19 +22,29 @@ GraphLds graph_lds_layout(int d, int elem_bytes, int R, int ef) {
     L.cpos = off; off = up(off + 4u * L.rp);
     L.cache = off; off = up(off + (4u << bits));
     L.ctl = off; off = up(off + 16u);
+    L.adj = off; off = up(off + 2u * 4u * RMAX_LDS);
+    L.um = off; off = up(off + 8u * ((uint32_t)ef + 63u) / 64u + 8u);
     L.total = off;
     return L;
 }
 
 namespace {
+template <class T, int RPT>
+hipError_t launch_rp(const void *X, int64_t N, int d, const int32_t *graph, int R, int entry, const void *Q, int B,
+                     int k, int ef, int32_t *ids, float *scores, const GraphLds &L, hipStream_t stream) {
+    static size_t big = 0;
+    if (hipError_t e = allow_big_lds(reinterpret_cast<const void *>(&graph_search_kernel<T, RPT>), L.total, &big))
+        return e;
+    hipLaunchKernelGGL((graph_search_kernel<T, RPT>), dim3(B), dim3(GRAPH_THREADS), L.total, stream, X, N, d, graph, R,
+                       entry, Q, k, ef, ids, scores, L);
+    return hipGetLastError();
+}
+
 template <class T>
 hipError_t launch(const void *X, int64_t N, int d, const int32_t *graph, int R, int entry, const void *Q, int B,
                   int k, int ef, int32_t *ids, float *scores, const GraphLds &L, hipStream_t stream) {
-    static size_t big = 0;
-    if (hipError_t e = allow_big_lds(reinterpret_cast<const void *>(&graph_search_kernel<T>), L.total, &big)) return e;
-    hipLaunchKernelGGL((graph_search_kernel<T>), dim3(B), dim3(GRAPH_THREADS), L.total, stream, X, N, d, graph, R,
-                       entry, Q, k, ef, ids, scores, L);
-    return hipGetLastError();
+    return L.rp == 32 ? launch_rp<T, 32>(X, N, d, graph, R, entry, Q, B, k, ef, ids, scores, L, stream)
+                      : launch_rp<T, 0>(X, N, d, graph, R, entry, Q, B, k, ef, ids, scores, L, stream);
 }
 }  // namespace
 

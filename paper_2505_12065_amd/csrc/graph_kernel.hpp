@@ -26,6 +26,7 @@ constexpr int GRAPH_WAVES = GRAPH_THREADS / WAVE;
 constexpr int LANES_PER_ROW = 8;
 constexpr int ROWS_PER_PASS = GRAPH_THREADS / LANES_PER_ROW;   // 32 neighbours scored at once
 constexpr uint32_t EXPANDED = 0x80000000u;
+constexpr int RMAX_LDS = 256;                                  // row stride of the read-ahead buffers (>= R)
 
 // number of entries of the ordered list (s[0..len), id[0..len)) that precede (v, vid)
 __device__ __forceinline__ int list_lower_bound(const float *s, const uint32_t *id, int len, float v, int vid) {
@@ -38,7 +39,10 @@ __device__ __forceinline__ int list_lower_bound(const float *s, const uint32_t *
     return lo;
 }
 
-template <class T>
+// RPT: number of graph slots rounded up to 32 when it is known at compile time (32 for
+// R <= 32: the short loops over the scored neighbours are then fully unrolled and their
+// LDS reads issued together), 0 = taken from the layout at run time.
+template <class T, int RPT>
 __global__ __launch_bounds__(GRAPH_THREADS) void graph_search_kernel(
     const void *__restrict__ X, int64_t N, int d, const int32_t *__restrict__ graph, int R, int entry,
     const void *__restrict__ Q, int k, int ef, int32_t *__restrict__ ids, float *__restrict__ scores,
@@ -51,12 +55,14 @@ __global__ __launch_bounds__(GRAPH_THREADS) void graph_search_kernel(
     int *ci = reinterpret_cast<int *>(smem + L.ci);
     int *cpos = reinterpret_cast<int *>(smem + L.cpos);
     int *cache = reinterpret_cast<int *>(smem + L.cache);
-    int *ctl = reinterpret_cast<int *>(smem + L.ctl);     // [0], [1]: first unexpanded index, by parity
+    int *adj = reinterpret_cast<int *>(smem + L.adj);     // [2][RMAX_LDS] adjacency rows read ahead
+    int *adj_id = reinterpret_cast<int *>(smem + L.ctl);  // [2] whose rows they are
+    uint64_t *um = reinterpret_cast<uint64_t *>(smem + L.um);   // [ef/64] "unexpanded" bit masks
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int b = blockIdx.x;
     const int nch = d * T::bytes / 16;                    // 16-byte chunks per row
-    const int RP = (int)L.rp;
+    const int RP = RPT ? RPT : (int)L.rp;
     const uint32_t cache_shift = 32u - L.cache_bits;
 
     for (int c = tid; c < nch; c += GRAPH_THREADS)
@@ -67,22 +73,25 @@ __global__ __launch_bounds__(GRAPH_THREADS) void graph_search_kernel(
     const int sub = lane & (LANES_PER_ROW - 1);           // lane's position inside its row group
     const int grp = wave * (WAVE / LANES_PER_ROW) + lane / LANES_PER_ROW;   // 0..31
 
-    // <q, x_v> by the 8 lanes of a row group; every lane of the group gets the sum
+    // <q, x_v> by the 8 lanes of a row group; every lane of the group gets the sum.  All
+    // of a lane's 16-byte loads of the row are issued before the first one is used, so a
+    // whole expansion costs one memory latency, not one per batch of loads.
     auto score_row = [&](int v) -> float {
         const char *rp = static_cast<const char *>(X) + (size_t)v * nch * 16;
         float acc = 0.f;
-        int c = sub;
-        for (; c + 3 * LANES_PER_ROW < nch; c += 4 * LANES_PER_ROW) {
-            const u4 x0 = load_chunk(rp + (size_t)c * 16);
-            const u4 x1 = load_chunk(rp + (size_t)(c + LANES_PER_ROW) * 16);
-            const u4 x2 = load_chunk(rp + (size_t)(c + 2 * LANES_PER_ROW) * 16);
-            const u4 x3 = load_chunk(rp + (size_t)(c + 3 * LANES_PER_ROW) * 16);
-            acc = dot_chunk<T>(x0, qs[c], acc);
-            acc = dot_chunk<T>(x1, qs[c + LANES_PER_ROW], acc);
-            acc = dot_chunk<T>(x2, qs[c + 2 * LANES_PER_ROW], acc);
-            acc = dot_chunk<T>(x3, qs[c + 3 * LANES_PER_ROW], acc);
+        for (int c0 = sub; c0 < nch; c0 += 16 * LANES_PER_ROW) {
+            u4 x[16];
+#pragma unroll
+            for (int u = 0; u < 16; ++u) {
+                const int c = c0 + u * LANES_PER_ROW;
+                x[u] = c < nch ? load_chunk(rp + (size_t)c * 16) : zero_chunk();
+            }
+#pragma unroll
+            for (int u = 0; u < 16; ++u) {
+                const int c = c0 + u * LANES_PER_ROW;
+                if (c < nch) acc = dot_chunk<T>(x[u], qs[c], acc);
+            }
         }
-        for (; c < nch; c += LANES_PER_ROW) acc = dot_chunk<T>(load_chunk(rp + (size_t)c * 16), qs[c], acc);
         acc += __shfl_xor(acc, 1);
         acc += __shfl_xor(acc, 2);
         acc += __shfl_xor(acc, 4);
@@ -96,24 +105,36 @@ __global__ __launch_bounds__(GRAPH_THREADS) void graph_search_kernel(
             ls[0][0] = s;
             li[0][0] = (uint32_t)entry;
             cache[((uint32_t)entry * 2654435761u) >> cache_shift] = entry;
-            ctl[0] = 0;
         }
     }
     __syncthreads();
 
-    int cur = 0, len = 1, par = 0;
+    // adj[s] may hold the adjacency row of node adj_id[s], read ahead of time (see below)
+    if (tid < 2) adj_id[tid] = -1;
+    __syncthreads();
+
+    int cur = 0, len = 1;
+    int p = 0, p2 = -1;                                   // best and second-best unexpanded entries
     for (;;) {
-        const int p = ctl[par];
-        if (p == INT_MAX) break;                          // nothing left to expand: natural stop
+        if (p < 0) break;                                 // nothing left to expand: natural stop
         const int node = (int)(li[cur][p] & ~EXPANDED);
-        __syncthreads();                                  // all have read p and node
-        if (tid == 0) { li[cur][p] |= EXPANDED; ctl[par ^ 1] = INT_MAX; }
+        const int node2 = p2 >= 0 ? (int)(li[cur][p2] & ~EXPANDED) : -1;
+        const int have = adj_id[0] == node ? 0 : (adj_id[1] == node ? 1 : -1);
+        const bool have2 = node2 < 0 || adj_id[0] == node2 || adj_id[1] == node2;
+        __syncthreads();                                  // all have read the list and adj_id
+        if (tid == 0) li[cur][p] |= EXPANDED;
+
+        // Read-ahead: the second-best unexpanded entry is the most likely next expansion, so
+        // its adjacency row is fetched now, under the gathers of this expansion.  It only
+        // saves a dependent memory round trip later; nothing is decided from it here.
+        int ahead = -1;
+        if (!have2 && tid < R) ahead = graph[(size_t)node2 * R + tid];
 
         // score the unseen neighbours of `node`, 32 graph slots per pass
         for (int base = 0; base < RP; base += ROWS_PER_PASS) {
             const int slot = base + grp;
             int v = -1;
-            if (slot < R) v = graph[(size_t)node * R + slot];
+            if (slot < R) v = have >= 0 ? adj[have * RMAX_LDS + slot] : graph[(size_t)node * R + slot];
             int fresh = 0;
             if ((unsigned)v < (unsigned)N) {
                 if (sub == 0) {
@@ -126,6 +147,11 @@ __global__ __launch_bounds__(GRAPH_THREADS) void graph_search_kernel(
             if (fresh) s = score_row(v);
             if (sub == 0) { cs[slot] = s; ci[slot] = fresh ? v : -1; }
         }
+        if (!have2) {                                     // keep the row of `node` if it is in a slot
+            const int into = have == 0 ? 1 : 0;
+            if (tid < R) adj[into * RMAX_LDS + tid] = ahead;
+            if (tid == 0) adj_id[into] = node2;
+        }
         __syncthreads();
 
         // where would each scored neighbour go?  cpos = entries of the list that precede it,
@@ -136,7 +162,8 @@ __global__ __launch_bounds__(GRAPH_THREADS) void graph_search_kernel(
             if (v >= 0) {
                 const float s = cs[i];
                 bool dup = false;
-                for (int j = 0; j < i; ++j) dup |= (ci[j] == v);
+#pragma unroll
+                for (int j = 0; j < (RPT ? RPT : i); ++j) dup |= (j < i && ci[j] == v);
                 if (!dup && s == s) {                      // a NaN score is never listed
                     pos = list_lower_bound(ls[cur], li[cur], len, s, v);
                     if (pos >= ef || (pos < len && (int)(li[cur][pos] & ~EXPANDED) == v)) pos = -1;
@@ -150,6 +177,7 @@ __global__ __launch_bounds__(GRAPH_THREADS) void graph_search_kernel(
         // old entry j moves down by the number of new entries that precede it
         const int nxt = cur ^ 1;
         int n_new = 0;
+#pragma unroll
         for (int i = 0; i < RP; ++i) n_new += (cpos[i] >= 0);
         for (int i = tid; i < RP; i += GRAPH_THREADS) {
             const int pos = cpos[i];
@@ -157,29 +185,41 @@ __global__ __launch_bounds__(GRAPH_THREADS) void graph_search_kernel(
                 const float s = cs[i];
                 const int v = ci[i];
                 int r = 0;
+#pragma unroll
                 for (int j = 0; j < RP; ++j) r += (cpos[j] >= 0 && precedes(cs[j], ci[j], s, v));
                 if (pos + r < ef) { ls[nxt][pos + r] = s; li[nxt][pos + r] = (uint32_t)v; }
             }
         }
         for (int j = tid; j < len; j += GRAPH_THREADS) {
             int shift = 0;
-            if (n_new)
+            if (n_new) {
+#pragma unroll
                 for (int i = 0; i < RP; ++i) shift += (cpos[i] >= 0 && cpos[i] <= j);
+            }
             if (j + shift < ef) { ls[nxt][j + shift] = ls[cur][j]; li[nxt][j + shift] = li[cur][j]; }
         }
         len = min(ef, len + n_new);
         cur = nxt;
-        par ^= 1;
         __syncthreads();
 
-        // first unexpanded entry of the new list
-        int first = INT_MAX;
-        for (int j = tid; j < len; j += GRAPH_THREADS)
-            if (!(li[cur][j] & EXPANDED)) { first = j; break; }
-#pragma unroll
-        for (int m = 1; m < 64; m <<= 1) first = min(first, __shfl_xor(first, m));
-        if (lane == 0 && first != INT_MAX) atomicMin(&ctl[par], first);
+        // best and second-best unexpanded entries of the new list: one ballot per 64 entries
+        const int words = (len + 63) >> 6;
+        for (int j0 = 0; j0 < len; j0 += GRAPH_THREADS) {
+            const int j = j0 + tid;
+            const uint64_t m = __builtin_amdgcn_ballot_w64(j < len && !(li[cur][j] & EXPANDED));
+            if (lane == 0 && (j0 >> 6) + wave < words) um[(j0 >> 6) + wave] = m;
+        }
         __syncthreads();
+        p = -1;
+        p2 = -1;
+        for (int w = 0; w < words && p2 < 0; ++w) {
+            uint64_t m = um[w];
+            while (m != 0 && p2 < 0) {
+                const int j = w * 64 + __builtin_ctzll(m);
+                m &= m - 1;
+                if (p < 0) p = j; else p2 = j;
+            }
+        }
     }
 
     for (int j = tid; j < k; j += GRAPH_THREADS) {

@@ -49,7 +49,7 @@ hipError_t launch_flat_merge(int kp, const Cand *partial, int P, int B, int k, i
 
 struct GraphLds {
     // byte offsets into dynamic LDS; all 16-byte aligned
-    uint32_t q, ls0, ls1, li0, li1, cs, ci, cpos, cache, ctl, total;
+    uint32_t q, ls0, ls1, li0, li1, cs, ci, cpos, cache, ctl, adj, um, total;
     uint32_t cache_bits, rp;
 };
 GraphLds graph_lds_layout(int d, int elem_bytes, int R, int ef);

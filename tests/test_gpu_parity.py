@@ -78,6 +78,9 @@ def test_cfg0_graph_fp32(cfg0):
     (777, 64, 300, 4),              # matrix-core path, two 256-query tiles, second one ragged
     (70001, 256, 129, 1),           # matrix-core path, many tiles per slab
     (100, 32, 2100, 2),             # more query tiles than tile groups; corpus smaller than a tile
+    (50_000, 768, 32, 3),           # two query groups, many tiles per wave
+    (2049, 96, 20, 10),             # ... ragged tile, k > 4
+    (300, 4096, 9, 2),              # largest d
     (600_001, 64, 200, 3),          # matrix-core path with the sampling pass, one query tile
     (300_000, 32, 600, 4),          # ... three query tiles
 ])
