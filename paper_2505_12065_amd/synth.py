@@ -132,6 +132,18 @@ def mean_entry(x: torch.Tensor) -> int:
     return best_id
 
 
+def _scores(a: torch.Tensor, b: torch.Tensor) -> torch.Tensor:
+    """fp32 inner products a @ b.T.  16-bit inputs on a GPU go through the matrix cores
+    with fp32 output when torch offers that (exact products, fp32 accumulation); otherwise
+    the operands are widened to fp32 first."""
+    if a.is_cuda and a.dtype in (torch.float16, torch.bfloat16):
+        try:
+            return torch.mm(a, b.T, out_dtype=torch.float32)
+        except (RuntimeError, TypeError):
+            pass
+    return a.float() @ b.float().T
+
+
 def _topr_rows(scores: torch.Tensor, ids: torch.Tensor, R: int) -> Tuple[torch.Tensor, torch.Tensor]:
     """Best R per row by (score desc, id asc). `ids[j]` is the row id of column j,
     ascending. Rows with fewer than R finite scores are padded with id -1."""
@@ -178,7 +190,8 @@ def knn_graph(x: torch.Tensor, R: int, *, row_block: int = 2048) -> torch.Tensor
 
 
 def knn_graph_cluster_restricted(corpus: Corpus, R: int, n_near: int = 8, *,
-                                 row_block: int = 4096, col_block: int = 1 << 16) -> torch.Tensor:
+                                 row_block: int = 4096, col_block: int = 1 << 16,
+                                 progress: bool = False) -> torch.Tensor:
     """Directed R-NN graph where point i's candidate pool is every point whose
     generator label is one of the `n_near` clusters whose L2-normalised centroid
     has the largest inner product with x_i. Self excluded, ties to the lower
@@ -201,21 +214,26 @@ def knn_graph_cluster_restricted(corpus: Corpus, R: int, n_near: int = 8, *,
 
     best_v = torch.full((N, R), -math.inf, dtype=torch.float32, device=dev)
     best_i = torch.full((N, R), -1, dtype=torch.int64, device=dev)
+    import time
+    last = time.time()
     for b in range(C):
         nb = int(counts[b])
         if nb == 0:
             continue
+        if progress and time.time() - last > 20:
+            print(f"  graph build: cluster {b}/{C} ({nb} members)", flush=True)
+            last = time.time()
         members = order[int(starts[b]): int(starts[b]) + nb]
         askers = (near == b).any(dim=1).nonzero().flatten()   # points whose pool contains cluster b
         if askers.numel() == 0:
             continue
         for a0 in range(0, askers.numel(), row_block):
             a = askers[a0:a0 + row_block]
-            xa = x[a].float()
+            xa = x[a]
             cur_v, cur_i = best_v[a], best_i[a]
             for m0 in range(0, nb, col_block):
                 m = members[m0:m0 + col_block]
-                s = xa @ x[m].float().T
+                s = _scores(xa, x[m])
                 s[a[:, None] == m[None, :]] = -math.inf
                 v, i = _topr_rows(s, m, R)
                 # merge the running best with this block's best, same total order

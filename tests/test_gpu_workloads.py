@@ -1,0 +1,144 @@
+"""GPU parity at the full sizes of the five workload configurations, in the launch
+configuration bench.py times.  Where the oracle cannot do every query in seconds
+(flat search over 1 M / 21 M rows) it is run on a sample of the queries and every
+output row of those queries is compared; the graph oracle is cheap and does them all."""
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2505_12065_amd as ann
+from paper_2505_12065_amd import synth
+from parity import compare_topk, recall
+
+pytestmark = [pytest.mark.gpu, pytest.mark.timeout(900)]
+DEV = "cuda:0"
+K = 3
+
+
+def say(*a):
+    print(*a, flush=True)
+    sys.stdout.flush()
+
+
+def sample_rows(B, n=12):
+    """Query rows the flat oracle is run on: the first few, the last few, some in between."""
+    if B <= n:
+        return np.arange(B)
+    return np.unique(np.concatenate([np.arange(4), np.linspace(4, B - 5, n - 8).astype(int), np.arange(B - 4, B)]))
+
+
+def check_flat_sampled(x, xh, q, B):
+    qb = q[:B].contiguous()
+    ids, sc = ann.ann_flat_search_typed(x, qb, K)
+    torch.cuda.synchronize()
+    rows = sample_rows(B)
+    qh = qb.cpu().numpy()
+    o_ids, _, o_sc64 = oracle.flat_search(xh, qh[rows], K)
+    strict, tolerant, n = compare_topk(ids.cpu().numpy()[rows], sc.cpu().numpy()[rows], o_ids, o_sc64, xh, qh, rows=rows)
+    return strict, tolerant, n, ids
+
+
+# ------------------------------------------------------------------ configurations 1 and 2 (1 M x 768)
+
+@pytest.fixture(scope="module")
+def cfg1():
+    c = synth.workload_corpus(1, device=DEV)
+    q = synth.make_queries(c, 512)
+    xh = c.x.cpu().numpy()
+    return c, q, xh
+
+
+@pytest.mark.parametrize("B", [1, 16, 64, 256, 512])
+def test_cfg1_flat_full_size(cfg1, B):
+    c, q, xh = cfg1
+    strict, tolerant, n, _ = check_flat_sampled(c.x, xh, q, B)
+    say(f"cfg1 flat N=1,000,000 B={B}: oracle on {n} sampled queries, strict={strict} tolerant={tolerant}")
+    assert strict >= n - 1
+
+
+@pytest.fixture(scope="module")
+def cfg2(cfg1):
+    c, q, xh = cfg1
+    g = synth.knn_graph_cluster_restricted(c, 32, 8)
+    entry = synth.mean_entry(c.x)
+    exact, _ = ann.ann_flat_search_typed(c.x, q, K)
+    torch.cuda.synchronize()
+    return g, g.cpu().numpy(), entry, exact.cpu().numpy()
+
+
+def test_cfg2_graph_matches_generator_definition_on_sampled_rows(cfg1, cfg2):
+    """The graph is an input; check a sample of its rows against numpy brute force over the
+    pool the configuration defines (points of the 8 clusters with the nearest centroids)."""
+    c, _, xh = cfg1
+    _, gh, _, _ = cfg2
+    labels = c.labels.numpy()
+    cn = (c.centroids / c.centroids.norm(dim=1, keepdim=True)).numpy().astype(np.float64)
+    rng = np.random.default_rng(5)
+    for i in rng.integers(0, xh.shape[0], 6):
+        near = np.argsort(-(cn @ xh[i].astype(np.float64)), kind="stable")[:8]
+        pool = np.nonzero(np.isin(labels, near))[0]
+        pool = pool[pool != i]
+        s = xh[pool].astype(np.float64) @ xh[i].astype(np.float64)
+        want = pool[np.lexsort((pool, -s))[:32]]
+        got = gh[i]
+        if got.tolist() != want.tolist():       # fp32 build vs fp64 check: only near-equal scores may swap
+            sg = np.sort(xh[got].astype(np.float64) @ xh[i].astype(np.float64))
+            sw = np.sort(xh[want].astype(np.float64) @ xh[i].astype(np.float64))
+            assert np.allclose(sg, sw, atol=1e-6), i
+
+
+@pytest.mark.parametrize("ef", [8, 16, 32, 64, 128, 256])
+def test_cfg2_graph_full_size(cfg1, cfg2, ef):
+    c, q, xh = cfg1
+    g, gh, entry, exact = cfg2
+    qh = q.cpu().numpy()
+    for B in (1, 64, 512):
+        qb = q[:B].contiguous()
+        ids, sc = ann.ann_graph_search_typed(c.x, g, entry, qb, K, ef)
+        torch.cuda.synchronize()
+        o_ids, _, o_sc64, nd, ne = oracle.graph_search(xh, gh, entry, qh[:B], K, ef)
+        strict, tolerant, n = compare_topk(ids.cpu().numpy(), sc.cpu().numpy(), o_ids, o_sc64, xh, qh[:B])
+        say(f"cfg2 graph ef={ef} B={B}: strict={strict}/{n} tolerant={tolerant} "
+            f"recall@3={recall(ids.cpu().numpy(), exact[:B]):.3f} n_dist={nd.mean():.0f} n_expand={ne.mean():.0f}")
+        assert strict >= n - max(1, n // 100)
+
+
+# ------------------------------------------------------------------ configuration 3 (21 M x 768, 32 GB)
+
+def test_cfg3_flat_full_size():
+    c = synth.workload_corpus(3, device=DEV)
+    assert c.x.shape == (21_000_000, 768)
+    q = synth.make_queries(c, 256)
+    xh = c.x.cpu().numpy()
+    for B in (1, 16, 256):
+        strict, tolerant, n, _ = check_flat_sampled(c.x, xh, q, B)
+        say(f"cfg3 flat N=21,000,000 B={B}: oracle on {n} sampled queries, strict={strict} tolerant={tolerant}")
+        assert strict >= n - 1
+    del xh, c
+    torch.cuda.empty_cache()
+
+
+# ------------------------------------------------------------------ configuration 4 (10 M x 768, graph)
+
+def test_cfg4_graph_full_size():
+    c = synth.workload_corpus(4, device=DEV)
+    assert c.x.shape == (10_000_000, 768)
+    q = synth.make_queries(c, 256)
+    g = synth.knn_graph_cluster_restricted(c, 32, 8)
+    entry = synth.mean_entry(c.x)
+    exact, _ = ann.ann_flat_search_typed(c.x, q, K)
+    torch.cuda.synchronize()
+    xh, gh, qh, exact = c.x.cpu().numpy(), g.cpu().numpy(), q.cpu().numpy(), exact.cpu().numpy()
+    for ef in (32, 64, 128):
+        ids, sc = ann.ann_graph_search_typed(c.x, g, entry, q, K, ef)
+        torch.cuda.synchronize()
+        o_ids, _, o_sc64, nd, ne = oracle.graph_search(xh, gh, entry, qh, K, ef)
+        strict, tolerant, n = compare_topk(ids.cpu().numpy(), sc.cpu().numpy(), o_ids, o_sc64, xh, qh)
+        say(f"cfg4 graph N=10,000,000 ef={ef} B=256: strict={strict}/{n} tolerant={tolerant} "
+            f"recall@3={recall(ids.cpu().numpy(), exact):.3f} n_dist={nd.mean():.0f} n_expand={ne.mean():.0f}")
+        assert strict >= n - 3
+    del xh, gh, c, g
+    torch.cuda.empty_cache()
