@@ -206,17 +206,18 @@ __global__ __launch_bounds__(256) void flat_f32_kernel(const float *__restrict__
     }
 }
 
-// One workgroup per query: the k best of its P*KP partial pairs, written in order;
-// unused tail slots become id -1 / score -inf.
+// One workgroup (1 to 4 wavefronts, by the amount of work) per query: the k best of its
+// P*KP partial pairs, written in order; unused tail slots become id -1 / score -inf.
 template <int KP>
 __global__ __launch_bounds__(256) void flat_merge_kernel(const Cand *__restrict__ partial, int P, int k,
                                                          int32_t *__restrict__ ids, float *__restrict__ scores) {
     __shared__ Cand wl[4 * KP];
     const int q = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int nwaves = blockDim.x >> 6;
     const Cand *in = partial + (size_t)q * P * KP;
     TopList<KP> best;
     best.init();
-    for (int e = tid; e < P * KP; e += 256) {
+    for (int e = tid; e < P * KP; e += blockDim.x) {
         const Cand c = in[e];
         if (best.admits(c.s, c.id)) best.insert(c.s, c.id);
     }
@@ -230,7 +231,7 @@ __global__ __launch_bounds__(256) void flat_merge_kernel(const Cand *__restrict_
     if (tid == 0) {
         TopList<KP> fin;
         fin.init();
-        for (int e = 0; e < 4 * KP; ++e)
+        for (int e = 0; e < nwaves * KP; ++e)
             if (fin.admits(wl[e].s, wl[e].id)) fin.insert(wl[e].s, wl[e].id);
 #pragma unroll
         for (int j = 0; j < KP; ++j)

@@ -261,16 +261,21 @@ __global__ __launch_bounds__(128 * NWN) void flat_wide_kernel(const void *__rest
 #pragma unroll
                                 for (int r = 0; r < 16; ++r) m = fmaxf(m, acc[decltype(ic)::value][j][r]);
                             });
-                            int row = EMPTY_ID;
+                            int idx = 64;                          // first accumulator holding the maximum
                             static_for<4>([&](auto ic) {
                                 constexpr int i = decltype(ic)::value;
 #pragma unroll
-                                for (int r = 0; r < 16; ++r) {          // lowest row id holding the maximum
-                                    const bool hit = acc[i][j][r] == m && row == EMPTY_ID;
-                                    row = hit ? rbase + (i * 32 + 8 * (r / 4) + (r % 4)) : row;
-                                    acc[i][j][r] = hit ? -INFINITY : acc[i][j][r];
-                                }
+                                for (int r = 0; r < 16; ++r) idx = min(idx, acc[i][j][r] == m ? i * 16 + r : 64);
                             });
+                            static_for<4>([&](auto ic) {
+                                constexpr int i = decltype(ic)::value;
+#pragma unroll
+                                for (int r = 0; r < 16; ++r) acc[i][j][r] = (i * 16 + r == idx) ? -INFINITY : acc[i][j][r];
+                            });
+                            // accumulator e = 16 i + r holds tile row 32 i + 8 (r / 4) + r % 4 (+ 4 lhi), so
+                            // the first maximum in accumulator order is also the one with the lowest row id
+                            const int r = idx & 15;
+                            const int row = rbase + (idx >> 4) * 32 + 8 * (r >> 2) + (r & 3);
                             if (m > -INFINITY && best[j].admits(m, row)) best[j].insert(m, row);
                         }
                     });
