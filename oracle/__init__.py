@@ -56,6 +56,11 @@ def _load():
         lib.oracle_graph_search.argtypes = [c.c_void_p, c.c_int64, c.c_int32, c.c_int, c.c_void_p, c.c_int32,
                                             c.c_int32, c.c_void_p, c.c_int32, c.c_int32, c.c_int32,
                                             c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_int]
+        lib.oracle_graph_search_nonstall.restype = c.c_int
+        lib.oracle_graph_search_nonstall.argtypes = [c.c_void_p, c.c_int64, c.c_int32, c.c_int, c.c_void_p, c.c_int32,
+                                                     c.c_int32, c.c_void_p, c.c_int32, c.c_int32, c.c_int32,
+                                                     c.c_float, c.c_int32, c.c_int64, c.c_int64,
+                                                     c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_int]
         _lib = lib
     return _lib
 
@@ -126,6 +131,31 @@ def graph_search(corpus, graph, entry: int, queries, k: int, ef: int, *, dtype: 
     if rc != 0:
         raise ValueError("oracle_graph_search: bad arguments")
     return ids, sc, sc64, nd, ne
+
+
+def graph_search_nonstall(corpus, graph, entry: int, queries, k: int, ef: int, *, tau: float = 0.9,
+                          window: int = 500, ready_from: int = 0, max_expand: int = 0,
+                          dtype: Optional[str] = None, n_threads: int = 0):
+    """Best-first graph search with the maturity (non-stall) exit of Section 3.3.
+    Returns (ids, scores fp32, scores fp64, stats int32 [B,3] = (early, n_dist, n_expand), ema fp32 [B])."""
+    corpus, queries, code = _prep(corpus, queries, dtype)
+    graph = np.ascontiguousarray(graph, dtype=np.int32)
+    N, d = corpus.shape
+    if graph.ndim != 2 or graph.shape[0] != N:
+        raise ValueError("graph [N,R] expected")
+    B = queries.shape[0]
+    ids = np.empty((B, k), np.int32)
+    sc = np.empty((B, k), np.float32)
+    sc64 = np.empty((B, k), np.float64)
+    stats = np.empty((B, 3), np.int32)
+    ema = np.empty(B, np.float32)
+    rc = _load().oracle_graph_search_nonstall(corpus.ctypes.data, N, d, code, graph.ctypes.data, graph.shape[1], entry,
+                                              queries.ctypes.data, B, k, ef, tau, window, ready_from, max_expand,
+                                              ids.ctypes.data, sc.ctypes.data, sc64.ctypes.data, stats.ctypes.data,
+                                              ema.ctypes.data, n_threads)
+    if rc != 0:
+        raise ValueError("oracle_graph_search_nonstall: bad arguments")
+    return ids, sc, sc64, stats, ema
 
 
 def recall_at_k(approx_ids: np.ndarray, exact_ids: np.ndarray) -> float:

@@ -249,3 +249,106 @@ int oracle_graph_search(const void *corpus, int64_t N, int32_t d, int dtype,
     }
     return failed ? -1 : 0;
 }
+
+/*
+ * Graph retrieval with the non-stall (maturity) exit of Section 3.3 / Appendix B.2.
+ *
+ * The search is the one above.  In addition every newly scored node t yields
+ *     RQ_t = (d_t - d_best) / (d_worst - d_best),     d = -score (a distance),
+ * where d_best / d_worst belong to the best and worst entries of the candidate list.
+ * RQ is smoothed by an exponential moving average with window W ("window size of
+ * 500"; read as alpha = 2 / (W + 1), EMA_0 = 0), and the search stops as soon as
+ * EMA > tau (0.9 in the paper) AND the engine is ready; otherwise it stops naturally.
+ *
+ * Readings: the neighbours of one expansion are handled as a batch, so best and worst
+ * are those of the list as it stood when the expansion started; neighbours enter the
+ * average in slot order; a node whose RQ is undefined (fewer than two list entries, or
+ * best == worst) is skipped; the exit test is made after each expansion.
+ * `ready_from` models the engine: it is ready from expansion count `ready_from` on
+ * (0 = always, a huge value = never).  `max_expand` > 0 additionally stops the search
+ * after that many expansions (used to check that an early exit returns exactly the
+ * state the full search had at that point).
+ *
+ * Decision precision: RQ and the EMA are computed in binary32 with one fused
+ * multiply-add per update, the same operations the GPU kernel uses, from the score
+ * rounded to binary32.  stats[b] = {early exit (0/1), scored nodes, expansions}.
+ */
+int oracle_graph_search_nonstall(const void *corpus, int64_t N, int32_t d, int dtype,
+                                 const int32_t *graph, int32_t R, int32_t entry,
+                                 const void *queries, int32_t B, int32_t k, int32_t ef,
+                                 float tau, int32_t window, int64_t ready_from, int64_t max_expand,
+                                 int32_t *ids, float *scores, double *scores64,
+                                 int32_t *stats, float *ema_out, int threads)
+{
+    if (!corpus || !graph || !queries || !ids || !scores || N < 1 || d < 1 || R < 1 ||
+        B < 1 || k < 1 || ef < k || entry < 0 || entry >= N || window < 1)
+        return -1;
+    prepare_tables();
+    const float alpha = 2.0f / ((float)window + 1.0f);
+    int failed = 0;
+#pragma omp parallel for schedule(dynamic, 1) num_threads(use_threads(threads))
+    for (int32_t b = 0; b < B; ++b) {
+        double *q = malloc(sizeof(double) * (size_t)d);
+        uint8_t *visited = calloc((size_t)N, 1);
+        scored_t *L = malloc(sizeof(scored_t) * (size_t)(ef + 1));
+        uint8_t *expanded = malloc((size_t)(ef + 1));
+        if (!q || !visited || !L || !expanded) {
+            failed = 1; free(q); free(visited); free(L); free(expanded); continue;
+        }
+        for (int32_t j = 0; j < d; ++j) q[j] = load_value(queries, (int64_t)b * d + j, dtype);
+
+        int32_t len = 1, early = 0;
+        int64_t dist_count = 1, expand_count = 0;
+        float ema = 0.0f;
+        visited[entry] = 1;
+        L[0].s = score_row(corpus, entry, d, dtype, q);
+        L[0].id = entry;
+        expanded[0] = 0;
+
+        for (;;) {
+            int32_t p = 0;
+            while (p < len && expanded[p]) ++p;
+            if (p == len) break;
+            if (max_expand > 0 && expand_count >= max_expand) break;
+            expanded[p] = 1;
+            ++expand_count;
+            int32_t node = L[p].id;
+            /* best and worst of the list as this expansion starts */
+            const int have_range = len >= 2;
+            const float s_best = (float)L[0].s, s_worst = (float)L[len - 1].s;
+            for (int32_t slot = 0; slot < R; ++slot) {
+                int32_t v = graph[(int64_t)node * R + slot];
+                if (v < 0 || v >= N || visited[v]) continue;
+                visited[v] = 1;
+                ++dist_count;
+                double s = score_row(corpus, v, d, dtype, q);
+                if (have_range && s_best != s_worst) {
+                    /* (d_t - d_best) / (d_worst - d_best) with d = -score */
+                    const float rq = (s_best - (float)s) / (s_best - s_worst);
+                    ema = fmaf(alpha, rq - ema, ema);
+                }
+                if (len == ef && !precedes(s, v, L[len - 1].s, L[len - 1].id)) continue;
+                int32_t pos = len;
+                while (pos > 0 && precedes(s, v, L[pos - 1].s, L[pos - 1].id)) --pos;
+                for (int32_t i = len; i > pos; --i) { L[i] = L[i - 1]; expanded[i] = expanded[i - 1]; }
+                L[pos].s = s; L[pos].id = v; expanded[pos] = 0;
+                if (len < ef) ++len;
+            }
+            if (ema > tau && expand_count >= ready_from) { early = 1; break; }
+        }
+        for (int32_t i = 0; i < k; ++i) {
+            int has = i < len;
+            ids[(int64_t)b * k + i] = has ? L[i].id : -1;
+            scores[(int64_t)b * k + i] = has ? (float)L[i].s : -INFINITY;
+            if (scores64) scores64[(int64_t)b * k + i] = has ? L[i].s : -INFINITY;
+        }
+        if (stats) {
+            stats[(int64_t)b * 3 + 0] = early;
+            stats[(int64_t)b * 3 + 1] = (int32_t)dist_count;
+            stats[(int64_t)b * 3 + 2] = (int32_t)expand_count;
+        }
+        if (ema_out) ema_out[b] = ema;
+        free(q); free(visited); free(L); free(expanded);
+    }
+    return failed ? -1 : 0;
+}

@@ -127,6 +127,8 @@ def read_trace():
             ef, k = (int(t) for t in a.split())
             nd, ne = (int(t) for t in c.split())
             cases.append((ef, k, [int(t) for t in b.split()], nd, ne))
+        elif line.startswith("nonstall"):
+            continue
         elif line.startswith("exact3"):
             exact = [int(t) for t in line.split("|")[1].split()]
     return values, cases, exact
@@ -288,3 +290,124 @@ def test_recall_definition():
     exact = np.array([[1, 2, 3], [4, 5, 6]], np.int32)
     approx = np.array([[3, 9, 1], [-1, -1, 4]], np.int32)
     assert oracle.recall_at_k(approx, exact) == pytest.approx(3 / 6)
+
+
+# ---------------------------------------------------------------- maturity (non-stall) exit
+
+def read_nonstall_trace():
+    out = []
+    for line in open(os.path.join(GOLDEN, "path_graph_trace.txt")):
+        if line.startswith("nonstall"):
+            a, b, c, e = line[len("nonstall"):].split("|")
+            w, tau, rf = a.split()
+            out.append((int(w), float(tau), int(rf), [int(t) for t in b.split()], [int(t) for t in c.split()], float(e)))
+    return out
+
+
+def test_nonstall_hand_trace():
+    values, _, _ = read_trace()
+    corpus = np.array(values, np.float32).reshape(-1, 1)
+    q = np.ones((1, 1), np.float32)
+    g = path_graph(len(values))
+    cases = read_nonstall_trace()
+    assert len(cases) == 5
+    for w, tau, rf, want_ids, want_stats, want_ema in cases:
+        ids, _, _, stats, ema = oracle.graph_search_nonstall(corpus, g, 0, q, 3, 3, tau=tau, window=w, ready_from=rf)
+        assert ids[0].tolist() == want_ids, (w, tau, rf)
+        assert stats[0].tolist() == want_stats, (w, tau, rf)
+        assert ema[0] == pytest.approx(want_ema, abs=2e-6)
+
+
+def test_nonstall_constant_rq_closed_form():
+    """Path graph, scores 1, 0, 0, 0, ...: from the second expansion on every new node has
+    RQ = (1 - 0) / (1 - 0) = 1, so after n samples EMA = 1 - (1 - alpha)^n and the exit
+    comes at the first n with EMA > tau: n = floor(ln(1 - tau) / ln(1 - alpha)) + 1."""
+    n = 1500
+    corpus = np.zeros((n, 1), np.float32)
+    corpus[0] = 1.0
+    q = np.ones((1, 1), np.float32)
+    g = path_graph(n)
+    for window, tau in ((500, 0.9), (100, 0.5), (20, 0.97)):
+        alpha = 2.0 / (window + 1)
+        n_samples = int(np.floor(np.log(1 - tau) / np.log(1 - alpha))) + 1
+        assert abs((1 - (1 - alpha) ** n_samples) - tau) > 1e-4          # not a borderline decision
+        assert abs((1 - (1 - alpha) ** (n_samples - 1)) - tau) > 1e-4
+        ids, _, _, stats, ema = oracle.graph_search_nonstall(corpus, g, 0, q, 3, n, tau=tau, window=window)
+        early, nd, ne = stats[0].tolist()
+        assert early == 1
+        assert ne == n_samples + 1                    # the first expansion yields no sample
+        assert nd == ne + 1
+        assert ema[0] == pytest.approx(1 - (1 - alpha) ** n_samples, abs=1e-4)
+        assert ids[0].tolist() == [0, 1, 2]
+
+
+def nonstall_by_sets(S, graph, entry, ef, tau, alpha, ready_from):
+    """Second formulation in double precision: the list is recomputed as the best ef of all
+    scored nodes; returns (early, n_dist, n_expand, min |EMA - tau| seen at a test)."""
+    N = len(S)
+    key = lambda v: (-S[v], v)
+    scored, expanded, ema, margin = {entry}, set(), 0.0, np.inf
+    while True:
+        L = sorted(scored, key=key)[:ef]
+        todo = [v for v in L if v not in expanded]
+        if not todo:
+            return 0, len(scored), len(expanded), margin
+        p = todo[0]
+        expanded.add(p)
+        best, worst = S[L[0]], S[L[-1]]
+        for v in graph[p]:
+            if 0 <= v < N and v not in scored:
+                scored.add(int(v))
+                if len(L) >= 2 and best != worst:
+                    ema += alpha * ((best - S[v]) / (best - worst) - ema)
+        margin = min(margin, abs(ema - tau))
+        if ema > tau and len(expanded) >= ready_from:
+            return 1, len(scored), len(expanded), margin
+
+
+@pytest.mark.parametrize("ef,window,tau,ready_from", [(8, 10, 0.7, 0), (16, 30, 0.8, 0), (16, 30, 0.8, 12), (32, 60, 0.9, 0), (4, 5, 0.5, 3)])
+def test_nonstall_matches_set_formulation(ef, window, tau, ready_from):
+    n, R = 400, 6
+    x = unit_rows(n, 12)
+    g = random_graph(n, R)
+    q = unit_rows(6, 12)
+    S = x.astype(np.float64) @ q.astype(np.float64).T
+    _, _, _, stats, _ = oracle.graph_search_nonstall(x, g, 0, q, 3, ef, tau=tau, window=window, ready_from=ready_from)
+    checked = 0
+    for b in range(q.shape[0]):
+        early, nd, ne, margin = nonstall_by_sets(S[:, b], g, 0, ef, tau, 2.0 / (window + 1), ready_from)
+        if margin < 1e-4:         # binary32 vs double could decide differently: not a pin
+            continue
+        assert stats[b].tolist() == [early, nd, ne], b
+        checked += 1
+    assert checked >= 4
+
+
+def test_nonstall_never_triggered_equals_natural_stop():
+    n = 600
+    x = unit_rows(n, 16)
+    g = random_graph(n, 8)
+    q = unit_rows(5, 16)
+    ref = oracle.graph_search(x, g, 0, q, 4, 24)
+    for kw in (dict(tau=np.inf), dict(tau=0.1, ready_from=1 << 40)):
+        ids, sc, sc64, stats, _ = oracle.graph_search_nonstall(x, g, 0, q, 4, 24, window=7, **kw)
+        assert np.array_equal(ids, ref[0]) and np.array_equal(sc64, ref[2])
+        assert np.array_equal(stats[:, 0], np.zeros(5, np.int32))
+        assert np.array_equal(stats[:, 1], ref[3]) and np.array_equal(stats[:, 2], ref[4])
+
+
+def test_nonstall_exit_returns_the_state_of_the_full_search_at_that_point():
+    """An early exit only cuts the search short: its result is what the natural search
+    holds after the same number of expansions, and it never expands more."""
+    n = 800
+    x = unit_rows(n, 16)
+    g = random_graph(n, 8)
+    q = unit_rows(8, 16)
+    nat = oracle.graph_search(x, g, 0, q, 3, 32)
+    ids, _, sc64, stats, _ = oracle.graph_search_nonstall(x, g, 0, q, 3, 32, tau=0.6, window=15)
+    assert stats[:, 0].sum() >= 4
+    for b in range(8):
+        assert stats[b, 2] <= nat[4][b]
+        cut = oracle.graph_search_nonstall(x, g, 0, q[b:b + 1], 3, 32, tau=np.inf, max_expand=int(stats[b, 2]))
+        assert np.array_equal(cut[0][0], ids[b]) and np.array_equal(cut[2][0], sc64[b])
+        assert cut[3][0, 1] == stats[b, 1]
