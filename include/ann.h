@@ -124,6 +124,40 @@ int ann_graph_search(const void *corpus, const int32_t *graph, int32_t R, int32_
                      const void *queries, int32_t B, int32_t k, int32_t ef,
                      int32_t *ids, float *scores, void *stream);
 
+/* Approximate retrieval with the maturity (non-stall) exit (Section 3.3 "Non-Stall
+ * Retrieval", Appendix B.2 "Retrieval Maturity Estimation").  The search of
+ * ann_graph_search_typed, with one addition.  Every newly scored node t yields
+ *     RQ_t = (d_t - d_best) / (d_worst - d_best),   d = -score,
+ * against the best and worst entries of the candidate list; the values feed an
+ * exponential moving average (EMA_0 = 0, alpha = 2 / (window + 1)); a query returns
+ * its current list as soon as EMA > tau and the engine-ready word is non-zero, else
+ * it stops naturally.  The neighbours of one expansion form a batch: best / worst are
+ * those of the list as the expansion starts, samples are taken in slot order, nodes
+ * with an undefined RQ (best == worst) are skipped, the test follows the expansion.
+ * RQ and the average are binary32.
+ *
+ *   tau, window    threshold and EMA window (the paper uses 0.9 and 500); window >= 1
+ *   engine_ready   device-visible int32 (device memory or pinned host memory) the host
+ *                  may change while the call runs; read with system scope each time a
+ *                  mature query tests it; NULL = always ready.  Not owned.
+ *   stats          device, [B, 3] int32 = (1 if left early, nodes scored, expansions),
+ *                  or NULL
+ *   ema            device, [B] float, final value of the average, or NULL
+ *
+ * Uses a per-device workspace of B * 64 * ceil(N / 512) bytes (exact visited sets),
+ * grown on demand and cleared by the call; calls on one device must not overlap.
+ * Errors as ann_graph_search_typed, plus ANN_ERR_INVALID for window < 1 or a NaN tau
+ * and ANN_ERR_NOMEM. */
+int ann_graph_search_nonstall_typed(const void *corpus, int64_t N, int32_t d, int32_t dtype,
+                                    const int32_t *graph, int32_t R, int32_t entry,
+                                    const void *queries, int32_t B, int32_t k, int32_t ef,
+                                    float tau, int32_t window, const int32_t *engine_ready,
+                                    int32_t *ids, float *scores, int32_t *stats, float *ema,
+                                    void *stream);
+
+/* Bytes of workspace ann_graph_search_nonstall_typed needs for (N, B). */
+int64_t ann_graph_nonstall_workspace_bytes(int64_t N, int32_t B);
+
 /* Remember the shape and element type of a corpus so that ann_graph_search can
  * be called with the short argument list.  Re-registering a pointer replaces
  * its record.  The library never dereferences or frees the pointer here. */

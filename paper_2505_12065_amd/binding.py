@@ -21,7 +21,8 @@ _DTYPES = {torch.float16: ANN_F16, torch.bfloat16: ANN_BF16, torch.float32: ANN_
 
 EXPORTS = ("ann_version", "ann_last_error", "ann_flat_search_typed", "ann_flat_search",
            "ann_graph_search_typed", "ann_graph_search", "ann_register_corpus", "ann_unregister_corpus",
-           "ann_set_default_dtype", "ann_flat_workspace_bytes", "ann_release_workspace")
+           "ann_set_default_dtype", "ann_flat_workspace_bytes", "ann_release_workspace",
+           "ann_graph_search_nonstall_typed", "ann_graph_nonstall_workspace_bytes")
 
 
 class AnnError(RuntimeError):
@@ -55,8 +56,12 @@ def lib() -> ctypes.CDLL:
         L.ann_set_default_dtype.argtypes = [i32]
         L.ann_flat_workspace_bytes.argtypes = [i64, i32, i32, i32, i32]
         L.ann_flat_workspace_bytes.restype = i64
+        L.ann_graph_search_nonstall_typed.argtypes = [vp, i64, i32, i32, vp, i32, i32, vp, i32, i32, i32,
+                                                      c.c_float, i32, vp, vp, vp, vp, vp, vp]
+        L.ann_graph_nonstall_workspace_bytes.argtypes = [i64, i32]
+        L.ann_graph_nonstall_workspace_bytes.restype = i64
         for name in EXPORTS:
-            if name not in ("ann_last_error", "ann_flat_workspace_bytes"):
+            if name not in ("ann_last_error", "ann_flat_workspace_bytes", "ann_graph_nonstall_workspace_bytes"):
                 getattr(L, name).restype = c.c_int
         _lib = L
     return _lib
@@ -149,6 +154,46 @@ def ann_graph_search_typed(corpus: torch.Tensor, graph: torch.Tensor, entry: int
                                             graph.shape[1], int(entry), queries.data_ptr(), B, k, ef,
                                             ids.data_ptr(), scores.data_ptr(), _stream(stream)))
     return ids, scores
+
+
+def ann_graph_search_nonstall_typed(corpus: torch.Tensor, graph: torch.Tensor, entry: int, queries: torch.Tensor,
+                                    k: int, ef: int, *, tau: float = 0.9, window: int = 500,
+                                    engine_ready: Optional[torch.Tensor] = None, ids=None, scores=None,
+                                    stats=None, ema=None, stream=None):
+    """Graph search with the maturity (non-stall) exit.  `engine_ready` is an int32 tensor of one
+    element on the device or in pinned host memory (None = always ready).  Returns
+    (ids, scores, stats [B,3] = (early, scored, expansions), ema [B])."""
+    _matrix(corpus, "corpus"), _matrix(queries, "queries")
+    if queries.dtype != corpus.dtype or queries.shape[1] != corpus.shape[1]:
+        raise ValueError("queries must have the corpus' element type and dimension")
+    (N, d), B = corpus.shape, queries.shape[0]
+    _graph(graph, N)
+    ids, scores = _outputs(B, k, corpus.device, ids, scores)
+    if stats is None:
+        stats = torch.empty(B, 3, dtype=torch.int32, device=corpus.device)
+    if ema is None:
+        ema = torch.empty(B, dtype=torch.float32, device=corpus.device)
+    if stats.dtype != torch.int32 or tuple(stats.shape) != (B, 3) or not stats.is_contiguous() or not stats.is_cuda:
+        raise ValueError("stats must be a contiguous int32 [B, 3] device tensor")
+    if ema.dtype != torch.float32 or tuple(ema.shape) != (B,) or not ema.is_contiguous() or not ema.is_cuda:
+        raise ValueError("ema must be a contiguous float32 [B] device tensor")
+    ready_ptr = 0
+    if engine_ready is not None:
+        if engine_ready.dtype != torch.int32 or engine_ready.numel() != 1 or \
+                not (engine_ready.is_cuda or engine_ready.is_pinned()):
+            raise ValueError("engine_ready must be one int32 on the device or in pinned host memory")
+        ready_ptr = engine_ready.data_ptr()
+    with torch.cuda.device(corpus.device):
+        _check(lib().ann_graph_search_nonstall_typed(corpus.data_ptr(), N, d, _DTYPES[corpus.dtype], graph.data_ptr(),
+                                                     graph.shape[1], int(entry), queries.data_ptr(), B, k, ef,
+                                                     float(tau), int(window), ready_ptr, ids.data_ptr(),
+                                                     scores.data_ptr(), stats.data_ptr(), ema.data_ptr(),
+                                                     _stream(stream)))
+    return ids, scores, stats, ema
+
+
+def ann_graph_nonstall_workspace_bytes(N: int, B: int) -> int:
+    return int(lib().ann_graph_nonstall_workspace_bytes(N, B))
 
 
 def ann_graph_search(corpus: torch.Tensor, graph: torch.Tensor, entry: int, queries: torch.Tensor, k: int, ef: int,

@@ -35,6 +35,8 @@ struct DeviceState {
     int cus = 0;
     void *ws = nullptr;
     size_t ws_bytes = 0;
+    void *vis = nullptr;          // visited bitsets of the non-stall graph search
+    size_t vis_bytes = 0;
 };
 
 std::mutex g_mu;
@@ -55,19 +57,24 @@ int device_state(DeviceState **out) {
     return ANN_OK;
 }
 
-int ensure_workspace(DeviceState *st, size_t bytes) {
-    if (st->ws_bytes >= bytes) return ANN_OK;
-    if (st->ws) (void)hipFree(st->ws);           // synchronises the device: no kernel still uses it
-    st->ws = nullptr;
-    st->ws_bytes = 0;
+int grow(void **buf, size_t *have, size_t bytes) {
+    if (*have >= bytes) return ANN_OK;
+    if (*buf) (void)hipFree(*buf);               // synchronises the device: no kernel still uses it
+    *buf = nullptr;
+    *have = 0;
     size_t want = bytes + bytes / 4;
-    if (hipMalloc(&st->ws, want) != hipSuccess) {
+    if (hipMalloc(buf, want) != hipSuccess) {
         (void)hipGetLastError();
         return fail(ANN_ERR_NOMEM, "cannot allocate %zu bytes of device workspace", want);
     }
-    st->ws_bytes = want;
+    *have = want;
     return ANN_OK;
 }
+
+int ensure_workspace(DeviceState *st, size_t bytes) { return grow(&st->ws, &st->ws_bytes, bytes); }
+
+// words of one query's visited bitset: one bit per node, rounded to 16-byte units
+int64_t visited_words(int64_t N) { return (N + 511) / 512 * 16; }
 
 int check_launch(const char *what, hipError_t e) {
     if (e != hipSuccess) {
@@ -240,6 +247,9 @@ int ann_release_workspace(void) {
     if (st->ws) (void)hipFree(st->ws);
     st->ws = nullptr;
     st->ws_bytes = 0;
+    if (st->vis) (void)hipFree(st->vis);
+    st->vis = nullptr;
+    st->vis_bytes = 0;
     return ANN_OK;
 }
 
@@ -263,9 +273,9 @@ int ann_flat_search(const void *corpus, int64_t N, int32_t d, const void *querie
     return ann_flat_search_typed(corpus, N, d, g_default_dtype, queries, B, k, ids, scores, stream);
 }
 
-int ann_graph_search_typed(const void *corpus, int64_t N, int32_t d, int32_t dtype, const int32_t *graph,
-                           int32_t R, int32_t entry, const void *queries, int32_t B, int32_t k, int32_t ef,
-                           int32_t *ids, float *scores, void *stream) {
+static int check_graph(const void *corpus, int64_t N, int32_t d, int32_t dtype, const int32_t *graph, int32_t R,
+                       int32_t entry, const void *queries, int32_t B, int32_t k, int32_t ef, const int32_t *ids,
+                       const float *scores, GraphLds *L) {
     if (!graph) return fail(ANN_ERR_INVALID, "null graph pointer");
     if (R < 1 || R > ANN_R_MAX) return fail(ANN_ERR_INVALID, "R = %d out of range [1, %d]", R, ANN_R_MAX);
     if (ef < 1 || ef > ANN_EF_MAX) return fail(ANN_ERR_INVALID, "ef = %d out of range [1, %d]", ef, ANN_EF_MAX);
@@ -273,8 +283,50 @@ int ann_graph_search_typed(const void *corpus, int64_t N, int32_t d, int32_t dty
     if (k > ef) return fail(ANN_ERR_INVALID, "ef = %d is smaller than k = %d", ef, k);
     if (entry < 0 || entry >= N) return fail(ANN_ERR_INVALID, "entry = %d is not a node id", entry);
     if (reinterpret_cast<uintptr_t>(graph) & 3) return fail(ANN_ERR_ALIGNMENT, "graph must be 4-byte aligned");
-    const GraphLds L = graph_lds_layout(d, elem_bytes(dtype), R, ef);
-    if (L.total > LDS_MAX) return fail(ANN_ERR_INVALID, "d = %d, ef = %d need %u bytes of LDS", d, ef, L.total);
+    *L = graph_lds_layout(d, elem_bytes(dtype), R, ef);
+    if (L->total > LDS_MAX) return fail(ANN_ERR_INVALID, "d = %d, ef = %d need %u bytes of LDS", d, ef, L->total);
+    return ANN_OK;
+}
+
+int64_t ann_graph_nonstall_workspace_bytes(int64_t N, int32_t B) {
+    if (N < 1 || N > INT32_MAX || B < 1) return ANN_ERR_INVALID;
+    return (int64_t)B * visited_words(N) * 4;
+}
+
+int ann_graph_search_nonstall_typed(const void *corpus, int64_t N, int32_t d, int32_t dtype, const int32_t *graph,
+                                    int32_t R, int32_t entry, const void *queries, int32_t B, int32_t k, int32_t ef,
+                                    float tau, int32_t window, const int32_t *engine_ready, int32_t *ids,
+                                    float *scores, int32_t *stats, float *ema, void *stream) {
+    GraphLds L;
+    if (int rc = check_graph(corpus, N, d, dtype, graph, R, entry, queries, B, k, ef, ids, scores, &L)) return rc;
+    if (window < 1) return fail(ANN_ERR_INVALID, "window = %d must be at least 1", window);
+    if (tau != tau) return fail(ANN_ERR_INVALID, "tau is not a number");
+    if ((reinterpret_cast<uintptr_t>(engine_ready) | reinterpret_cast<uintptr_t>(stats) |
+         reinterpret_cast<uintptr_t>(ema)) & 3)
+        return fail(ANN_ERR_ALIGNMENT, "engine_ready, stats and ema must be 4-byte aligned");
+    std::lock_guard<std::mutex> lock(g_mu);
+    DeviceState *st = nullptr;
+    if (int rc = device_state(&st)) return rc;
+    NonStall ns;
+    ns.tau = tau;
+    ns.alpha = 2.0f / ((float)window + 1.0f);
+    ns.ready = engine_ready;
+    ns.words = visited_words(N);
+    ns.stats = stats;
+    ns.ema = ema;
+    if (int rc = grow(&st->vis, &st->vis_bytes, (size_t)B * (size_t)ns.words * 4)) return rc;
+    ns.visited = static_cast<uint32_t *>(st->vis);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    return check_launch("graph_search_kernel (non-stall)",
+                        launch_graph_search_nonstall(dtype, corpus, N, d, graph, R, entry, queries, B, k, ef, ids,
+                                                     scores, L, ns, s));
+}
+
+int ann_graph_search_typed(const void *corpus, int64_t N, int32_t d, int32_t dtype, const int32_t *graph,
+                           int32_t R, int32_t entry, const void *queries, int32_t B, int32_t k, int32_t ef,
+                           int32_t *ids, float *scores, void *stream) {
+    GraphLds L;
+    if (int rc = check_graph(corpus, N, d, dtype, graph, R, entry, queries, B, k, ef, ids, scores, &L)) return rc;
     std::lock_guard<std::mutex> lock(g_mu);
     hipStream_t s = static_cast<hipStream_t>(stream);
     return check_launch("graph_search_kernel",

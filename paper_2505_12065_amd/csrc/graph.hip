@@ -24,38 +24,60 @@ GraphLds graph_lds_layout(int d, int elem_bytes, int R, int ef) {
     L.ctl = off; off = up(off + 16u);
     L.adj = off; off = up(off + 2u * 4u * RMAX_LDS);
     L.um = off; off = up(off + 8u * ((uint32_t)ef + 63u) / 64u + 8u);
+    L.rq = off; off = up(off + 4u * L.rp);
+    L.co = off; off = up(off + 4u * L.rp);
     L.total = off;
     return L;
 }
 
 namespace {
-template <class T, int RPT>
+template <class T, int RPT, bool NS>
 hipError_t launch_rp(const void *X, int64_t N, int d, const int32_t *graph, int R, int entry, const void *Q, int B,
-                     int k, int ef, int32_t *ids, float *scores, const GraphLds &L, hipStream_t stream) {
+                     int k, int ef, int32_t *ids, float *scores, const GraphLds &L, const NonStall &ns,
+                     hipStream_t stream) {
     static size_t big = 0;
-    if (hipError_t e = allow_big_lds(reinterpret_cast<const void *>(&graph_search_kernel<T, RPT>), L.total, &big))
+    if (hipError_t e = allow_big_lds(reinterpret_cast<const void *>(&graph_search_kernel<T, RPT, NS>), L.total, &big))
         return e;
-    hipLaunchKernelGGL((graph_search_kernel<T, RPT>), dim3(B), dim3(GRAPH_THREADS), L.total, stream, X, N, d, graph, R,
-                       entry, Q, k, ef, ids, scores, L);
+    hipLaunchKernelGGL((graph_search_kernel<T, RPT, NS>), dim3(B), dim3(GRAPH_THREADS), L.total, stream, X, N, d,
+                       graph, R, entry, Q, k, ef, ids, scores, L, ns);
     return hipGetLastError();
 }
 
-template <class T>
+template <class T, bool NS>
 hipError_t launch(const void *X, int64_t N, int d, const int32_t *graph, int R, int entry, const void *Q, int B,
-                  int k, int ef, int32_t *ids, float *scores, const GraphLds &L, hipStream_t stream) {
-    return L.rp == 32 ? launch_rp<T, 32>(X, N, d, graph, R, entry, Q, B, k, ef, ids, scores, L, stream)
-                      : launch_rp<T, 0>(X, N, d, graph, R, entry, Q, B, k, ef, ids, scores, L, stream);
+                  int k, int ef, int32_t *ids, float *scores, const GraphLds &L, const NonStall &ns,
+                  hipStream_t stream) {
+    return L.rp == 32 ? launch_rp<T, 32, NS>(X, N, d, graph, R, entry, Q, B, k, ef, ids, scores, L, ns, stream)
+                      : launch_rp<T, 0, NS>(X, N, d, graph, R, entry, Q, B, k, ef, ids, scores, L, ns, stream);
+}
+
+template <bool NS>
+hipError_t launch_dtype(int dtype, const void *X, int64_t N, int d, const int32_t *graph, int R, int entry,
+                        const void *Q, int B, int k, int ef, int32_t *ids, float *scores, const GraphLds &L,
+                        const NonStall &ns, hipStream_t stream) {
+    switch (dtype) {
+    case 0: return launch<F16, NS>(X, N, d, graph, R, entry, Q, B, k, ef, ids, scores, L, ns, stream);
+    case 1: return launch<BF16, NS>(X, N, d, graph, R, entry, Q, B, k, ef, ids, scores, L, ns, stream);
+    default: return launch<F32, NS>(X, N, d, graph, R, entry, Q, B, k, ef, ids, scores, L, ns, stream);
+    }
 }
 }  // namespace
 
 hipError_t launch_graph_search(int dtype, const void *X, int64_t N, int d, const int32_t *graph, int R, int entry,
                                const void *Q, int B, int k, int ef, int32_t *ids, float *scores,
                                const GraphLds &L, hipStream_t stream) {
-    switch (dtype) {
-    case 0: return launch<F16>(X, N, d, graph, R, entry, Q, B, k, ef, ids, scores, L, stream);
-    case 1: return launch<BF16>(X, N, d, graph, R, entry, Q, B, k, ef, ids, scores, L, stream);
-    default: return launch<F32>(X, N, d, graph, R, entry, Q, B, k, ef, ids, scores, L, stream);
-    }
+    return launch_dtype<false>(dtype, X, N, d, graph, R, entry, Q, B, k, ef, ids, scores, L, NonStall{}, stream);
+}
+
+hipError_t launch_graph_search_nonstall(int dtype, const void *X, int64_t N, int d, const int32_t *graph, int R,
+                                        int entry, const void *Q, int B, int k, int ef, int32_t *ids, float *scores,
+                                        const GraphLds &L, const NonStall &ns, hipStream_t stream) {
+    const size_t n16 = (size_t)B * (size_t)ns.words / 4;
+    const size_t blocks = (n16 + 255) / 256;
+    hipLaunchKernelGGL(zero_words_kernel, dim3((unsigned)(blocks < 4096 ? blocks : 4096)), dim3(256), 0, stream,
+                       reinterpret_cast<u4 *>(ns.visited), n16);
+    if (hipError_t e = hipGetLastError()) return e;
+    return launch_dtype<true>(dtype, X, N, d, graph, R, entry, Q, B, k, ef, ids, scores, L, ns, stream);
 }
 
 }  // namespace ann

@@ -14,6 +14,16 @@
 // never claims an unseen node as seen (no false positives) gives identical
 // results whatever it forgets.  The id cache is such a filter; it fits LDS at any
 // corpus size, where an exact bitset (N/8 bytes per query) does not.
+//
+// Maturity (non-stall) exit, Section 3.3 and Appendix B.2: every newly scored node t gives
+// RQ_t = (d_t - d_best) / (d_worst - d_best) against the best and worst list entries, the
+// values are smoothed by an exponential moving average, and the search returns its current
+// list once the average exceeds tau and the engine-ready word is non-zero.  Here the
+// neighbours of one expansion form a batch: best and worst are those of the list as the
+// expansion starts, samples enter the average in slot order, the test follows the merge.
+// The sample stream must not contain re-scored nodes, so this variant backs the id cache
+// with an exact per-query bitset in global memory (one atomic OR per candidate, issued
+// together with the row loads so it adds no round trip of its own).
 #pragma once
 
 #include "common.hpp"
@@ -42,11 +52,12 @@ __device__ __forceinline__ int list_lower_bound(const float *s, const uint32_t *
 // RPT: number of graph slots rounded up to 32 when it is known at compile time (32 for
 // R <= 32: the short loops over the scored neighbours are then fully unrolled and their
 // LDS reads issued together), 0 = taken from the layout at run time.
-template <class T, int RPT>
+// NS: with the maturity exit (parameters in `ns`, ignored otherwise).
+template <class T, int RPT, bool NS>
 __global__ __launch_bounds__(GRAPH_THREADS) void graph_search_kernel(
     const void *__restrict__ X, int64_t N, int d, const int32_t *__restrict__ graph, int R, int entry,
     const void *__restrict__ Q, int k, int ef, int32_t *__restrict__ ids, float *__restrict__ scores,
-    GraphLds L) {
+    GraphLds L, NonStall ns) {
     extern __shared__ __align__(16) unsigned char smem[];
     u4 *qs = reinterpret_cast<u4 *>(smem + L.q);
     float *ls[2] = {reinterpret_cast<float *>(smem + L.ls0), reinterpret_cast<float *>(smem + L.ls1)};
@@ -58,12 +69,15 @@ __global__ __launch_bounds__(GRAPH_THREADS) void graph_search_kernel(
     int *adj = reinterpret_cast<int *>(smem + L.adj);     // [2][RMAX_LDS] adjacency rows read ahead
     int *adj_id = reinterpret_cast<int *>(smem + L.ctl);  // [2] whose rows they are
     uint64_t *um = reinterpret_cast<uint64_t *>(smem + L.um);   // [ef/64] "unexpanded" bit masks
+    float *rq = reinterpret_cast<float *>(smem + L.rq);   // RQ of each scored neighbour, NaN = no sample
+    int *co = reinterpret_cast<int *>(smem + L.co);       // the valid ids of the adjacency row as read
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int b = blockIdx.x;
     const int nch = d * T::bytes / 16;                    // 16-byte chunks per row
     const int RP = RPT ? RPT : (int)L.rp;
     const uint32_t cache_shift = 32u - L.cache_bits;
+    uint32_t *seen_bits = NS ? ns.visited + (size_t)b * ns.words : nullptr;   // zero on entry
 
     for (int c = tid; c < nch; c += GRAPH_THREADS)
         qs[c] = load_chunk(static_cast<const char *>(Q) + ((size_t)b * nch + c) * 16);
@@ -105,6 +119,7 @@ __global__ __launch_bounds__(GRAPH_THREADS) void graph_search_kernel(
             ls[0][0] = s;
             li[0][0] = (uint32_t)entry;
             cache[((uint32_t)entry * 2654435761u) >> cache_shift] = entry;
+            if (NS) atomicOr(&seen_bits[entry >> 5], 1u << (entry & 31));
         }
     }
     __syncthreads();
@@ -115,8 +130,11 @@ __global__ __launch_bounds__(GRAPH_THREADS) void graph_search_kernel(
 
     int cur = 0, len = 1;
     int p = 0, p2 = -1;                                   // best and second-best unexpanded entries
+    float ema = 0.f;                                      // identical in every thread
+    int n_dist = 1, n_expand = 0, early = 0;
     for (;;) {
         if (p < 0) break;                                 // nothing left to expand: natural stop
+        ++n_expand;
         const int node = (int)(li[cur][p] & ~EXPANDED);
         const int node2 = p2 >= 0 ? (int)(li[cur][p2] & ~EXPANDED) : -1;
         const int have = adj_id[0] == node ? 0 : (adj_id[1] == node ? 1 : -1);
@@ -143,9 +161,19 @@ __global__ __launch_bounds__(GRAPH_THREADS) void graph_search_kernel(
                 }
                 fresh = __shfl(fresh, lane & ~(LANES_PER_ROW - 1));
             }
+            uint32_t seen = 0;
+            if (NS && fresh && sub == 0) seen = atomicOr(&seen_bits[v >> 5], 1u << (v & 31));
             float s = 0.f;
             if (fresh) s = score_row(v);
-            if (sub == 0) { cs[slot] = s; ci[slot] = fresh ? v : -1; }
+            if (NS) {                                     // the cache may have forgotten v: the bitset has not
+                seen = __shfl(seen, lane & ~(LANES_PER_ROW - 1));
+                if (fresh && ((seen >> (v & 31)) & 1u)) fresh = 0;
+            }
+            if (sub == 0) {
+                cs[slot] = s;
+                ci[slot] = fresh ? v : -1;
+                if (NS) co[slot] = (unsigned)v < (unsigned)N ? v : -1;
+            }
         }
         if (!have2) {                                     // keep the row of `node` if it is in a slot
             const int into = have == 0 ? 1 : 0;
@@ -170,8 +198,32 @@ __global__ __launch_bounds__(GRAPH_THREADS) void graph_search_kernel(
                 }
             }
             cpos[i] = pos;
+            if (NS) {
+                // best / worst of the list as it stands before this expansion's entries go in
+                const float s_best = ls[cur][0], s_worst = ls[cur][len - 1];
+                // An id named twice in one pass is scored once, by whichever slot won the race
+                // for the visited bit; its sample belongs to the first slot that names it.
+                const int me = co[i], pass0 = i & ~(ROWS_PER_PASS - 1);
+                bool first = me >= 0, scored = false;
+                float sv = 0.f;
+#pragma unroll
+                for (int jj = 0; jj < ROWS_PER_PASS; ++jj) {
+                    const int j = pass0 + jj;
+                    if (j < i && co[j] == me) first = false;
+                    if (ci[j] == me) { scored = true; sv = cs[j]; }
+                }
+                rq[i] = (first && scored && s_best != s_worst) ? (s_best - sv) / (s_best - s_worst) : NAN;
+            }
         }
         __syncthreads();
+        if (NS) {
+#pragma unroll
+            for (int i = 0; i < RP; ++i) {
+                const float r = rq[i];
+                if (r == r) ema = fmaf(ns.alpha, r - ema, ema);
+                n_dist += (ci[i] >= 0);
+            }
+        }
 
         // merge into the other buffer: new entries at pos + (rank among new entries),
         // old entry j moves down by the number of new entries that precede it
@@ -220,6 +272,15 @@ __global__ __launch_bounds__(GRAPH_THREADS) void graph_search_kernel(
                 if (p < 0) p = j; else p2 = j;
             }
         }
+        if (NS && ema > ns.tau) {                         // mature: leave as soon as the engine is ready
+            int ready = 1;
+            if (ns.ready) {
+                if (tid == 0) adj_id[2] = __hip_atomic_load(ns.ready, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+                __syncthreads();
+                ready = adj_id[2];
+            }
+            if (ready) { early = 1; break; }
+        }
     }
 
     for (int j = tid; j < k; j += GRAPH_THREADS) {
@@ -227,6 +288,20 @@ __global__ __launch_bounds__(GRAPH_THREADS) void graph_search_kernel(
         ids[(size_t)b * k + j] = has ? (int)(li[cur][j] & ~EXPANDED) : -1;
         scores[(size_t)b * k + j] = has ? ls[cur][j] : -INFINITY;
     }
+    if (NS && tid == 0) {
+        if (ns.stats) {
+            ns.stats[(size_t)b * 3 + 0] = early;
+            ns.stats[(size_t)b * 3 + 1] = n_dist;
+            ns.stats[(size_t)b * 3 + 2] = n_expand;
+        }
+        if (ns.ema) ns.ema[b] = ema;
+    }
+}
+
+// words[0 .. n) <- 0, 16 bytes per store (n a multiple of 4)
+__global__ __launch_bounds__(256) void zero_words_kernel(u4 *__restrict__ p, size_t n16) {
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += (size_t)gridDim.x * blockDim.x)
+        p[i] = zero_chunk();
 }
 
 }  // namespace ann

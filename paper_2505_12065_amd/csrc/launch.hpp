@@ -49,13 +49,27 @@ hipError_t launch_flat_merge(int kp, const Cand *partial, int P, int B, int k, i
 
 struct GraphLds {
     // byte offsets into dynamic LDS; all 16-byte aligned
-    uint32_t q, ls0, ls1, li0, li1, cs, ci, cpos, cache, ctl, adj, um, total;
+    uint32_t q, ls0, ls1, li0, li1, cs, ci, cpos, cache, ctl, adj, um, rq, co, total;
     uint32_t cache_bits, rp;
+};
+// Maturity exit of the graph search (Section 3.3, Appendix B.2): leave once the moving
+// average of RQ exceeds tau and *ready != 0 (ready == nullptr: always ready).
+struct NonStall {
+    float tau, alpha;
+    const int32_t *ready;     // device-visible word the host may change while the kernel runs
+    uint32_t *visited;        // [B][words] bitset, zero on entry
+    int64_t words;            // words per query, a multiple of 4
+    int32_t *stats;           // [B][3] = (early exit, scored nodes, expansions), may be null
+    float *ema;               // [B] final moving average, may be null
 };
 GraphLds graph_lds_layout(int d, int elem_bytes, int R, int ef);
 // dtype: ANN_F16 / ANN_BF16 / ANN_F32 codes 0 / 1 / 2
 hipError_t launch_graph_search(int dtype, const void *X, int64_t N, int d, const int32_t *graph, int R, int entry,
                                const void *Q, int B, int k, int ef, int32_t *ids, float *scores,
                                const GraphLds &L, hipStream_t stream);
+// Same with the maturity exit; clears ns.visited (B * ns.words words) first.
+hipError_t launch_graph_search_nonstall(int dtype, const void *X, int64_t N, int d, const int32_t *graph, int R,
+                                        int entry, const void *Q, int B, int k, int ef, int32_t *ids, float *scores,
+                                        const GraphLds &L, const NonStall &ns, hipStream_t stream);
 
 }  // namespace ann

@@ -61,5 +61,33 @@ def compare_topk(g_ids, g_sc, o_ids, o_sc64, corpus_np, queries_np, dtype=None, 
     return strict, B - strict, B
 
 
+def compare_nonstall(gpu, o, xn, gn, qn, name, entry, k, ef, tau, window, max_off=None):
+    """GPU (ids, scores, stats, ema) against the oracle's non-stall result (ids, sc, sc64, stats, ema).
+    Queries with the same (early, scored, expansions) are compared list by list.  A query that
+    left at another expansion made a borderline decision (the moving averages sit at tau): its
+    list must be the oracle's list cut after the GPU's number of expansions.
+    Returns (n_same, n_off)."""
+    ids, sc, stats, ema = gpu
+    o_ids, _, o_sc64, o_stats, o_ema = o
+    B = qn.shape[0]
+    same = [b for b in range(B) if stats[b].tolist() == o_stats[b].tolist()]
+    off = [b for b in range(B) if stats[b].tolist() != o_stats[b].tolist()]
+    if same:
+        compare_topk(ids[same], sc[same], o_ids[same], o_sc64[same], xn, qn, dtype=name, rows=same)
+        # RQ divides by (best - worst), which amplifies the last-bit differences of the scores
+        assert np.allclose(ema[same], o_ema[same], rtol=5e-4, atol=5e-4)
+    for b in off:
+        cut = oracle.graph_search_nonstall(xn, gn, entry, qn[b:b + 1], k, ef, tau=np.inf, window=window,
+                                           max_expand=int(stats[b, 2]), dtype=name)
+        compare_topk(ids[b:b + 1], sc[b:b + 1], cut[0], cut[2], xn, qn, dtype=name, rows=[b])
+        assert cut[3][0, 1] == stats[b, 1], (b, cut[3], stats[b])
+        assert abs(float(cut[4][0]) - float(ema[b])) < 5e-4 * (1 + abs(float(ema[b])))
+        assert abs(float(ema[b]) - tau) < 2e-3 or abs(float(o_ema[b]) - tau) < 2e-3, (b, ema[b], o_ema[b], tau)
+    if max_off is None:
+        max_off = max(1, B // 50)
+    assert len(off) <= max_off, (len(off), B)
+    return len(same), len(off)
+
+
 def recall(approx_ids, exact_ids):
     return oracle.recall_at_k(np.asarray(approx_ids), np.asarray(exact_ids))

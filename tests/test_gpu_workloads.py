@@ -11,7 +11,7 @@ import torch
 import oracle
 import paper_2505_12065_amd as ann
 from paper_2505_12065_amd import synth
-from parity import compare_topk, recall
+from parity import compare_nonstall, compare_topk, recall
 
 pytestmark = [pytest.mark.gpu, pytest.mark.timeout(900)]
 DEV = "cuda:0"
@@ -104,6 +104,23 @@ def test_cfg2_graph_full_size(cfg1, cfg2, ef):
         say(f"cfg2 graph ef={ef} B={B}: strict={strict}/{n} tolerant={tolerant} "
             f"recall@3={recall(ids.cpu().numpy(), exact[:B]):.3f} n_dist={nd.mean():.0f} n_expand={ne.mean():.0f}")
         assert strict >= n - max(1, n // 100)
+
+
+@pytest.mark.parametrize("ef,tau,window", [(64, 0.9, 500), (256, 0.9, 500), (64, 3.0, 500)])
+def test_cfg2_graph_nonstall_full_size(cfg1, cfg2, ef, tau, window):
+    """Maturity exit (Section 3.3) on the configuration-2 graph, all 512 queries."""
+    c, q, xh = cfg1
+    g, gh, entry, exact = cfg2
+    qh = q.cpu().numpy()
+    gpu = ann.ann_graph_search_nonstall_typed(c.x, g, entry, q, K, ef, tau=tau, window=window)
+    torch.cuda.synchronize()
+    gpu = [t.cpu().numpy() for t in gpu]
+    o = oracle.graph_search_nonstall(xh, gh, entry, qh, K, ef, tau=tau, window=window)
+    n_same, n_off = compare_nonstall(gpu, o, xh, gh, qh, "f16", entry, K, ef, tau, window)
+    nat = oracle.graph_search(xh, gh, entry, qh, K, ef)
+    say(f"cfg2 non-stall ef={ef} tau={tau} window={window}: same decision {n_same}/512, early exits "
+        f"{int(gpu[2][:, 0].sum())}, expansions {gpu[2][:, 2].mean():.1f} (natural stop {nat[4].mean():.1f}), "
+        f"recall@3 {recall(gpu[0], exact):.3f} (natural stop {recall(nat[0], exact):.3f})")
 
 
 # ------------------------------------------------------------------ configuration 3 (21 M x 768, 32 GB)
