@@ -124,6 +124,26 @@ int ann_graph_search(const void *corpus, const int32_t *graph, int32_t R, int32_
                      const void *queries, int32_t B, int32_t k, int32_t ef,
                      int32_t *ids, float *scores, void *stream);
 
+/* ann_graph_search_typed with one entry node per query (Section 2.1: graph-based
+ * approximate retrieval; the entry is where the best-first search starts, so a caller
+ * with a coarse index, e.g. one representative per cluster found by ann_flat_search
+ * over the representatives, starts each query next to its answer).
+ *
+ *   entries   device, [B] int32 node ids.  A query whose entry is not in [0, N) gets
+ *             k padding results (id -1, score -inf); that is not an error.
+ */
+int ann_graph_search_entries_typed(const void *corpus, int64_t N, int32_t d, int32_t dtype,
+                                   const int32_t *graph, int32_t R, const int32_t *entries,
+                                   const void *queries, int32_t B, int32_t k, int32_t ef,
+                                   int32_t *ids, float *scores, void *stream);
+
+/* out[i] = table[idx[i]] for i in [0, n), or -1 where idx[i] is not in [0, M): turns the
+ * row numbers a search over a sub-matrix returns (representatives, a shard) into node ids,
+ * e.g. into the `entries` above.  All three arrays device, int32; out may not alias idx
+ * or table. */
+int ann_gather_ids(const int32_t *table, int64_t M, const int32_t *idx, int64_t n,
+                   int32_t *out, void *stream);
+
 /* Approximate retrieval with the maturity (non-stall) exit (Section 3.3 "Non-Stall
  * Retrieval", Appendix B.2 "Retrieval Maturity Estimation").  The search of
  * ann_graph_search_typed, with one addition.  Every newly scored node t yields
@@ -136,6 +156,8 @@ int ann_graph_search(const void *corpus, const int32_t *graph, int32_t R, int32_
  * with an undefined RQ (best == worst) are skipped, the test follows the expansion.
  * RQ and the average are binary32.
  *
+ *   entries        NULL, or device [B] per-query entry nodes used instead of `entry`
+ *                  (as in ann_graph_search_entries_typed)
  *   tau, window    threshold and EMA window (the paper uses 0.9 and 500); window >= 1
  *   engine_ready   device-visible int32 (device memory or pinned host memory) the host
  *                  may change while the call runs; read with system scope each time a
@@ -151,7 +173,8 @@ int ann_graph_search(const void *corpus, const int32_t *graph, int32_t R, int32_
 int ann_graph_search_nonstall_typed(const void *corpus, int64_t N, int32_t d, int32_t dtype,
                                     const int32_t *graph, int32_t R, int32_t entry,
                                     const void *queries, int32_t B, int32_t k, int32_t ef,
-                                    float tau, int32_t window, const int32_t *engine_ready,
+                                    const int32_t *entries, float tau, int32_t window,
+                                    const int32_t *engine_ready,
                                     int32_t *ids, float *scores, int32_t *stats, float *ema,
                                     void *stream);
 

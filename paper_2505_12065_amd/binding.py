@@ -22,7 +22,8 @@ _DTYPES = {torch.float16: ANN_F16, torch.bfloat16: ANN_BF16, torch.float32: ANN_
 EXPORTS = ("ann_version", "ann_last_error", "ann_flat_search_typed", "ann_flat_search",
            "ann_graph_search_typed", "ann_graph_search", "ann_register_corpus", "ann_unregister_corpus",
            "ann_set_default_dtype", "ann_flat_workspace_bytes", "ann_release_workspace",
-           "ann_graph_search_nonstall_typed", "ann_graph_nonstall_workspace_bytes")
+           "ann_graph_search_nonstall_typed", "ann_graph_nonstall_workspace_bytes",
+           "ann_graph_search_entries_typed", "ann_gather_ids")
 
 
 class AnnError(RuntimeError):
@@ -56,8 +57,10 @@ def lib() -> ctypes.CDLL:
         L.ann_set_default_dtype.argtypes = [i32]
         L.ann_flat_workspace_bytes.argtypes = [i64, i32, i32, i32, i32]
         L.ann_flat_workspace_bytes.restype = i64
-        L.ann_graph_search_nonstall_typed.argtypes = [vp, i64, i32, i32, vp, i32, i32, vp, i32, i32, i32,
+        L.ann_graph_search_nonstall_typed.argtypes = [vp, i64, i32, i32, vp, i32, i32, vp, i32, i32, i32, vp,
                                                       c.c_float, i32, vp, vp, vp, vp, vp, vp]
+        L.ann_graph_search_entries_typed.argtypes = [vp, i64, i32, i32, vp, i32, vp, vp, i32, i32, i32, vp, vp, vp]
+        L.ann_gather_ids.argtypes = [vp, i64, vp, i64, vp, vp]
         L.ann_graph_nonstall_workspace_bytes.argtypes = [i64, i32]
         L.ann_graph_nonstall_workspace_bytes.restype = i64
         for name in EXPORTS:
@@ -157,8 +160,8 @@ def ann_graph_search_typed(corpus: torch.Tensor, graph: torch.Tensor, entry: int
 
 
 def ann_graph_search_nonstall_typed(corpus: torch.Tensor, graph: torch.Tensor, entry: int, queries: torch.Tensor,
-                                    k: int, ef: int, *, tau: float = 0.9, window: int = 500,
-                                    engine_ready: Optional[torch.Tensor] = None, ids=None, scores=None,
+                                    k: int, ef: int, *, entries: Optional[torch.Tensor] = None, tau: float = 0.9,
+                                    window: int = 500, engine_ready: Optional[torch.Tensor] = None, ids=None, scores=None,
                                     stats=None, ema=None, stream=None):
     """Graph search with the maturity (non-stall) exit.  `engine_ready` is an int32 tensor of one
     element on the device or in pinned host memory (None = always ready).  Returns
@@ -177,6 +180,9 @@ def ann_graph_search_nonstall_typed(corpus: torch.Tensor, graph: torch.Tensor, e
         raise ValueError("stats must be a contiguous int32 [B, 3] device tensor")
     if ema.dtype != torch.float32 or tuple(ema.shape) != (B,) or not ema.is_contiguous() or not ema.is_cuda:
         raise ValueError("ema must be a contiguous float32 [B] device tensor")
+    entries_ptr = 0
+    if entries is not None:
+        entries_ptr = _entries(entries, B).data_ptr()
     ready_ptr = 0
     if engine_ready is not None:
         if engine_ready.dtype != torch.int32 or engine_ready.numel() != 1 or \
@@ -186,10 +192,50 @@ def ann_graph_search_nonstall_typed(corpus: torch.Tensor, graph: torch.Tensor, e
     with torch.cuda.device(corpus.device):
         _check(lib().ann_graph_search_nonstall_typed(corpus.data_ptr(), N, d, _DTYPES[corpus.dtype], graph.data_ptr(),
                                                      graph.shape[1], int(entry), queries.data_ptr(), B, k, ef,
-                                                     float(tau), int(window), ready_ptr, ids.data_ptr(),
+                                                     entries_ptr, float(tau), int(window), ready_ptr, ids.data_ptr(),
                                                      scores.data_ptr(), stats.data_ptr(), ema.data_ptr(),
                                                      _stream(stream)))
     return ids, scores, stats, ema
+
+
+def _entries(entries: torch.Tensor, B: int) -> torch.Tensor:
+    if entries.dtype != torch.int32 or tuple(entries.shape) != (B,) or not entries.is_contiguous() or \
+            not entries.is_cuda:
+        raise ValueError("entries must be a contiguous int32 [B] device tensor")
+    return entries
+
+
+def ann_graph_search_entries_typed(corpus: torch.Tensor, graph: torch.Tensor, entries: torch.Tensor,
+                                   queries: torch.Tensor, k: int, ef: int, *, ids=None, scores=None,
+                                   stream=None) -> Tuple[torch.Tensor, torch.Tensor]:
+    """Graph search with one entry node per query."""
+    _matrix(corpus, "corpus"), _matrix(queries, "queries")
+    if queries.dtype != corpus.dtype or queries.shape[1] != corpus.shape[1]:
+        raise ValueError("queries must have the corpus' element type and dimension")
+    (N, d), B = corpus.shape, queries.shape[0]
+    _graph(graph, N)
+    _entries(entries, B)
+    ids, scores = _outputs(B, k, corpus.device, ids, scores)
+    with torch.cuda.device(corpus.device):
+        _check(lib().ann_graph_search_entries_typed(corpus.data_ptr(), N, d, _DTYPES[corpus.dtype], graph.data_ptr(),
+                                                    graph.shape[1], entries.data_ptr(), queries.data_ptr(), B, k, ef,
+                                                    ids.data_ptr(), scores.data_ptr(), _stream(stream)))
+    return ids, scores
+
+
+def ann_gather_ids(table: torch.Tensor, idx: torch.Tensor, *, out=None, stream=None) -> torch.Tensor:
+    """out[i] = table[idx[i]] (-1 where idx[i] is out of range); int32 device tensors."""
+    for t in (table, idx):
+        if t.dtype != torch.int32 or not t.is_contiguous() or not t.is_cuda:
+            raise ValueError("table and idx must be contiguous int32 device tensors")
+    if out is None:
+        out = torch.empty_like(idx)
+    if out.dtype != torch.int32 or out.shape != idx.shape or not out.is_contiguous() or not out.is_cuda:
+        raise ValueError("out must be a contiguous int32 device tensor shaped like idx")
+    with torch.cuda.device(table.device):
+        _check(lib().ann_gather_ids(table.data_ptr(), table.numel(), idx.data_ptr(), idx.numel(), out.data_ptr(),
+                                    _stream(stream)))
+    return out
 
 
 def ann_graph_nonstall_workspace_bytes(N: int, B: int) -> int:

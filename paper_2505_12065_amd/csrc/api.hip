@@ -295,10 +295,13 @@ int64_t ann_graph_nonstall_workspace_bytes(int64_t N, int32_t B) {
 
 int ann_graph_search_nonstall_typed(const void *corpus, int64_t N, int32_t d, int32_t dtype, const int32_t *graph,
                                     int32_t R, int32_t entry, const void *queries, int32_t B, int32_t k, int32_t ef,
-                                    float tau, int32_t window, const int32_t *engine_ready, int32_t *ids,
-                                    float *scores, int32_t *stats, float *ema, void *stream) {
+                                    const int32_t *entries, float tau, int32_t window,
+                                    const int32_t *engine_ready, int32_t *ids, float *scores, int32_t *stats,
+                                    float *ema, void *stream) {
     GraphLds L;
-    if (int rc = check_graph(corpus, N, d, dtype, graph, R, entry, queries, B, k, ef, ids, scores, &L)) return rc;
+    if (int rc = check_graph(corpus, N, d, dtype, graph, R, entries ? 0 : entry, queries, B, k, ef, ids, scores, &L))
+        return rc;
+    if (reinterpret_cast<uintptr_t>(entries) & 3) return fail(ANN_ERR_ALIGNMENT, "entries must be 4-byte aligned");
     if (window < 1) return fail(ANN_ERR_INVALID, "window = %d must be at least 1", window);
     if (tau != tau) return fail(ANN_ERR_INVALID, "tau is not a number");
     if ((reinterpret_cast<uintptr_t>(engine_ready) | reinterpret_cast<uintptr_t>(stats) |
@@ -308,6 +311,7 @@ int ann_graph_search_nonstall_typed(const void *corpus, int64_t N, int32_t d, in
     DeviceState *st = nullptr;
     if (int rc = device_state(&st)) return rc;
     NonStall ns;
+    ns.entries = entries;
     ns.tau = tau;
     ns.alpha = 2.0f / ((float)window + 1.0f);
     ns.ready = engine_ready;
@@ -329,8 +333,30 @@ int ann_graph_search_typed(const void *corpus, int64_t N, int32_t d, int32_t dty
     if (int rc = check_graph(corpus, N, d, dtype, graph, R, entry, queries, B, k, ef, ids, scores, &L)) return rc;
     std::lock_guard<std::mutex> lock(g_mu);
     hipStream_t s = static_cast<hipStream_t>(stream);
-    return check_launch("graph_search_kernel",
-                        launch_graph_search(dtype, corpus, N, d, graph, R, entry, queries, B, k, ef, ids, scores, L, s));
+    return check_launch("graph_search_kernel", launch_graph_search(dtype, corpus, N, d, graph, R, entry, nullptr,
+                                                                   queries, B, k, ef, ids, scores, L, s));
+}
+
+int ann_graph_search_entries_typed(const void *corpus, int64_t N, int32_t d, int32_t dtype, const int32_t *graph,
+                                   int32_t R, const int32_t *entries, const void *queries, int32_t B, int32_t k,
+                                   int32_t ef, int32_t *ids, float *scores, void *stream) {
+    if (!entries) return fail(ANN_ERR_INVALID, "null entries pointer");
+    if (reinterpret_cast<uintptr_t>(entries) & 3) return fail(ANN_ERR_ALIGNMENT, "entries must be 4-byte aligned");
+    GraphLds L;
+    if (int rc = check_graph(corpus, N, d, dtype, graph, R, 0, queries, B, k, ef, ids, scores, &L)) return rc;
+    std::lock_guard<std::mutex> lock(g_mu);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    return check_launch("graph_search_kernel", launch_graph_search(dtype, corpus, N, d, graph, R, 0, entries, queries,
+                                                                   B, k, ef, ids, scores, L, s));
+}
+
+int ann_gather_ids(const int32_t *table, int64_t M, const int32_t *idx, int64_t n, int32_t *out, void *stream) {
+    if (!table || !idx || !out) return fail(ANN_ERR_INVALID, "null pointer argument");
+    if (M < 1 || n < 1) return fail(ANN_ERR_INVALID, "M = %lld, n = %lld out of range", (long long)M, (long long)n);
+    if ((reinterpret_cast<uintptr_t>(table) | reinterpret_cast<uintptr_t>(idx) | reinterpret_cast<uintptr_t>(out)) & 3)
+        return fail(ANN_ERR_ALIGNMENT, "table, idx and out must be 4-byte aligned");
+    return check_launch("gather_ids_kernel",
+                        launch_gather_ids(table, M, idx, n, out, static_cast<hipStream_t>(stream)));
 }
 
 int ann_graph_search(const void *corpus, const int32_t *graph, int32_t R, int32_t entry, const void *queries,

@@ -8,9 +8,13 @@ GraphLds graph_lds_layout(int d, int elem_bytes, int R, int ef) {
     auto up = [](uint32_t x) { return (x + 15u) & ~15u; };
     uint32_t off = 0;
     L.rp = (uint32_t)((R + ROWS_PER_PASS - 1) / ROWS_PER_PASS * ROWS_PER_PASS);
-    // cache slots: a few times the number of nodes a search scores (about 10 ef)
+    // cache slots: a few times the number of nodes a search scores (about 10 ef), but not
+    // so many that only one workgroup fits a compute unit when two could
+    const uint32_t rest = (uint32_t)d * elem_bytes + 16u * ef + 5u * 4u * L.rp + 2u * 4u * RMAX_LDS +
+                          8u * (((uint32_t)ef + 63u) / 64u) + 512u;
     uint32_t bits = 10;
     while ((1u << bits) < 32u * (uint32_t)ef && bits < 14) ++bits;
+    while (bits > 11 && rest + (4u << bits) > LDS_MAX / 2 && rest + (4u << 11) <= LDS_MAX / 2) --bits;
     L.cache_bits = bits;
     L.q = off; off = up(off + (uint32_t)d * elem_bytes);
     L.ls0 = off; off = up(off + 4u * ef);
@@ -64,9 +68,19 @@ hipError_t launch_dtype(int dtype, const void *X, int64_t N, int d, const int32_
 }  // namespace
 
 hipError_t launch_graph_search(int dtype, const void *X, int64_t N, int d, const int32_t *graph, int R, int entry,
-                               const void *Q, int B, int k, int ef, int32_t *ids, float *scores,
-                               const GraphLds &L, hipStream_t stream) {
-    return launch_dtype<false>(dtype, X, N, d, graph, R, entry, Q, B, k, ef, ids, scores, L, NonStall{}, stream);
+                               const int32_t *entries, const void *Q, int B, int k, int ef, int32_t *ids,
+                               float *scores, const GraphLds &L, hipStream_t stream) {
+    NonStall ns{};
+    ns.entries = entries;
+    return launch_dtype<false>(dtype, X, N, d, graph, R, entry, Q, B, k, ef, ids, scores, L, ns, stream);
+}
+
+hipError_t launch_gather_ids(const int32_t *table, int64_t M, const int32_t *idx, int64_t n, int32_t *out,
+                             hipStream_t stream) {
+    const int64_t blocks = (n + 255) / 256;
+    hipLaunchKernelGGL(gather_ids_kernel, dim3((unsigned)(blocks < 1024 ? blocks : 1024)), dim3(256), 0, stream, table,
+                       M, idx, n, out);
+    return hipGetLastError();
 }
 
 hipError_t launch_graph_search_nonstall(int dtype, const void *X, int64_t N, int d, const int32_t *graph, int R,

@@ -74,6 +74,20 @@ __global__ __launch_bounds__(GRAPH_THREADS) void graph_search_kernel(
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int b = blockIdx.x;
+    if (ns.entries) {                                     // per-query entry node
+        entry = ns.entries[b];
+        if ((unsigned)entry >= (unsigned)N) {             // not a node: this query gets padding only
+            for (int j = tid; j < k; j += GRAPH_THREADS) {
+                ids[(size_t)b * k + j] = -1;
+                scores[(size_t)b * k + j] = -INFINITY;
+            }
+            if (NS && tid == 0) {
+                if (ns.stats) { ns.stats[(size_t)b * 3] = 0; ns.stats[(size_t)b * 3 + 1] = 0; ns.stats[(size_t)b * 3 + 2] = 0; }
+                if (ns.ema) ns.ema[b] = 0.f;
+            }
+            return;
+        }
+    }
     const int nch = d * T::bytes / 16;                    // 16-byte chunks per row
     const int RP = RPT ? RPT : (int)L.rp;
     const uint32_t cache_shift = 32u - L.cache_bits;
@@ -295,6 +309,16 @@ __global__ __launch_bounds__(GRAPH_THREADS) void graph_search_kernel(
             ns.stats[(size_t)b * 3 + 2] = n_expand;
         }
         if (ns.ema) ns.ema[b] = ema;
+    }
+}
+
+// out[i] <- table[idx[i]], or -1 where idx[i] is not in [0, M)
+__global__ __launch_bounds__(256) void gather_ids_kernel(const int32_t *__restrict__ table, int64_t M,
+                                                         const int32_t *__restrict__ idx, int64_t n,
+                                                         int32_t *__restrict__ out) {
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) {
+        const int32_t j = idx[i];
+        out[i] = (j >= 0 && j < M) ? table[j] : -1;
     }
 }
 

@@ -247,6 +247,72 @@ def knn_graph_cluster_restricted(corpus: Corpus, R: int, n_near: int = 8, *,
     return best_i.to(torch.int32)
 
 
+def cluster_representatives(corpus: Corpus) -> torch.Tensor:
+    """One node per non-empty cluster: the member with the largest inner product with the
+    cluster's L2-normalised centroid (ties: lower id).  int32, cluster order, corpus device.
+    A coarse index for per-query entry nodes: search the representatives' rows exactly and
+    start the graph search of a query at the best one."""
+    x = corpus.x
+    dev = x.device
+    labels = corpus.labels.to(dev).long()
+    cn = (corpus.centroids / corpus.centroids.norm(dim=1, keepdim=True)).to(dev)
+    C = cn.shape[0]
+    s = torch.empty(x.shape[0], dtype=torch.float32, device=dev)
+    for r0 in range(0, x.shape[0], _CHUNK_ROWS):
+        s[r0:r0 + _CHUNK_ROWS] = (x[r0:r0 + _CHUNK_ROWS].float() * cn[labels[r0:r0 + _CHUNK_ROWS]]).sum(1)
+    best = torch.full((C,), -math.inf, device=dev).scatter_reduce(0, labels, s, reduce="amax")
+    winners = (s == best[labels]).nonzero().flatten()            # ascending ids
+    rep = torch.full((C,), -1, dtype=torch.int64, device=dev)
+    rep.scatter_reduce_(0, labels[winners], winners, reduce="amin", include_self=False)
+    return rep[rep >= 0].to(torch.int32)
+
+
+def with_reverse_edges(graph: torch.Tensor, x: torch.Tensor, n_forward: Optional[int] = None, *,
+                       row_block: int = 8192) -> torch.Tensor:
+    """Same shape [N, R]: row j keeps its first `n_forward` (default R/2) neighbours, then takes the
+    best nodes that name j in their own row (reverse neighbours, by score desc, id asc, those already
+    kept skipped), then its remaining forward neighbours until R slots are full.  A standard way to
+    make a directed k-NN graph easier to navigate at the same degree."""
+    N, R = graph.shape
+    dev = graph.device
+    nf = R // 2 if n_forward is None else n_forward
+    g = graph.long()
+    # score of every edge i -> g[i, r]
+    sc = torch.full((N, R), -math.inf, dtype=torch.float32, device=dev)
+    for r0 in range(0, N, row_block):
+        gi = g[r0:r0 + row_block]
+        ok = gi >= 0
+        nb = x[gi.clamp(min=0)].float()                           # [rows, R, d]
+        sc[r0:r0 + row_block] = torch.where(ok, (nb * x[r0:r0 + row_block].float()[:, None, :]).sum(-1),
+                                            torch.full_like(sc[r0:r0 + row_block], -math.inf))
+    src = torch.arange(N, device=dev)[:, None].expand(N, R).reshape(-1)
+    dst, val = g.reshape(-1), sc.reshape(-1)
+    keep = dst >= 0
+    src, dst, val = src[keep], dst[keep], val[keep]                # src ascending
+    o = torch.argsort(val, descending=True, stable=True)
+    src, dst = src[o], dst[o]
+    o = torch.argsort(dst, stable=True)
+    src, dst = src[o], dst[o]                                      # by dst, then score desc, then src asc
+    counts = torch.bincount(dst, minlength=N)
+    starts = torch.cumsum(counts, 0) - counts
+    rank = torch.arange(dst.numel(), device=dev) - starts[dst]
+    top = rank < R
+    rev = torch.full((N, R), -1, dtype=torch.int64, device=dev)
+    rev[dst[top], rank[top]] = src[top]
+    out = torch.empty_like(graph)
+    for r0 in range(0, N, row_block):
+        cand = torch.cat([g[r0:r0 + row_block, :nf], rev[r0:r0 + row_block], g[r0:r0 + row_block, nf:]], 1)
+        W = cand.shape[1]
+        same = cand[:, :, None] == cand[:, None, :]                # [rows, W, W]
+        earlier = torch.tril(torch.ones(W, W, dtype=torch.bool, device=dev), diagonal=-1)
+        drop = (same & earlier).any(2) | (cand < 0)
+        o = torch.argsort(drop.to(torch.int8), dim=1, stable=True)  # kept entries first, order preserved
+        cand, drop = torch.gather(cand, 1, o), torch.gather(drop, 1, o)
+        cand = torch.where(drop, torch.full_like(cand, -1), cand)
+        out[r0:r0 + row_block] = cand[:, :R].to(graph.dtype)
+    return out
+
+
 def ring_union(graph: torch.Tensor) -> torch.Tensor:
     """Append the two ring edges i -> i±1 (mod N) to every row: a strongly
     connected test graph for the 'ef >= N equals exact search' special case."""

@@ -231,6 +231,70 @@ def test_graph_is_deterministic():
     assert torch.equal(a[0], b[0]) and torch.equal(a[1], b[1])
 
 
+@pytest.mark.parametrize("dtype", [torch.float16, torch.float32])
+def test_graph_per_query_entries(dtype):
+    """One entry node per query: each row equals the oracle started from that query's entry; an
+    entry that is not a node id yields padding."""
+    N = 8000
+    c = synth.make_corpus(N, 128, 12, seed=61, dtype=dtype, zipf_a=None, sigma=0.3)
+    q = synth.make_queries(c, 40)
+    g = synth.knn_graph(c.x, 12)
+    gen = torch.Generator().manual_seed(9)
+    entries = torch.randint(0, N, (40,), generator=gen, dtype=torch.int32)
+    entries[7], entries[21] = -1, N
+    ids, sc = ann.ann_graph_search_entries_typed(c.x.to(DEV), g.to(DEV), entries.to(DEV), q.to(DEV), 5, 40)
+    torch.cuda.synchronize()
+    ids, sc = ids.cpu().numpy(), sc.cpu().numpy()
+    xn, qn, gn = to_np(c.x), to_np(q), g.numpy()
+    strict = 0
+    for b in range(40):
+        e = int(entries[b])
+        if e < 0 or e >= N:
+            assert ids[b].tolist() == [-1] * 5 and np.isneginf(sc[b]).all()
+            continue
+        o_ids, _, o_sc64, _, _ = oracle.graph_search(xn, gn, e, qn[b:b + 1], 5, 40)
+        st, _, _ = compare_topk(ids[b:b + 1], sc[b:b + 1], o_ids, o_sc64, xn, qn, rows=[b])
+        strict += st
+    assert strict >= 37
+    # the same entry for everyone is the scalar-entry call
+    same = torch.full((40,), 11, dtype=torch.int32, device=DEV)
+    a = ann.ann_graph_search_entries_typed(c.x.to(DEV), g.to(DEV), same, q.to(DEV), 5, 40)
+    b_ = ann.ann_graph_search_typed(c.x.to(DEV), g.to(DEV), 11, q.to(DEV), 5, 40)
+    torch.cuda.synchronize()
+    assert torch.equal(a[0], b_[0]) and torch.equal(a[1], b_[1])
+
+
+def test_gather_ids():
+    gen = torch.Generator().manual_seed(4)
+    table = torch.randint(0, 1 << 30, (1000,), generator=gen, dtype=torch.int32)
+    idx = torch.randint(-5, 1005, (70_001,), generator=gen, dtype=torch.int32)
+    out = ann.ann_gather_ids(table.to(DEV), idx.to(DEV)).cpu()
+    ok = (idx >= 0) & (idx < 1000)
+    want = torch.where(ok, table[idx.clamp(0, 999).long()], torch.full_like(idx, -1))
+    assert torch.equal(out, want)
+
+
+def test_coarse_entries_then_graph_search_end_to_end():
+    """The two-level use: exact search over one representative per cluster, row numbers turned
+    into node ids, graph search from there.  Every step checked against the oracle."""
+    c = synth.make_corpus(12_000, 128, 24, seed=71, dtype=torch.float16, sigma=0.3)
+    q = synth.make_queries(c, 33)
+    g = synth.with_reverse_edges(synth.knn_graph(c.x, 16), c.x)
+    reps = synth.cluster_representatives(c)
+    xd, gd, qd = c.x.to(DEV), g.to(DEV), q.to(DEV)
+    rep_rows = xd[reps.long().to(DEV)].contiguous()
+    cid, _ = ann.ann_flat_search_typed(rep_rows, qd, 1)
+    entries = ann.ann_gather_ids(reps.to(DEV), cid.reshape(-1).contiguous())
+    ids, sc = ann.ann_graph_search_entries_typed(xd, gd, entries, qd, 3, 48)
+    torch.cuda.synchronize()
+    xn, qn, gn = c.x.numpy(), q.numpy(), g.numpy()
+    o_cid, _, _ = oracle.flat_search(xn[reps.numpy()], qn, 1)
+    assert entries.cpu().numpy().tolist() == reps.numpy()[o_cid[:, 0]].tolist()
+    for b in range(33):
+        o_ids, _, o_sc64, _, _ = oracle.graph_search(xn, gn, int(entries[b]), qn[b:b + 1], 3, 48)
+        compare_topk(ids[b:b + 1].cpu().numpy(), sc[b:b + 1].cpu().numpy(), o_ids, o_sc64, xn, qn, rows=[b])
+
+
 # ------------------------------------------------------------------ configuration 2 (graph, fp16, d = 768)
 
 @pytest.fixture(scope="module")

@@ -95,3 +95,43 @@ def test_mean_entry_and_ring():
     assert e == int((c.x.double() @ mu).argmax())
     g = synth.ring_union(torch.full((300, 2), -1, dtype=torch.int32))
     assert g.shape == (300, 4) and int(g[0, 3]) == 299 and int(g[299, 2]) == 0
+
+
+def test_cluster_representatives_match_brute_force():
+    c = synth.make_corpus(3000, 32, 6, seed=3, dtype=torch.float16, zipf_a=1.1, sigma=0.3)
+    reps = synth.cluster_representatives(c)
+    cn = c.centroids / c.centroids.norm(dim=1, keepdim=True)
+    assert reps.dtype == torch.int32 and reps.shape == (6,)
+    for ci in range(6):
+        m = (c.labels == ci).nonzero().flatten()
+        s = c.x[m].float() @ cn[ci]
+        assert int(reps[ci]) == int(m[(s == s.max()).nonzero()[0, 0]])
+
+
+def test_reverse_edge_graph_matches_brute_force():
+    c = synth.make_corpus(1500, 32, 5, seed=8, dtype=torch.float16, zipf_a=None, sigma=0.3)
+    g = synth.knn_graph(c.x, 8)
+    g[17, 5:] = -1                                  # a short row
+    h = synth.with_reverse_edges(g, c.x)
+    x, gn, hn = c.x.float().numpy(), g.numpy(), h.numpy()
+    N, R = gn.shape
+    rev = {j: [] for j in range(N)}
+    for i in range(N):
+        for j in gn[i]:
+            if j >= 0:
+                rev[int(j)].append((-float(np.float32(x[i] @ x[j])), i))
+    loose = 0
+    for j in range(N):
+        want = [int(v) for v in gn[j, :R // 2] if v >= 0]
+        for _, i in sorted(rev[j]):
+            if i not in want:
+                want.append(i)
+        for v in gn[j, R // 2:]:
+            if v >= 0 and int(v) not in want:
+                want.append(int(v))
+        want = (want + [-1] * R)[:R]
+        if want != hn[j].tolist():                  # summation order may swap near-equal reverse scores
+            assert sorted(want) == sorted(hn[j].tolist()) or len(set(want) ^ set(hn[j].tolist())) <= 2, j
+            loose += 1
+    assert loose <= N // 100
+    assert (hn[:, : R // 2] == gn[:, : R // 2])[gn[:, : R // 2] >= 0].all()
