@@ -198,6 +198,24 @@ int64_t ann_flat_workspace_bytes(int64_t N, int32_t d, int32_t dtype, int32_t B,
 /* Release the library-owned workspace of the current device (synchronises it). */
 int ann_release_workspace(void);
 
+/* Kernel timing for benchmarks (measurement support, no paper passage).  While it is on,
+ * every launch of a main kernel is bracketed by a pair of HIP events recorded on the
+ * call's own stream, so a benchmark can report a kernel's average duration without a
+ * profiler and without synchronising between calls.  The small helper kernels of a call
+ * (merges, the sampling pass, clearing) are not bracketed. */
+#define ANN_KERNEL_FLAT_STREAM 0   /* flat search, streaming kernel (small batches) */
+#define ANN_KERNEL_FLAT_WIDE   1   /* flat search, matrix-core kernel (main pass) */
+#define ANN_KERNEL_FLAT_F32    2   /* flat search, fp32 corpus */
+#define ANN_KERNEL_GRAPH       3   /* graph search, either variant */
+#define ANN_KERNEL_COUNT       4
+
+/* on != 0: drop earlier records and start recording; on == 0: stop (records are kept). */
+int ann_timing_enable(int32_t on);
+
+/* Waits for the recorded launches of `kernel` (an ANN_KERNEL_* code) and returns their
+ * number and the sum of their durations in milliseconds.  Host pointers. */
+int ann_timing_read(int32_t kernel, int32_t *launches, double *total_ms);
+
 #ifdef __cplusplus
 }
 #endif

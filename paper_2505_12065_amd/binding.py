@@ -23,7 +23,7 @@ EXPORTS = ("ann_version", "ann_last_error", "ann_flat_search_typed", "ann_flat_s
            "ann_graph_search_typed", "ann_graph_search", "ann_register_corpus", "ann_unregister_corpus",
            "ann_set_default_dtype", "ann_flat_workspace_bytes", "ann_release_workspace",
            "ann_graph_search_nonstall_typed", "ann_graph_nonstall_workspace_bytes",
-           "ann_graph_search_entries_typed", "ann_gather_ids")
+           "ann_graph_search_entries_typed", "ann_gather_ids", "ann_timing_enable", "ann_timing_read")
 
 
 class AnnError(RuntimeError):
@@ -61,6 +61,8 @@ def lib() -> ctypes.CDLL:
                                                       c.c_float, i32, vp, vp, vp, vp, vp, vp]
         L.ann_graph_search_entries_typed.argtypes = [vp, i64, i32, i32, vp, i32, vp, vp, i32, i32, i32, vp, vp, vp]
         L.ann_gather_ids.argtypes = [vp, i64, vp, i64, vp, vp]
+        L.ann_timing_enable.argtypes = [i32]
+        L.ann_timing_read.argtypes = [i32, c.POINTER(i32), c.POINTER(c.c_double)]
         L.ann_graph_nonstall_workspace_bytes.argtypes = [i64, i32]
         L.ann_graph_nonstall_workspace_bytes.restype = i64
         for name in EXPORTS:
@@ -236,6 +238,20 @@ def ann_gather_ids(table: torch.Tensor, idx: torch.Tensor, *, out=None, stream=N
         _check(lib().ann_gather_ids(table.data_ptr(), table.numel(), idx.data_ptr(), idx.numel(), out.data_ptr(),
                                     _stream(stream)))
     return out
+
+
+KERNEL_FLAT_STREAM, KERNEL_FLAT_WIDE, KERNEL_FLAT_F32, KERNEL_GRAPH = 0, 1, 2, 3
+
+
+def ann_timing_enable(on: bool) -> None:
+    _check(lib().ann_timing_enable(1 if on else 0))
+
+
+def ann_timing_read(kernel: int) -> Tuple[int, float]:
+    """(launches, total milliseconds) of the main kernel `kernel` since timing was switched on."""
+    n, ms = ctypes.c_int32(0), ctypes.c_double(0.0)
+    _check(lib().ann_timing_read(kernel, ctypes.byref(n), ctypes.byref(ms)))
+    return n.value, ms.value
 
 
 def ann_graph_nonstall_workspace_bytes(N: int, B: int) -> int:

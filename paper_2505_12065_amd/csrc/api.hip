@@ -9,6 +9,7 @@
 #include <mutex>
 #include <string>
 #include <unordered_map>
+#include <vector>
 
 #include "../../include/ann.h"
 #include "launch.hpp"
@@ -75,6 +76,40 @@ int ensure_workspace(DeviceState *st, size_t bytes) { return grow(&st->ws, &st->
 
 // words of one query's visited bitset: one bit per node, rounded to 16-byte units
 int64_t visited_words(int64_t N) { return (N + 511) / 512 * 16; }
+
+// ---- optional event timing of the main kernels -----------------------------------------------
+struct TimedLaunch { hipEvent_t a, b; int kernel; };
+bool g_timing = false;
+std::vector<TimedLaunch> g_timed;          // records of the current session
+std::vector<hipEvent_t> g_event_pool;      // events of earlier sessions, reused
+
+hipEvent_t pooled_event() {
+    if (!g_event_pool.empty()) {
+        hipEvent_t e = g_event_pool.back();
+        g_event_pool.pop_back();
+        return e;
+    }
+    hipEvent_t e = nullptr;
+    if (hipEventCreate(&e) != hipSuccess) { (void)hipGetLastError(); return nullptr; }
+    return e;
+}
+
+// Brackets a launch with events while timing is on (caller holds g_mu).
+struct TimedScope {
+    hipStream_t stream;
+    int index = -1;
+    TimedScope(int kernel, hipStream_t s) : stream(s) {
+        if (!g_timing) return;
+        TimedLaunch t{pooled_event(), pooled_event(), kernel};
+        if (!t.a || !t.b) return;
+        if (hipEventRecord(t.a, stream) != hipSuccess) { (void)hipGetLastError(); return; }
+        g_timed.push_back(t);
+        index = (int)g_timed.size() - 1;
+    }
+    ~TimedScope() {
+        if (index >= 0 && hipEventRecord(g_timed[index].b, stream) != hipSuccess) (void)hipGetLastError();
+    }
+};
 
 int check_launch(const char *what, hipError_t e) {
     if (e != hipSuccess) {
@@ -169,8 +204,12 @@ FlatPlan flat_plan(int cus, int64_t N, int d, int dtype, int B, int k) {
 int flat_search_run(const FlatPlan &pl, const void *X, int64_t N, int d, int dtype, const void *Q, int B, int k,
                     int32_t *ids, float *scores, Cand *partial, hipStream_t stream) {
     if (dtype == ANN_F32) {
-        hipError_t e = launch_flat_f32(pl.kp, static_cast<const float *>(X), N, d, static_cast<const float *>(Q), B,
-                                       partial, pl.P, stream);
+        hipError_t e;
+        {
+            TimedScope timed(ANN_KERNEL_FLAT_F32, stream);
+            e = launch_flat_f32(pl.kp, static_cast<const float *>(X), N, d, static_cast<const float *>(Q), B, partial,
+                                pl.P, stream);
+        }
         if (int rc = check_launch("flat_f32_kernel", e)) return rc;
     } else if (pl.wide_ntg > 0) {
         const float *thr0 = nullptr;
@@ -184,16 +223,23 @@ int flat_search_run(const FlatPlan &pl, const void *X, int64_t N, int d, int dty
             if (int rc = check_launch("flat_sample_merge_kernel", e)) return rc;
             thr0 = thr;
         }
-        hipError_t e = launch_flat_wide(dtype, false, X, N, d, Q, B, partial, pl.P, pl.wide_ntg, pl.sample_tiles,
-                                        thr0, pl.pstride, 0, stream);
+        hipError_t e;
+        {
+            TimedScope timed(ANN_KERNEL_FLAT_WIDE, stream);
+            e = launch_flat_wide(dtype, false, X, N, d, Q, B, partial, pl.P, pl.wide_ntg, pl.sample_tiles, thr0,
+                                 pl.pstride, 0, stream);
+        }
         if (int rc = check_launch("flat_wide_kernel", e)) return rc;
     } else {
         for (int q0 = 0; q0 < B; q0 += 16 * pl.nqg_max) {
             const int left = B - q0;
             const int nqg = left > 16 * pl.nqg_max ? pl.nqg_max : (left + 15) / 16;
-            hipError_t e = dtype == ANN_F16
-                               ? launch_flat_stream_f16(nqg, pl.kp, X, N, d, Q, B, q0, partial, pl.P, stream)
-                               : launch_flat_stream_bf16(nqg, pl.kp, X, N, d, Q, B, q0, partial, pl.P, stream);
+            hipError_t e;
+            {
+                TimedScope timed(ANN_KERNEL_FLAT_STREAM, stream);
+                e = dtype == ANN_F16 ? launch_flat_stream_f16(nqg, pl.kp, X, N, d, Q, B, q0, partial, pl.P, stream)
+                                     : launch_flat_stream_bf16(nqg, pl.kp, X, N, d, Q, B, q0, partial, pl.P, stream);
+            }
             if (int rc = check_launch("flat_stream_kernel", e)) return rc;
         }
     }
@@ -238,6 +284,40 @@ int64_t ann_flat_workspace_bytes(int64_t N, int32_t d, int32_t dtype, int32_t B,
     int cus = 256;
     if (device_state(&st) == ANN_OK) cus = st->cus;
     return (int64_t)flat_plan(cus, N, d, dtype, B, k).ws_bytes;
+}
+
+int ann_timing_enable(int32_t on) {
+    std::lock_guard<std::mutex> lock(g_mu);
+    if (on) {
+        for (const TimedLaunch &t : g_timed) {
+            g_event_pool.push_back(t.a);
+            g_event_pool.push_back(t.b);
+        }
+        g_timed.clear();
+    }
+    g_timing = on != 0;
+    return ANN_OK;
+}
+
+int ann_timing_read(int32_t kernel, int32_t *launches, double *total_ms) {
+    if (!launches || !total_ms) return fail(ANN_ERR_INVALID, "null pointer argument");
+    if (kernel < 0 || kernel >= ANN_KERNEL_COUNT) return fail(ANN_ERR_INVALID, "unknown kernel code %d", kernel);
+    std::lock_guard<std::mutex> lock(g_mu);
+    int n = 0;
+    double sum = 0.0;
+    for (const TimedLaunch &t : g_timed) {
+        if (t.kernel != kernel) continue;
+        float ms = 0.f;
+        if (hipEventSynchronize(t.b) != hipSuccess || hipEventElapsedTime(&ms, t.a, t.b) != hipSuccess) {
+            (void)hipGetLastError();
+            return fail(ANN_ERR_LAUNCH, "cannot read the events of a timed launch");
+        }
+        ++n;
+        sum += ms;
+    }
+    *launches = n;
+    *total_ms = sum;
+    return ANN_OK;
 }
 
 int ann_release_workspace(void) {
@@ -321,6 +401,9 @@ int ann_graph_search_nonstall_typed(const void *corpus, int64_t N, int32_t d, in
     if (int rc = grow(&st->vis, &st->vis_bytes, (size_t)B * (size_t)ns.words * 4)) return rc;
     ns.visited = static_cast<uint32_t *>(st->vis);
     hipStream_t s = static_cast<hipStream_t>(stream);
+    if (int rc = check_launch("zero_words_kernel", launch_zero_words(ns.visited, (size_t)B * (size_t)ns.words, s)))
+        return rc;
+    TimedScope timed(ANN_KERNEL_GRAPH, s);
     return check_launch("graph_search_kernel (non-stall)",
                         launch_graph_search_nonstall(dtype, corpus, N, d, graph, R, entry, queries, B, k, ef, ids,
                                                      scores, L, ns, s));
@@ -333,6 +416,7 @@ int ann_graph_search_typed(const void *corpus, int64_t N, int32_t d, int32_t dty
     if (int rc = check_graph(corpus, N, d, dtype, graph, R, entry, queries, B, k, ef, ids, scores, &L)) return rc;
     std::lock_guard<std::mutex> lock(g_mu);
     hipStream_t s = static_cast<hipStream_t>(stream);
+    TimedScope timed(ANN_KERNEL_GRAPH, s);
     return check_launch("graph_search_kernel", launch_graph_search(dtype, corpus, N, d, graph, R, entry, nullptr,
                                                                    queries, B, k, ef, ids, scores, L, s));
 }
@@ -346,6 +430,7 @@ int ann_graph_search_entries_typed(const void *corpus, int64_t N, int32_t d, int
     if (int rc = check_graph(corpus, N, d, dtype, graph, R, 0, queries, B, k, ef, ids, scores, &L)) return rc;
     std::lock_guard<std::mutex> lock(g_mu);
     hipStream_t s = static_cast<hipStream_t>(stream);
+    TimedScope timed(ANN_KERNEL_GRAPH, s);
     return check_launch("graph_search_kernel", launch_graph_search(dtype, corpus, N, d, graph, R, 0, entries, queries,
                                                                    B, k, ef, ids, scores, L, s));
 }

@@ -75,6 +75,14 @@ hipError_t launch_graph_search(int dtype, const void *X, int64_t N, int d, const
     return launch_dtype<false>(dtype, X, N, d, graph, R, entry, Q, B, k, ef, ids, scores, L, ns, stream);
 }
 
+hipError_t launch_zero_words(uint32_t *p, size_t words, hipStream_t stream) {
+    const size_t n16 = words / 4;
+    const size_t blocks = (n16 + 255) / 256;
+    hipLaunchKernelGGL(zero_words_kernel, dim3((unsigned)(blocks < 4096 ? blocks : 4096)), dim3(256), 0, stream,
+                       reinterpret_cast<u4 *>(p), n16);
+    return hipGetLastError();
+}
+
 hipError_t launch_gather_ids(const int32_t *table, int64_t M, const int32_t *idx, int64_t n, int32_t *out,
                              hipStream_t stream) {
     const int64_t blocks = (n + 255) / 256;
@@ -86,11 +94,6 @@ hipError_t launch_gather_ids(const int32_t *table, int64_t M, const int32_t *idx
 hipError_t launch_graph_search_nonstall(int dtype, const void *X, int64_t N, int d, const int32_t *graph, int R,
                                         int entry, const void *Q, int B, int k, int ef, int32_t *ids, float *scores,
                                         const GraphLds &L, const NonStall &ns, hipStream_t stream) {
-    const size_t n16 = (size_t)B * (size_t)ns.words / 4;
-    const size_t blocks = (n16 + 255) / 256;
-    hipLaunchKernelGGL(zero_words_kernel, dim3((unsigned)(blocks < 4096 ? blocks : 4096)), dim3(256), 0, stream,
-                       reinterpret_cast<u4 *>(ns.visited), n16);
-    if (hipError_t e = hipGetLastError()) return e;
     return launch_dtype<true>(dtype, X, N, d, graph, R, entry, Q, B, k, ef, ids, scores, L, ns, stream);
 }
 

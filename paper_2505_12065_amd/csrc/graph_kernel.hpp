@@ -22,8 +22,8 @@
 // neighbours of one expansion form a batch: best and worst are those of the list as the
 // expansion starts, samples enter the average in slot order, the test follows the merge.
 // The sample stream must not contain re-scored nodes, so this variant backs the id cache
-// with an exact per-query bitset in global memory (one atomic OR per candidate, issued
-// together with the row loads so it adds no round trip of its own).
+// with an exact per-query bitset in global memory (its word is read together with the row,
+// so it adds no round trip of its own, and set afterwards by an atomic without return).
 #pragma once
 
 #include "common.hpp"
@@ -144,8 +144,9 @@ __global__ __launch_bounds__(GRAPH_THREADS) void graph_search_kernel(
 
     int cur = 0, len = 1;
     int p = 0, p2 = -1;                                   // best and second-best unexpanded entries
-    float ema = 0.f;                                      // identical in every thread
-    int n_dist = 1, n_expand = 0, early = 0;
+    float ema = 0.f;                                      // kept by the last wave, copied to the others
+    int n_dist = 1, n_expand = 0, early = 0;              // n_dist: last wave only
+    float *ema_s = reinterpret_cast<float *>(adj_id + 3);
     for (;;) {
         if (p < 0) break;                                 // nothing left to expand: natural stop
         ++n_expand;
@@ -175,13 +176,18 @@ __global__ __launch_bounds__(GRAPH_THREADS) void graph_search_kernel(
                 }
                 fresh = __shfl(fresh, lane & ~(LANES_PER_ROW - 1));
             }
+            // The exact visited bit is read with the row (one round trip for both) and set
+            // afterwards by an atomic that returns nothing.  The read bypasses the vector L1;
+            // the atomics of earlier expansions completed before the barriers in between.
             uint32_t seen = 0;
-            if (NS && fresh && sub == 0) seen = atomicOr(&seen_bits[v >> 5], 1u << (v & 31));
+            if (NS && fresh && sub == 0)
+                seen = __hip_atomic_load(&seen_bits[v >> 5], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             float s = 0.f;
             if (fresh) s = score_row(v);
             if (NS) {                                     // the cache may have forgotten v: the bitset has not
                 seen = __shfl(seen, lane & ~(LANES_PER_ROW - 1));
                 if (fresh && ((seen >> (v & 31)) & 1u)) fresh = 0;
+                if (fresh && sub == 0) atomicOr(&seen_bits[v >> 5], 1u << (v & 31));
             }
             if (sub == 0) {
                 cs[slot] = s;
@@ -212,32 +218,71 @@ __global__ __launch_bounds__(GRAPH_THREADS) void graph_search_kernel(
                 }
             }
             cpos[i] = pos;
-            if (NS) {
-                // best / worst of the list as it stands before this expansion's entries go in
-                const float s_best = ls[cur][0], s_worst = ls[cur][len - 1];
-                // An id named twice in one pass is scored once, by whichever slot won the race
-                // for the visited bit; its sample belongs to the first slot that names it.
-                const int me = co[i], pass0 = i & ~(ROWS_PER_PASS - 1);
-                bool first = me >= 0, scored = false;
-                float sv = 0.f;
-#pragma unroll
-                for (int jj = 0; jj < ROWS_PER_PASS; ++jj) {
-                    const int j = pass0 + jj;
-                    if (j < i && co[j] == me) first = false;
-                    if (ci[j] == me) { scored = true; sv = cs[j]; }
+        }
+        // The moving average is kept by the last wave alone, beside the list work of the
+        // others (for short rows and lists that is all on wave 0), and handed over in LDS.
+        if (NS && wave == GRAPH_WAVES - 1) {
+            // best / worst of the list as it stands before this expansion's entries go in
+            const float s_best = ls[cur][0], s_worst = ls[cur][len - 1];
+            // RQ of slot i, or NaN: no newly scored node there, or -inf: one, but best == worst.
+            // An id named more than once in the row is scored by whichever slot won the race
+            // for the cache entry (rarely by two); its one sample belongs to the first slot
+            // that names it.
+            auto rq_of = [&](int i, int me, bool first, bool scored, float sv) -> float {
+                (void)i; (void)me;
+                return !(first && scored) ? NAN : s_best != s_worst ? (s_best - sv) / (s_best - s_worst) : -INFINITY;
+            };
+            auto take = [&](float r) {
+                if (r == r) {
+                    ++n_dist;
+                    if (r != -INFINITY) ema = fmaf(ns.alpha, r - ema, ema);
                 }
-                rq[i] = (first && scored && s_best != s_worst) ? (s_best - sv) / (s_best - s_worst) : NAN;
+            };
+            if constexpr (RPT == 32) {
+                // lane i < 32 handles slot i: the row in 24 wide LDS reads, samples passed on in
+                // slot order through scalar registers
+                float r = NAN;
+                if (lane < 32) {
+                    int4 o4[8], i4[8];
+                    f4 s4[8];
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) {
+                        o4[u] = reinterpret_cast<const int4 *>(co)[u];
+                        i4[u] = reinterpret_cast<const int4 *>(ci)[u];
+                        s4[u] = reinterpret_cast<const f4 *>(cs)[u];
+                    }
+                    const int me = co[lane];
+                    bool first = me >= 0, scored = false;
+                    float sv = 0.f;
+#pragma unroll
+                    for (int j = 0; j < 32; ++j) {
+                        const int4 oq = o4[j >> 2], iq = i4[j >> 2];
+                        const int oj = (j & 3) == 0 ? oq.x : (j & 3) == 1 ? oq.y : (j & 3) == 2 ? oq.z : oq.w;
+                        const int ij = (j & 3) == 0 ? iq.x : (j & 3) == 1 ? iq.y : (j & 3) == 2 ? iq.z : iq.w;
+                        if (j < lane && oj == me) first = false;
+                        if (ij == me) { scored = true; sv = s4[j >> 2][j & 3]; }
+                    }
+                    r = rq_of(lane, me, first, scored, sv);
+                }
+#pragma unroll
+                for (int i = 0; i < 32; ++i) take(__int_as_float(__builtin_amdgcn_readlane(__float_as_int(r), i)));
+            } else {
+                for (int i = lane; i < RP; i += WAVE) {
+                    const int me = co[i];
+                    bool first = me >= 0, scored = false;
+                    float sv = 0.f;
+                    for (int j = 0; j < RP; ++j) {
+                        if (j < i && co[j] == me) first = false;
+                        if (ci[j] == me) { scored = true; sv = cs[j]; }
+                    }
+                    rq[i] = rq_of(i, me, first, scored, sv);
+                }
+                // rq[] is written and read by this wave only, in program order
+                for (int i = 0; i < RP; ++i) take(rq[i]);
             }
+            if (lane == 0) ema_s[0] = ema;
         }
         __syncthreads();
-        if (NS) {
-#pragma unroll
-            for (int i = 0; i < RP; ++i) {
-                const float r = rq[i];
-                if (r == r) ema = fmaf(ns.alpha, r - ema, ema);
-                n_dist += (ci[i] >= 0);
-            }
-        }
 
         // merge into the other buffer: new entries at pos + (rank among new entries),
         // old entry j moves down by the number of new entries that precede it
@@ -286,6 +331,7 @@ __global__ __launch_bounds__(GRAPH_THREADS) void graph_search_kernel(
                 if (p < 0) p = j; else p2 = j;
             }
         }
+        if (NS) ema = ema_s[0];                           // written before the last two barriers
         if (NS && ema > ns.tau) {                         // mature: leave as soon as the engine is ready
             int ready = 1;
             if (ns.ready) {
@@ -302,7 +348,7 @@ __global__ __launch_bounds__(GRAPH_THREADS) void graph_search_kernel(
         ids[(size_t)b * k + j] = has ? (int)(li[cur][j] & ~EXPANDED) : -1;
         scores[(size_t)b * k + j] = has ? ls[cur][j] : -INFINITY;
     }
-    if (NS && tid == 0) {
+    if (NS && tid == GRAPH_THREADS - WAVE) {
         if (ns.stats) {
             ns.stats[(size_t)b * 3 + 0] = early;
             ns.stats[(size_t)b * 3 + 1] = n_dist;

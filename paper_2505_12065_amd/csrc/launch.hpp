@@ -71,7 +71,9 @@ hipError_t launch_graph_search(int dtype, const void *X, int64_t N, int d, const
                                float *scores, const GraphLds &L, hipStream_t stream);
 hipError_t launch_gather_ids(const int32_t *table, int64_t M, const int32_t *idx, int64_t n, int32_t *out,
                              hipStream_t stream);
-// Same with the maturity exit; clears ns.visited (B * ns.words words) first.
+// p[0 .. words) <- 0; words a multiple of 4, p 16-byte aligned
+hipError_t launch_zero_words(uint32_t *p, size_t words, hipStream_t stream);
+// Same with the maturity exit; ns.visited (B * ns.words words) must be zero.
 hipError_t launch_graph_search_nonstall(int dtype, const void *X, int64_t N, int d, const int32_t *graph, int R,
                                         int entry, const void *Q, int B, int k, int ef, int32_t *ids, float *scores,
                                         const GraphLds &L, const NonStall &ns, hipStream_t stream);
