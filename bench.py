@@ -60,9 +60,6 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--no-sweep", action="store_true", help="skip the untimed per-B / per-ef report")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
-    ap.add_argument("--calibrate", action="store_true",
-                    help="also run one plain device copy of the corpus (known size) before the steps, so that a "
-                         "counter profile of this command contains a reference kernel to scale byte counters by")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build is single-GPU only (no collectives, no sharding); run with --gpus 1",
@@ -113,8 +110,6 @@ def main() -> int:
             if events is not None:
                 events[i][1].record()
 
-    if args.calibrate:
-        torch.empty_like(x).copy_(x)
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()

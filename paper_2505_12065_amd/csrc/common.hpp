@@ -82,6 +82,51 @@ struct TopList {
     }
 };
 
+// ---- selection across lanes ------------------------------------------------------------------
+// (score, id) -> 64-bit key whose unsigned order is the list order: larger score first, equal
+// scores by lower id.  -0 is folded into +0 so that equal scores compare equal; an empty slot
+// (-inf, EMPTY_ID) maps to the smallest key any list entry can have.
+__device__ __forceinline__ uint64_t order_key(float s, int id) {
+    uint32_t b = __float_as_uint(s + 0.0f);
+    b = (b & 0x80000000u) ? ~b : (b | 0x80000000u);
+    return ((uint64_t)b << 32) | (uint32_t)~id;
+}
+__device__ __forceinline__ void order_key_decode(uint64_t key, float &s, int &id) {
+    uint32_t b = (uint32_t)(key >> 32);
+    b = (b & 0x80000000u) ? (b ^ 0x80000000u) : ~b;
+    s = __uint_as_float(b);
+    id = (int)~(uint32_t)key;
+}
+
+// out <- the KP best entries of the sorted lists `in` held by the lanes whose numbers differ
+// only in the bits LO <= bit < HI (LO, HI powers of two; HI = 64: up to the whole wave);
+// every lane of such a group receives the same result.  KP rounds of "largest head wins and
+// is popped": a round costs one max-reduction instead of a full list merge.  An entry held
+// by several lanes is taken once.
+template <int KP, int LP, int LO, int HI>
+__device__ __forceinline__ void group_top(const TopList<LP> &in, TopList<KP> &out) {
+    uint64_t key[LP];
+#pragma unroll
+    for (int i = 0; i < LP; ++i) key[i] = order_key(in.s[i], in.id[i]);
+    const uint64_t empty = order_key(-INFINITY, EMPTY_ID);
+#pragma unroll
+    for (int r = 0; r < KP; ++r) {
+        uint64_t m = key[0];
+#pragma unroll
+        for (int mask = LO; mask < HI; mask <<= 1) {
+            const uint32_t lo = __shfl_xor((uint32_t)m, mask), hi = __shfl_xor((uint32_t)(m >> 32), mask);
+            const uint64_t o = ((uint64_t)hi << 32) | lo;
+            m = o > m ? o : m;
+        }
+        if (key[0] == m) {
+#pragma unroll
+            for (int i = 0; i + 1 < LP; ++i) key[i] = key[i + 1];
+            key[LP - 1] = empty;
+        }
+        order_key_decode(m, out.s[r], out.id[r]);
+    }
+}
+
 // ---- 16-byte chunks -----------------------------------------------------------------------
 __device__ __forceinline__ u4 load_chunk(const void *p) { return *reinterpret_cast<const u4 *>(p); }
 

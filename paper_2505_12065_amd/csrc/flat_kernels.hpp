@@ -14,6 +14,7 @@
 #pragma once
 
 #include "common.hpp"
+#include "launch.hpp"
 
 namespace ann {
 
@@ -103,34 +104,41 @@ __global__ __launch_bounds__(512) void flat_stream_kernel(const void *__restrict
     }
 
     // the four lanes that share a query -> one list per wave and query
-    static_for<NQG>([&](auto gc) {
-        constexpr int g = decltype(gc)::value;
-        best[g].merge_xor(16);
-        best[g].merge_xor(32);
-    });
-
     __syncthreads();                                   // query fragments are dead from here
     Cand *wl = reinterpret_cast<Cand *>(smem);         // [nwaves][NQG*16][KP]
-    if (lane < 16) {
-        static_for<NQG>([&](auto gc) {
-            constexpr int g = decltype(gc)::value;
+    static_for<NQG>([&](auto gc) {
+        constexpr int g = decltype(gc)::value;
+        TopList<KP> wbest;
+        group_top<KP, KP, 16, 64>(best[g], wbest);
+        if (lane < 16) {
 #pragma unroll
             for (int j = 0; j < KP; ++j)
-                wl[((size_t)wave * NQG * 16 + g * 16 + lane) * KP + j] = Cand{best[g].s[j], best[g].id[j]};
-        });
-    }
+                wl[((size_t)wave * NQG * 16 + g * 16 + lane) * KP + j] = Cand{wbest.s[j], wbest.id[j]};
+        }
+    });
     __syncthreads();
-    if (tid < NQG * 16 && q0 + tid < B) {
-        TopList<KP> fin;
-        fin.init();
-        for (int w = 0; w < nwaves; ++w)
-            for (int j = 0; j < KP; ++j) {
-                const Cand c = wl[((size_t)w * NQG * 16 + tid) * KP + j];
-                if (fin.admits(c.s, c.id)) fin.insert(c.s, c.id);
-            }
-        Cand *out = partial + ((size_t)(q0 + tid) * P + blockIdx.x) * KP;
+    // the block's list of a query: its 8 wave lists spread over 32 lanes (4 lanes per wave
+    // list, KP/4 consecutive entries each), 16 queries per pass of the 512 threads
+    constexpr int NW = STREAM_THREADS / WAVE, LP = KP / 4;
+    static_assert(NW == 8 && KP % 4 == 0, "the final selection assumes 8 wave lists split four ways");
+    const int sub = tid & 31, w = sub >> 2, part = sub & 3;
 #pragma unroll
-        for (int j = 0; j < KP; ++j) out[j] = Cand{fin.s[j], fin.id[j]};
+    for (int pass = 0; pass < NQG; ++pass) {
+        const int qi = pass * 16 + (tid >> 5);
+        TopList<LP> mine;
+#pragma unroll
+        for (int j = 0; j < LP; ++j) {
+            const Cand c = wl[((size_t)w * NQG * 16 + qi) * KP + part * LP + j];
+            mine.s[j] = c.s;
+            mine.id[j] = c.id;
+        }
+        TopList<KP> fin;
+        group_top<KP, LP, 1, 32>(mine, fin);
+        if (sub == 0 && q0 + qi < B) {
+            Cand *out = partial + ((size_t)(q0 + qi) * P + blockIdx.x) * KP;
+#pragma unroll
+            for (int j = 0; j < KP; ++j) out[j] = Cand{fin.s[j], fin.id[j]};
+        }
     }
 }
 
@@ -208,6 +216,24 @@ __global__ __launch_bounds__(256) void flat_f32_kernel(const float *__restrict__
 
 // One workgroup (1 to 4 wavefronts, by the amount of work) per query: the k best of its
 // P*KP partial pairs, written in order; unused tail slots become id -1 / score -inf.
+// best <- best of itself and in[first], in[first + stride], ...: eight loads in flight per
+// thread, so a short list costs one memory latency instead of one per element
+template <int KP>
+__device__ __forceinline__ void gather_best(const Cand *__restrict__ in, int total, int first, int stride,
+                                            TopList<KP> &best) {
+    for (int e0 = first; e0 < total; e0 += 8 * stride) {
+        Cand c[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int e = e0 + u * stride;
+            c[u] = e < total ? in[e] : Cand{-INFINITY, EMPTY_ID};
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+            if (best.admits(c[u].s, c[u].id)) best.insert(c[u].s, c[u].id);
+    }
+}
+
 template <int KP>
 __global__ __launch_bounds__(256) void flat_merge_kernel(const Cand *__restrict__ partial, int P, int k,
                                                          int32_t *__restrict__ ids, float *__restrict__ scores) {
@@ -217,29 +243,29 @@ __global__ __launch_bounds__(256) void flat_merge_kernel(const Cand *__restrict_
     const Cand *in = partial + (size_t)q * P * KP;
     TopList<KP> best;
     best.init();
-    for (int e = tid; e < P * KP; e += blockDim.x) {
-        const Cand c = in[e];
-        if (best.admits(c.s, c.id)) best.insert(c.s, c.id);
-    }
-#pragma unroll
-    for (int m = 1; m < 64; m <<= 1) best.merge_xor(m);
+    gather_best<KP>(in, P * KP, tid, blockDim.x, best);
+    TopList<KP> wbest;
+    group_top<KP, KP, 1, 64>(best, wbest);
     if (lane == 0) {
 #pragma unroll
-        for (int j = 0; j < KP; ++j) wl[wave * KP + j] = Cand{best.s[j], best.id[j]};
+        for (int j = 0; j < KP; ++j) wl[wave * KP + j] = Cand{wbest.s[j], wbest.id[j]};
     }
     __syncthreads();
-    if (tid == 0) {
+    if (wave == 0) {                                  // one entry per lane, at most 4 waves x KP <= 64
+        TopList<1> one;
+        one.init();
+        if (lane < nwaves * KP) { one.s[0] = wl[lane].s; one.id[0] = wl[lane].id; }
         TopList<KP> fin;
-        fin.init();
-        for (int e = 0; e < nwaves * KP; ++e)
-            if (fin.admits(wl[e].s, wl[e].id)) fin.insert(wl[e].s, wl[e].id);
+        group_top<KP, 1, 1, 64>(one, fin);
+        if (lane == 0) {
 #pragma unroll
-        for (int j = 0; j < KP; ++j)
-            if (j < k) {
-                const bool has = fin.id[j] != EMPTY_ID;
-                ids[(size_t)q * k + j] = has ? fin.id[j] : -1;
-                scores[(size_t)q * k + j] = has ? fin.s[j] : -INFINITY;
-            }
+            for (int j = 0; j < KP; ++j)
+                if (j < k) {
+                    const bool has = fin.id[j] != EMPTY_ID;
+                    ids[(size_t)q * k + j] = has ? fin.id[j] : -1;
+                    scores[(size_t)q * k + j] = has ? fin.s[j] : -INFINITY;
+                }
+        }
     }
 }
 
@@ -253,17 +279,14 @@ __global__ __launch_bounds__(64) void flat_sample_merge_kernel(const Cand *__res
     const Cand *in = src + (size_t)q * Ps * KP;
     TopList<KP> best;
     best.init();
-    for (int e = lane; e < Ps * KP; e += 64) {
-        const Cand c = in[e];
-        if (best.admits(c.s, c.id)) best.insert(c.s, c.id);
-    }
-#pragma unroll
-    for (int m = 1; m < 64; m <<= 1) best.merge_xor(m);
+    gather_best<KP>(in, Ps * KP, lane, 64, best);
+    TopList<KP> top;
+    group_top<KP, KP, 1, 64>(best, top);
     if (lane == 0) {
         Cand *out = dst + ((size_t)q * pstride + pslot) * KP;
 #pragma unroll
-        for (int j = 0; j < KP; ++j) out[j] = Cand{best.s[j], best.id[j]};
-        thr[q] = best.id[KP - 1] != EMPTY_ID ? best.s[KP - 1] : -INFINITY;
+        for (int j = 0; j < KP; ++j) out[j] = Cand{top.s[j], top.id[j]};
+        thr[q] = top.id[KP - 1] != EMPTY_ID ? top.s[KP - 1] : -INFINITY;
     }
 }
 

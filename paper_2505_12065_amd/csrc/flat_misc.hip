@@ -35,7 +35,7 @@ hipError_t launch_flat_f32(int kp, const float *X, int64_t N, int d, const float
 
 hipError_t launch_flat_merge(int kp, const Cand *partial, int P, int B, int k, int32_t *ids, float *scores,
                              hipStream_t stream) {
-    const int threads = P * kp <= 1024 ? 64 : 256;      // at most 16 pairs per lane either way
+    const int threads = P * kp <= 512 ? 64 : 256;       // one batch of loads per lane where possible
     if (kp == 4)
         hipLaunchKernelGGL((flat_merge_kernel<4>), dim3(B), dim3(threads), 0, stream, partial, P, k, ids, scores);
     else

@@ -77,6 +77,12 @@ def compare_nonstall(gpu, o, xn, gn, qn, name, entry, k, ef, tau, window, max_of
         # RQ divides by (best - worst), which amplifies the last-bit differences of the scores
         assert np.allclose(ema[same], o_ema[same], rtol=5e-4, atol=5e-4)
     for b in off:
+        if stats[b, 0] == 0 and o_stats[b, 0] == 0:
+            # both stopped naturally: a near-tie ordered by fp32 rounding sent the two searches through
+            # slightly different expansions; the lists must still agree under the near-tie rule
+            compare_topk(ids[b:b + 1], sc[b:b + 1], o_ids[b:b + 1], o_sc64[b:b + 1], xn, qn, dtype=name, rows=[b])
+            assert abs(int(stats[b, 1]) - int(o_stats[b, 1])) <= max(64, o_stats[b, 1] // 20), (b, stats[b], o_stats[b])
+            continue
         cut = oracle.graph_search_nonstall(xn, gn, entry, qn[b:b + 1], k, ef, tau=np.inf, window=window,
                                            max_expand=int(stats[b, 2]), dtype=name)
         compare_topk(ids[b:b + 1], sc[b:b + 1], cut[0], cut[2], xn, qn, dtype=name, rows=[b])
