@@ -137,21 +137,26 @@ __device__ __forceinline__ u4 zero_chunk() { u4 z = {0u, 0u, 0u, 0u}; return z; 
 template <class T>
 __device__ __forceinline__ float dot_chunk(u4 x, u4 q, float acc);
 
+// 16-bit inputs: v_dot2c_f32_{f16,bf16}, two exact products added to the fp32 accumulator per
+// instruction (four instructions per chunk instead of eight conversions and eight FMAs).
+typedef _Float16 h2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf2 __attribute__((ext_vector_type(2)));
+
 template <>
 __device__ __forceinline__ float dot_chunk<F16>(u4 x, u4 q, float acc) {
     const h8 a = __builtin_bit_cast(h8, x), b = __builtin_bit_cast(h8, q);
 #pragma unroll
-    for (int i = 0; i < 8; ++i) acc = fmaf((float)a[i], (float)b[i], acc);
+    for (int i = 0; i < 4; ++i)
+        acc = __builtin_amdgcn_fdot2(h2{a[2 * i], a[2 * i + 1]}, h2{b[2 * i], b[2 * i + 1]}, acc, false);
     return acc;
 }
 
 template <>
 __device__ __forceinline__ float dot_chunk<BF16>(u4 x, u4 q, float acc) {
+    const b8 a = __builtin_bit_cast(b8, x), b = __builtin_bit_cast(b8, q);
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        acc = fmaf(__uint_as_float(x[i] << 16), __uint_as_float(q[i] << 16), acc);
-        acc = fmaf(__uint_as_float(x[i] & 0xffff0000u), __uint_as_float(q[i] & 0xffff0000u), acc);
-    }
+    for (int i = 0; i < 4; ++i)
+        acc = __builtin_amdgcn_fdot2_f32_bf16(bf2{a[2 * i], a[2 * i + 1]}, bf2{b[2 * i], b[2 * i + 1]}, acc, false);
     return acc;
 }
 

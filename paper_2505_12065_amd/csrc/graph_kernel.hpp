@@ -49,6 +49,11 @@ __device__ __forceinline__ int list_lower_bound(const float *s, const uint32_t *
     return lo;
 }
 
+// precedes() as 0 / 1 without short-circuit evaluation (no branches in unrolled loops)
+__device__ __forceinline__ int precedes01(float s, int id, float s2, int id2) {
+    return (int)(s > s2) | ((int)(s == s2) & (int)(id < id2));
+}
+
 // RPT: number of graph slots rounded up to 32 when it is known at compile time (32 for
 // R <= 32: the short loops over the scored neighbours are then fully unrolled and their
 // LDS reads issued together), 0 = taken from the layout at run time.
@@ -204,14 +209,29 @@ __global__ __launch_bounds__(GRAPH_THREADS) void graph_search_kernel(
 
         // where would each scored neighbour go?  cpos = entries of the list that precede it,
         // or -1 when it is a duplicate or does not make it into the best ef
+        // (the loops over the scored neighbours read them with wide, unconditional LDS loads and
+        // use branch-free arithmetic: a short-circuit "j < i && ci[j] == v" compiles into one
+        // predicated load-and-wait per j, i.e. 32 LDS round trips in a row)
         for (int i = tid; i < RP; i += GRAPH_THREADS) {
             const int v = ci[i];
             int pos = -1;
             if (v >= 0) {
                 const float s = cs[i];
-                bool dup = false;
+                int dup = 0;
+                if constexpr (RPT == 32) {
+                    int4 c4[8];
 #pragma unroll
-                for (int j = 0; j < (RPT ? RPT : i); ++j) dup |= (j < i && ci[j] == v);
+                    for (int u = 0; u < 8; ++u) c4[u] = reinterpret_cast<const int4 *>(ci)[u];
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) {
+                        dup |= (int)(c4[u].x == v) & (int)(4 * u + 0 < i);
+                        dup |= (int)(c4[u].y == v) & (int)(4 * u + 1 < i);
+                        dup |= (int)(c4[u].z == v) & (int)(4 * u + 2 < i);
+                        dup |= (int)(c4[u].w == v) & (int)(4 * u + 3 < i);
+                    }
+                } else {
+                    for (int j = 0; j < i; ++j) dup |= (int)(ci[j] == v);
+                }
                 if (!dup && s == s) {                      // a NaN score is never listed
                     pos = list_lower_bound(ls[cur], li[cur], len, s, v);
                     if (pos >= ef || (pos < len && (int)(li[cur][pos] & ~EXPANDED) == v)) pos = -1;
@@ -288,26 +308,65 @@ __global__ __launch_bounds__(GRAPH_THREADS) void graph_search_kernel(
         // old entry j moves down by the number of new entries that precede it
         const int nxt = cur ^ 1;
         int n_new = 0;
+        if constexpr (RPT == 32) {
+            int4 p4[8];                                   // every thread: the 32 positions
 #pragma unroll
-        for (int i = 0; i < RP; ++i) n_new += (cpos[i] >= 0);
-        for (int i = tid; i < RP; i += GRAPH_THREADS) {
-            const int pos = cpos[i];
-            if (pos >= 0) {
-                const float s = cs[i];
-                const int v = ci[i];
-                int r = 0;
+            for (int u = 0; u < 8; ++u) p4[u] = reinterpret_cast<const int4 *>(cpos)[u];
 #pragma unroll
-                for (int j = 0; j < RP; ++j) r += (cpos[j] >= 0 && precedes(cs[j], ci[j], s, v));
-                if (pos + r < ef) { ls[nxt][pos + r] = s; li[nxt][pos + r] = (uint32_t)v; }
+            for (int u = 0; u < 8; ++u)
+                n_new += (int)(p4[u].x >= 0) + (int)(p4[u].y >= 0) + (int)(p4[u].z >= 0) + (int)(p4[u].w >= 0);
+            if (tid < 32) {
+                const int pos = cpos[tid];
+                if (pos >= 0) {
+                    const float s = cs[tid];
+                    const int v = ci[tid];
+                    f4 s4[8];
+                    int4 c4[8];
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) {
+                        s4[u] = reinterpret_cast<const f4 *>(cs)[u];
+                        c4[u] = reinterpret_cast<const int4 *>(ci)[u];
+                    }
+                    int r = 0;
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) {
+                        r += (int)(p4[u].x >= 0) & precedes01(s4[u][0], c4[u].x, s, v);
+                        r += (int)(p4[u].y >= 0) & precedes01(s4[u][1], c4[u].y, s, v);
+                        r += (int)(p4[u].z >= 0) & precedes01(s4[u][2], c4[u].z, s, v);
+                        r += (int)(p4[u].w >= 0) & precedes01(s4[u][3], c4[u].w, s, v);
+                    }
+                    if (pos + r < ef) { ls[nxt][pos + r] = s; li[nxt][pos + r] = (uint32_t)v; }
+                }
             }
-        }
-        for (int j = tid; j < len; j += GRAPH_THREADS) {
-            int shift = 0;
-            if (n_new) {
+            for (int j = tid; j < len; j += GRAPH_THREADS) {
+                int shift = 0;
 #pragma unroll
-                for (int i = 0; i < RP; ++i) shift += (cpos[i] >= 0 && cpos[i] <= j);
+                for (int u = 0; u < 8; ++u) {
+                    // a position is in 0 .. j exactly when, as an unsigned number, it is <= j (-1 is not)
+                    shift += (int)((unsigned)p4[u].x <= (unsigned)j) + (int)((unsigned)p4[u].y <= (unsigned)j) +
+                             (int)((unsigned)p4[u].z <= (unsigned)j) + (int)((unsigned)p4[u].w <= (unsigned)j);
+                }
+                if (j + shift < ef) { ls[nxt][j + shift] = ls[cur][j]; li[nxt][j + shift] = li[cur][j]; }
             }
-            if (j + shift < ef) { ls[nxt][j + shift] = ls[cur][j]; li[nxt][j + shift] = li[cur][j]; }
+        } else {
+            for (int i = 0; i < RP; ++i) n_new += (cpos[i] >= 0);
+            for (int i = tid; i < RP; i += GRAPH_THREADS) {
+                const int pos = cpos[i];
+                if (pos >= 0) {
+                    const float s = cs[i];
+                    const int v = ci[i];
+                    int r = 0;
+                    for (int j = 0; j < RP; ++j) r += (int)(cpos[j] >= 0) & precedes01(cs[j], ci[j], s, v);
+                    if (pos + r < ef) { ls[nxt][pos + r] = s; li[nxt][pos + r] = (uint32_t)v; }
+                }
+            }
+            for (int j = tid; j < len; j += GRAPH_THREADS) {
+                int shift = 0;
+                if (n_new) {
+                    for (int i = 0; i < RP; ++i) shift += (int)((unsigned)cpos[i] <= (unsigned)j);
+                }
+                if (j + shift < ef) { ls[nxt][j + shift] = ls[cur][j]; li[nxt][j + shift] = li[cur][j]; }
+            }
         }
         len = min(ef, len + n_new);
         cur = nxt;
