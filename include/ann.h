@@ -58,7 +58,7 @@ extern "C" {
 #define ANN_F32   2
 
 #define ANN_K_MAX    16      /* largest k of the flat search */
-#define ANN_EF_MAX   4096    /* largest candidate list of the graph search (k <= ef) */
+#define ANN_EF_MAX   16384   /* largest candidate list of the graph search (k <= ef) */
 #define ANN_R_MAX    256     /* largest graph out-degree */
 #define ANN_D_MAX    4096    /* largest embedding dimension */
 
@@ -110,8 +110,11 @@ int ann_flat_search(const void *corpus, int64_t N, int32_t d,
  *   entry   node id in [0, N), by value, shared by all queries
  *   k, ef   1 <= k <= ef <= ANN_EF_MAX
  *
- * One workgroup serves one query; candidate list and visited filter live in
- * LDS, so no workspace is used.
+ * One workgroup serves one query; the candidate list lives in LDS.  Up to ef = 2048
+ * the visited filter does too and no workspace is used; longer lists score so many
+ * nodes that an exact visited bitset in global memory is used instead (the workspace of
+ * ann_graph_search_nonstall_typed, same size and rules).  d, R and ef together must fit
+ * the 160 KB of LDS (ef = 16384 fits with d <= 1024 at 16 bits), else ANN_ERR_INVALID.
  */
 int ann_graph_search_typed(const void *corpus, int64_t N, int32_t d, int32_t dtype,
                            const int32_t *graph, int32_t R, int32_t entry,

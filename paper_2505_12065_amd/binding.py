@@ -15,7 +15,7 @@ LIB_PATH = os.environ.get("ANN_LIBRARY_PATH", os.path.join(_HERE, "libann.so"))
 
 ANN_OK, ANN_ERR_INVALID, ANN_ERR_ALIGNMENT, ANN_ERR_UNKNOWN_CORPUS, ANN_ERR_LAUNCH, ANN_ERR_NOMEM = 0, -1, -2, -3, -4, -5
 ANN_F16, ANN_BF16, ANN_F32 = 0, 1, 2
-ANN_K_MAX, ANN_EF_MAX, ANN_R_MAX, ANN_D_MAX = 16, 4096, 256, 4096
+ANN_K_MAX, ANN_EF_MAX, ANN_R_MAX, ANN_D_MAX = 16, 16384, 256, 4096
 
 _DTYPES = {torch.float16: ANN_F16, torch.bfloat16: ANN_BF16, torch.float32: ANN_F32}
 

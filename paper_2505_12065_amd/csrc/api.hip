@@ -409,16 +409,42 @@ int ann_graph_search_nonstall_typed(const void *corpus, int64_t N, int32_t d, in
                                                      scores, L, ns, s));
 }
 
+// Plain search.  Lists longer than GRAPH_EF_DOUBLE score far more nodes than the LDS id cache
+// remembers, so they run on the kernel variant with the exact visited bitset, with an exit
+// threshold no average can exceed.
+static int graph_search_any(const void *corpus, int64_t N, int32_t d, int32_t dtype, const int32_t *graph, int32_t R,
+                            int32_t entry, const int32_t *entries, const void *queries, int32_t B, int32_t k,
+                            int32_t ef, int32_t *ids, float *scores, const GraphLds &L, hipStream_t s) {
+    std::lock_guard<std::mutex> lock(g_mu);
+    if (ef <= GRAPH_EF_DOUBLE) {
+        TimedScope timed(ANN_KERNEL_GRAPH, s);
+        return check_launch("graph_search_kernel", launch_graph_search(dtype, corpus, N, d, graph, R, entry, entries,
+                                                                       queries, B, k, ef, ids, scores, L, s));
+    }
+    DeviceState *st = nullptr;
+    if (int rc = device_state(&st)) return rc;
+    NonStall ns{};
+    ns.entries = entries;
+    ns.tau = INFINITY;
+    ns.alpha = 0.f;
+    ns.words = visited_words(N);
+    if (int rc = grow(&st->vis, &st->vis_bytes, (size_t)B * (size_t)ns.words * 4)) return rc;
+    ns.visited = static_cast<uint32_t *>(st->vis);
+    if (int rc = check_launch("zero_words_kernel", launch_zero_words(ns.visited, (size_t)B * (size_t)ns.words, s)))
+        return rc;
+    TimedScope timed(ANN_KERNEL_GRAPH, s);
+    return check_launch("graph_search_kernel (long list)",
+                        launch_graph_search_nonstall(dtype, corpus, N, d, graph, R, entry, queries, B, k, ef, ids,
+                                                     scores, L, ns, s));
+}
+
 int ann_graph_search_typed(const void *corpus, int64_t N, int32_t d, int32_t dtype, const int32_t *graph,
                            int32_t R, int32_t entry, const void *queries, int32_t B, int32_t k, int32_t ef,
                            int32_t *ids, float *scores, void *stream) {
     GraphLds L;
     if (int rc = check_graph(corpus, N, d, dtype, graph, R, entry, queries, B, k, ef, ids, scores, &L)) return rc;
-    std::lock_guard<std::mutex> lock(g_mu);
-    hipStream_t s = static_cast<hipStream_t>(stream);
-    TimedScope timed(ANN_KERNEL_GRAPH, s);
-    return check_launch("graph_search_kernel", launch_graph_search(dtype, corpus, N, d, graph, R, entry, nullptr,
-                                                                   queries, B, k, ef, ids, scores, L, s));
+    return graph_search_any(corpus, N, d, dtype, graph, R, entry, nullptr, queries, B, k, ef, ids, scores, L,
+                            static_cast<hipStream_t>(stream));
 }
 
 int ann_graph_search_entries_typed(const void *corpus, int64_t N, int32_t d, int32_t dtype, const int32_t *graph,
@@ -428,11 +454,8 @@ int ann_graph_search_entries_typed(const void *corpus, int64_t N, int32_t d, int
     if (reinterpret_cast<uintptr_t>(entries) & 3) return fail(ANN_ERR_ALIGNMENT, "entries must be 4-byte aligned");
     GraphLds L;
     if (int rc = check_graph(corpus, N, d, dtype, graph, R, 0, queries, B, k, ef, ids, scores, &L)) return rc;
-    std::lock_guard<std::mutex> lock(g_mu);
-    hipStream_t s = static_cast<hipStream_t>(stream);
-    TimedScope timed(ANN_KERNEL_GRAPH, s);
-    return check_launch("graph_search_kernel", launch_graph_search(dtype, corpus, N, d, graph, R, 0, entries, queries,
-                                                                   B, k, ef, ids, scores, L, s));
+    return graph_search_any(corpus, N, d, dtype, graph, R, 0, entries, queries, B, k, ef, ids, scores, L,
+                            static_cast<hipStream_t>(stream));
 }
 
 int ann_gather_ids(const int32_t *table, int64_t M, const int32_t *idx, int64_t n, int32_t *out, void *stream) {

@@ -4,34 +4,39 @@
 namespace ann {
 
 GraphLds graph_lds_layout(int d, int elem_bytes, int R, int ef) {
-    GraphLds L;
     auto up = [](uint32_t x) { return (x + 15u) & ~15u; };
-    uint32_t off = 0;
-    L.rp = (uint32_t)((R + ROWS_PER_PASS - 1) / ROWS_PER_PASS * ROWS_PER_PASS);
-    // cache slots: a few times the number of nodes a search scores (about 10 ef), but not
-    // so many that only one workgroup fits a compute unit when two could
-    const uint32_t rest = (uint32_t)d * elem_bytes + 16u * ef + 5u * 4u * L.rp + 2u * 4u * RMAX_LDS +
-                          8u * (((uint32_t)ef + 63u) / 64u) + 512u;
-    uint32_t bits = 10;
-    while ((1u << bits) < 32u * (uint32_t)ef && bits < 14) ++bits;
-    while (bits > 11 && rest + (4u << bits) > LDS_MAX / 2 && rest + (4u << 11) <= LDS_MAX / 2) --bits;
-    L.cache_bits = bits;
-    L.q = off; off = up(off + (uint32_t)d * elem_bytes);
-    L.ls0 = off; off = up(off + 4u * ef);
-    L.ls1 = off; off = up(off + 4u * ef);
-    L.li0 = off; off = up(off + 4u * ef);
-    L.li1 = off; off = up(off + 4u * ef);
-    L.cs = off; off = up(off + 4u * L.rp);
-    L.ci = off; off = up(off + 4u * L.rp);
-    L.cpos = off; off = up(off + 4u * L.rp);
-    L.cache = off; off = up(off + (4u << bits));
-    L.ctl = off; off = up(off + 16u);
-    L.adj = off; off = up(off + 2u * 4u * RMAX_LDS);
-    L.um = off; off = up(off + 8u * ((uint32_t)ef + 63u) / 64u + 8u);
-    L.rq = off; off = up(off + 4u * L.rp);
-    L.co = off; off = up(off + 4u * L.rp);
-    L.total = off;
-    return L;
+    const bool inplace = ef > GRAPH_EF_DOUBLE;           // long lists: one buffer, merged in place
+    auto lay = [&](uint32_t bits) {
+        GraphLds L;
+        uint32_t off = 0;
+        L.rp = (uint32_t)((R + ROWS_PER_PASS - 1) / ROWS_PER_PASS * ROWS_PER_PASS);
+        L.cache_bits = bits;
+        L.q = off; off = up(off + (uint32_t)d * elem_bytes);
+        L.ls0 = off; off = up(off + 4u * ef);
+        if (inplace) L.ls1 = L.ls0; else { L.ls1 = off; off = up(off + 4u * ef); }
+        L.li0 = off; off = up(off + 4u * ef);
+        if (inplace) L.li1 = L.li0; else { L.li1 = off; off = up(off + 4u * ef); }
+        L.cs = off; off = up(off + 4u * L.rp);
+        L.ci = off; off = up(off + 4u * L.rp);
+        L.cpos = off; off = up(off + 4u * L.rp);
+        L.cache = off; off = up(off + (4u << bits));
+        L.ctl = off; off = up(off + 16u);
+        L.adj = off; off = up(off + 2u * 4u * RMAX_LDS);
+        L.um = off; off = up(off + 8u * (((uint32_t)ef + 63u) / 64u) + 8u);
+        L.rq = off; off = up(off + 4u * L.rp);
+        L.co = off; off = up(off + 4u * L.rp);
+        L.total = off;
+        return L;
+    };
+    // cache slots: a few times the number of nodes a search scores (about 10 ef), at most 2^14;
+    // fewer when that lets two workgroups share a compute unit, or when the list needs the room
+    uint32_t want = 10;
+    while ((1u << want) < 32u * (uint32_t)ef && want < 14) ++want;
+    uint32_t bits = want;
+    if (lay(11).total <= LDS_MAX / 2)
+        while (bits > 11 && lay(bits).total > LDS_MAX / 2) --bits;
+    while (bits > 10 && lay(bits).total > LDS_MAX) --bits;
+    return lay(bits);
 }
 
 namespace {

@@ -304,22 +304,53 @@ __global__ __launch_bounds__(GRAPH_THREADS) void graph_search_kernel(
         }
         __syncthreads();
 
-        // merge into the other buffer: new entries at pos + (rank among new entries),
-        // old entry j moves down by the number of new entries that precede it
-        const int nxt = cur ^ 1;
+        // merge: new entries go to pos + (rank among the new entries), old entry j moves up by the
+        // number of new entries that precede it.  Lists of up to 2048 entries are double-buffered
+        // (merged into the other buffer); longer ones have one buffer and are merged in place.
+        const bool inplace = L.ls1 == L.ls0;
+        const int nxt = inplace ? cur : cur ^ 1;
         int n_new = 0;
+        unsigned jmin = 0xffffffffu;                      // lowest position a new entry takes
+        int4 p4[RPT == 32 ? 8 : 1];                       // R <= 32: every thread holds the 32 positions
         if constexpr (RPT == 32) {
-            int4 p4[8];                                   // every thread: the 32 positions
 #pragma unroll
             for (int u = 0; u < 8; ++u) p4[u] = reinterpret_cast<const int4 *>(cpos)[u];
 #pragma unroll
-            for (int u = 0; u < 8; ++u)
+            for (int u = 0; u < 8; ++u) {
                 n_new += (int)(p4[u].x >= 0) + (int)(p4[u].y >= 0) + (int)(p4[u].z >= 0) + (int)(p4[u].w >= 0);
-            if (tid < 32) {
-                const int pos = cpos[tid];
-                if (pos >= 0) {
-                    const float s = cs[tid];
-                    const int v = ci[tid];
+                jmin = min(min(jmin, (unsigned)p4[u].x), min((unsigned)p4[u].y, min((unsigned)p4[u].z, (unsigned)p4[u].w)));
+            }
+        } else {
+            for (int i = 0; i < RP; ++i) {
+                n_new += (cpos[i] >= 0);
+                jmin = min(jmin, (unsigned)cpos[i]);
+            }
+        }
+        // number of new entries at or before list position j (a position is in 0 .. j exactly
+        // when, as an unsigned number, it is <= j; -1 is not)
+        auto shift_of = [&](int j) {
+            int shift = 0;
+            if constexpr (RPT == 32) {
+#pragma unroll
+                for (int u = 0; u < 8; ++u)
+                    shift += (int)((unsigned)p4[u].x <= (unsigned)j) + (int)((unsigned)p4[u].y <= (unsigned)j) +
+                             (int)((unsigned)p4[u].z <= (unsigned)j) + (int)((unsigned)p4[u].w <= (unsigned)j);
+            } else {
+                for (int i = 0; i < RP; ++i) shift += (int)((unsigned)cpos[i] <= (unsigned)j);
+            }
+            return shift;
+        };
+        // the new entry of this thread (slot tid, RP <= GRAPH_THREADS): final position or -1
+        int new_at = -1;
+        float new_s = 0.f;
+        int new_v = 0;
+        if (tid < RP) {
+            const int pos = cpos[tid];
+            if (pos >= 0) {
+                new_s = cs[tid];
+                new_v = ci[tid];
+                int r = 0;
+                if constexpr (RPT == 32) {
                     f4 s4[8];
                     int4 c4[8];
 #pragma unroll
@@ -327,46 +358,51 @@ __global__ __launch_bounds__(GRAPH_THREADS) void graph_search_kernel(
                         s4[u] = reinterpret_cast<const f4 *>(cs)[u];
                         c4[u] = reinterpret_cast<const int4 *>(ci)[u];
                     }
-                    int r = 0;
 #pragma unroll
                     for (int u = 0; u < 8; ++u) {
-                        r += (int)(p4[u].x >= 0) & precedes01(s4[u][0], c4[u].x, s, v);
-                        r += (int)(p4[u].y >= 0) & precedes01(s4[u][1], c4[u].y, s, v);
-                        r += (int)(p4[u].z >= 0) & precedes01(s4[u][2], c4[u].z, s, v);
-                        r += (int)(p4[u].w >= 0) & precedes01(s4[u][3], c4[u].w, s, v);
+                        r += (int)(p4[u].x >= 0) & precedes01(s4[u][0], c4[u].x, new_s, new_v);
+                        r += (int)(p4[u].y >= 0) & precedes01(s4[u][1], c4[u].y, new_s, new_v);
+                        r += (int)(p4[u].z >= 0) & precedes01(s4[u][2], c4[u].z, new_s, new_v);
+                        r += (int)(p4[u].w >= 0) & precedes01(s4[u][3], c4[u].w, new_s, new_v);
                     }
-                    if (pos + r < ef) { ls[nxt][pos + r] = s; li[nxt][pos + r] = (uint32_t)v; }
+                } else {
+                    for (int j = 0; j < RP; ++j) r += (int)(cpos[j] >= 0) & precedes01(cs[j], ci[j], new_s, new_v);
                 }
+                if (pos + r < ef) new_at = pos + r;
             }
+        }
+        if (!inplace) {
+            if (new_at >= 0) { ls[nxt][new_at] = new_s; li[nxt][new_at] = (uint32_t)new_v; }
             for (int j = tid; j < len; j += GRAPH_THREADS) {
-                int shift = 0;
+                const int shift = n_new ? shift_of(j) : 0;
+                if (j + shift < ef) { ls[nxt][j + shift] = ls[cur][j]; li[nxt][j + shift] = li[cur][j]; }
+            }
+        } else if (n_new) {
+            // Entries below jmin stay.  The others move up by at most RP: chunks of MOVE entries
+            // are taken from the top down; a chunk is read by everyone before anyone writes it
+            // (its targets lie in itself and in the chunk above, which has already moved).
+            constexpr int PER = 4, MOVE = PER * GRAPH_THREADS;
+            const int lowest = (int)jmin & ~(MOVE - 1);
+            for (int base = (len - 1) & ~(MOVE - 1); base >= lowest; base -= MOVE) {
+                float ms[PER];
+                uint32_t mi[PER];
 #pragma unroll
-                for (int u = 0; u < 8; ++u) {
-                    // a position is in 0 .. j exactly when, as an unsigned number, it is <= j (-1 is not)
-                    shift += (int)((unsigned)p4[u].x <= (unsigned)j) + (int)((unsigned)p4[u].y <= (unsigned)j) +
-                             (int)((unsigned)p4[u].z <= (unsigned)j) + (int)((unsigned)p4[u].w <= (unsigned)j);
+                for (int u = 0; u < PER; ++u) {
+                    const int j = base + u * GRAPH_THREADS + tid;
+                    if (j < len && j >= (int)jmin) { ms[u] = ls[cur][j]; mi[u] = li[cur][j]; }
                 }
-                if (j + shift < ef) { ls[nxt][j + shift] = ls[cur][j]; li[nxt][j + shift] = li[cur][j]; }
-            }
-        } else {
-            for (int i = 0; i < RP; ++i) n_new += (cpos[i] >= 0);
-            for (int i = tid; i < RP; i += GRAPH_THREADS) {
-                const int pos = cpos[i];
-                if (pos >= 0) {
-                    const float s = cs[i];
-                    const int v = ci[i];
-                    int r = 0;
-                    for (int j = 0; j < RP; ++j) r += (int)(cpos[j] >= 0) & precedes01(cs[j], ci[j], s, v);
-                    if (pos + r < ef) { ls[nxt][pos + r] = s; li[nxt][pos + r] = (uint32_t)v; }
+                __syncthreads();
+#pragma unroll
+                for (int u = 0; u < PER; ++u) {
+                    const int j = base + u * GRAPH_THREADS + tid;
+                    if (j < len && j >= (int)jmin) {
+                        const int to = j + shift_of(j);
+                        if (to < ef) { ls[cur][to] = ms[u]; li[cur][to] = mi[u]; }
+                    }
                 }
             }
-            for (int j = tid; j < len; j += GRAPH_THREADS) {
-                int shift = 0;
-                if (n_new) {
-                    for (int i = 0; i < RP; ++i) shift += (int)((unsigned)cpos[i] <= (unsigned)j);
-                }
-                if (j + shift < ef) { ls[nxt][j + shift] = ls[cur][j]; li[nxt][j + shift] = li[cur][j]; }
-            }
+            __syncthreads();                              // every old entry is out of the way
+            if (new_at >= 0) { ls[cur][new_at] = new_s; li[cur][new_at] = (uint32_t)new_v; }
         }
         len = min(ef, len + n_new);
         cur = nxt;

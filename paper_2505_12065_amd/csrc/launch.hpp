@@ -47,6 +47,7 @@ hipError_t launch_flat_f32(int kp, const float *X, int64_t N, int d, const float
 hipError_t launch_flat_merge(int kp, const Cand *partial, int P, int B, int k, int32_t *ids, float *scores,
                              hipStream_t stream);
 
+constexpr int GRAPH_EF_DOUBLE = 2048;    // candidate lists up to this length are double-buffered in LDS
 struct GraphLds {
     // byte offsets into dynamic LDS; all 16-byte aligned
     uint32_t q, ls0, ls1, li0, li1, cs, ci, cpos, cache, ctl, adj, um, rq, co, total;

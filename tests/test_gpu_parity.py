@@ -207,6 +207,28 @@ def test_graph_shapes(R, ef, k):
     assert strict >= n - 2, (strict, n)
 
 
+@pytest.mark.parametrize("ef,R,dtype", [(2049, 32, torch.float16), (3000, 12, torch.float16), (6000, 32, torch.bfloat16),
+                                        (16384, 40, torch.float16), (5000, 32, torch.float32)])
+def test_graph_long_lists(ef, R, dtype):
+    """Lists longer than 2048 entries: one LDS buffer merged in place, exact visited bitset."""
+    N = 30_000
+    say(f"graph long list: ef={ef} R={R} {dtype}")
+    c = synth.make_corpus(N, 64, 12, seed=ef, dtype=dtype, zipf_a=None, sigma=0.35)
+    q = synth.make_queries(c, 6)
+    g = synth.ring_union(synth.knn_graph(c.x.to(DEV), R - 2).cpu()).contiguous()
+    ids, sc = ann.ann_graph_search_typed(c.x.to(DEV), g.to(DEV), 7, q.to(DEV), 5, ef)
+    torch.cuda.synchronize()
+    name = np_dtype_name(c.x)
+    o_ids, _, o_sc64, nd, ne = oracle.graph_search(to_np(c.x), g.numpy(), 7, to_np(q), 5, ef, dtype=name)
+    strict, tolerant, n = compare_topk(ids.cpu().numpy(), sc.cpu().numpy(), o_ids, o_sc64, to_np(c.x), to_np(q), dtype=name)
+    say(f"  strict {strict}/{n}, oracle expansions {ne.mean():.0f}, scored {nd.mean():.0f}")
+    assert strict >= n - 1
+    # the counters of the long-list path through the non-stall entry point are the oracle's
+    _, _, stats, _ = ann.ann_graph_search_nonstall_typed(c.x.to(DEV), g.to(DEV), 7, q.to(DEV), 5, ef, tau=float("inf"))
+    st = stats.cpu().numpy()
+    assert np.abs(st[:, 1] - nd).max() <= max(8, nd.max() // 100) and np.abs(st[:, 2] - ne).max() <= max(4, ne.max() // 100)
+
+
 def test_graph_padding_when_few_nodes_are_reachable():
     c = synth.make_corpus(200, 64, 4, seed=2, dtype=torch.float16, zipf_a=None, sigma=0.3)
     q = synth.make_queries(c, 4)
