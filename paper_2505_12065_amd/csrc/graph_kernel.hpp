@@ -408,22 +408,31 @@ __global__ __launch_bounds__(GRAPH_THREADS) void graph_search_kernel(
         cur = nxt;
         __syncthreads();
 
-        // best and second-best unexpanded entries of the new list: one ballot per 64 entries
-        const int words = (len + 63) >> 6;
-        for (int j0 = 0; j0 < len; j0 += GRAPH_THREADS) {
-            const int j = j0 + tid;
-            const uint64_t m = __builtin_amdgcn_ballot_w64(j < len && !(li[cur][j] & EXPANDED));
-            if (lane == 0 && (j0 >> 6) + wave < words) um[(j0 >> 6) + wave] = m;
-        }
-        __syncthreads();
-        p = -1;
-        p2 = -1;
-        for (int w = 0; w < words && p2 < 0; ++w) {
-            uint64_t m = um[w];
-            while (m != 0 && p2 < 0) {
-                const int j = w * 64 + __builtin_ctzll(m);
-                m &= m - 1;
-                if (p < 0) p = j; else p2 = j;
+        // Best and second-best unexpanded entries of the new list: one ballot per 64 entries.
+        // Everything before the entry just expanded was expanded already, and the merge has not
+        // touched the list before its lowest insertion, so the scan starts at the lower of the
+        // two and goes on, 256 entries per round, only until two are found (one round as a rule,
+        // whatever the length of the list).
+        {
+            const unsigned first = min((unsigned)p, jmin);
+            p = -1;
+            p2 = -1;
+            for (int base = (int)first & ~(GRAPH_THREADS - 1); base < len; base += GRAPH_THREADS) {
+                const int j = base + tid;
+                const uint64_t m = __builtin_amdgcn_ballot_w64(j < len && !(li[cur][j] & EXPANDED));
+                if (lane == 0) um[wave] = m;
+                __syncthreads();
+#pragma unroll
+                for (int w = 0; w < GRAPH_WAVES; ++w) {
+                    uint64_t mw = um[w];
+                    while (mw != 0 && p2 < 0) {
+                        const int jj = base + w * 64 + __builtin_ctzll(mw);
+                        mw &= mw - 1;
+                        if (p < 0) p = jj; else p2 = jj;
+                    }
+                }
+                if (p2 >= 0) break;
+                __syncthreads();                          // um is rewritten in the next round
             }
         }
         if (NS) ema = ema_s[0];                           // written before the last two barriers
