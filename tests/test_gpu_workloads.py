@@ -159,3 +159,37 @@ def test_cfg4_graph_full_size():
         assert strict >= n - 3
     del xh, gh, c, g
     torch.cuda.empty_cache()
+
+
+# ------------------------------------------------------------------ paper-shaped workload, scaled (d = 384, k = 5)
+
+def test_paper_shape_scaled_two_level_search():
+    """The shape of the paper's own index (384-d, at most 32 neighbours, k = 5, search ranges into the
+    thousands; Appendix B.3) at 2 % of its 21 M rows: coarse entry search over one representative per
+    cluster, then graph search from there, every query against the oracle started at the same entry."""
+    N, d, C = 420_000, 384, 82
+    c = synth.make_corpus(N, d, C, seed=5, sigma=(0.2, 0.5), zipf_a=1.1, dtype=torch.float16, device=DEV)
+    q = synth.make_queries(c, 48, noise_std=0.05 / np.sqrt(d))
+    g = synth.with_reverse_edges(synth.knn_graph_cluster_restricted(c, 32, 8), c.x)
+    reps = synth.cluster_representatives(c)
+    rep_rows = c.x[reps.long()].contiguous()
+    cid, _ = ann.ann_flat_search_typed(rep_rows, q, 1)
+    entries = ann.ann_gather_ids(reps, cid.view(-1))
+    exact, _ = ann.ann_flat_search_typed(c.x, q, 5)
+    torch.cuda.synchronize()
+    xh, gh, qh, eh = c.x.cpu().numpy(), g.cpu().numpy(), q.cpu().numpy(), entries.cpu().numpy()
+    o_cid, _, _ = oracle.flat_search(xh[reps.cpu().numpy()], qh, 1)
+    assert eh.tolist() == reps.cpu().numpy()[o_cid[:, 0]].tolist()
+    o_exact, _, o_exact64 = oracle.flat_search(xh, qh[:8], 5)
+    compare_topk(exact[:8].cpu().numpy(), ann.ann_flat_search_typed(c.x, q, 5)[1][:8].cpu().numpy(), o_exact, o_exact64, xh, qh)
+    for ef in (256, 4096):
+        ids, sc = ann.ann_graph_search_entries_typed(c.x, g, entries, q, 5, ef)
+        torch.cuda.synchronize()
+        ids, sc = ids.cpu().numpy(), sc.cpu().numpy()
+        strict = 0
+        for b in range(48):
+            o_ids, _, o_sc64, _, _ = oracle.graph_search(xh, gh, int(eh[b]), qh[b:b + 1], 5, ef)
+            st, _, _ = compare_topk(ids[b:b + 1], sc[b:b + 1], o_ids, o_sc64, xh, qh, rows=[b])
+            strict += st
+        say(f"paper shape (N={N}, d={d}) ef={ef}: strict {strict}/48, recall@5 {recall(ids, exact.cpu().numpy()):.3f}")
+        assert strict >= 46
