@@ -163,6 +163,13 @@ def main() -> int:
         "graph_b512": {"bound": "hbm", "achieved": graph_bytes / kernel_ms["graph_b512"] / 1e6, "peak": HBM_PEAK_GBS,
                        "unit": "GB/s"},
     }
+    # what the matrix cores of this machine sustain on register operands (no memory traffic at all): with one
+    # constant operand the nominal peak, with random operands that change every instruction much less
+    # (clocks follow the switching activity); the second is the ceiling for a kernel fed with real data
+    mfma_box = {"constant_operands_TFLOPs": ann.ann_measure_mfma_rate(False),
+                "random_operands_TFLOPs": ann.ann_measure_mfma_rate(True)}
+    rooflines["flat_b512"]["box_mfma_rate"] = mfma_box
+    rooflines["flat_b512"]["frac_of_box_random_operand_rate"] = rooflines["flat_b512"]["achieved"] / mfma_box["random_operands_TFLOPs"]
     traffic = measured_traffic()
     for i, (leg, r) in enumerate(rooflines.items()):
         r["frac"] = r["achieved"] / r["peak"]

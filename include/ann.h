@@ -219,6 +219,14 @@ int ann_timing_enable(int32_t on);
  * number and the sum of their durations in milliseconds.  Host pointers. */
 int ann_timing_read(int32_t kernel, int32_t *launches, double *total_ms);
 
+/* Measurement support (no paper passage): the dense fp16 MFMA rate the current device sustains
+ * on register-resident operands, in TFLOP/s, on the default stream (synchronises it).  With
+ * random_operands != 0 the operands are random fp16 values that change from one MFMA to the
+ * next, as in a real contraction; with 0 they are one constant.  On parts whose clocks follow
+ * the switching activity of the data the two differ widely; the first is the ceiling a kernel
+ * working on real data can be held against.  iters: MFMA groups per wave (100000 runs ~30 ms). */
+int ann_measure_mfma_rate(int32_t random_operands, int32_t iters, double *tflops);
+
 #ifdef __cplusplus
 }
 #endif

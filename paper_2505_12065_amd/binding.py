@@ -23,7 +23,8 @@ EXPORTS = ("ann_version", "ann_last_error", "ann_flat_search_typed", "ann_flat_s
            "ann_graph_search_typed", "ann_graph_search", "ann_register_corpus", "ann_unregister_corpus",
            "ann_set_default_dtype", "ann_flat_workspace_bytes", "ann_release_workspace",
            "ann_graph_search_nonstall_typed", "ann_graph_nonstall_workspace_bytes",
-           "ann_graph_search_entries_typed", "ann_gather_ids", "ann_timing_enable", "ann_timing_read")
+           "ann_graph_search_entries_typed", "ann_gather_ids", "ann_timing_enable", "ann_timing_read",
+           "ann_measure_mfma_rate")
 
 
 class AnnError(RuntimeError):
@@ -61,6 +62,7 @@ def lib() -> ctypes.CDLL:
                                                       c.c_float, i32, vp, vp, vp, vp, vp, vp]
         L.ann_graph_search_entries_typed.argtypes = [vp, i64, i32, i32, vp, i32, vp, vp, i32, i32, i32, vp, vp, vp]
         L.ann_gather_ids.argtypes = [vp, i64, vp, i64, vp, vp]
+        L.ann_measure_mfma_rate.argtypes = [i32, i32, c.POINTER(c.c_double)]
         L.ann_timing_enable.argtypes = [i32]
         L.ann_timing_read.argtypes = [i32, c.POINTER(i32), c.POINTER(c.c_double)]
         L.ann_graph_nonstall_workspace_bytes.argtypes = [i64, i32]
@@ -241,6 +243,13 @@ def ann_gather_ids(table: torch.Tensor, idx: torch.Tensor, *, out=None, stream=N
 
 
 KERNEL_FLAT_STREAM, KERNEL_FLAT_WIDE, KERNEL_FLAT_F32, KERNEL_GRAPH = 0, 1, 2, 3
+
+
+def ann_measure_mfma_rate(random_operands: bool, iters: int = 100000) -> float:
+    """Dense fp16 MFMA rate (TFLOP/s) the current device sustains on register operands."""
+    out = ctypes.c_double(0.0)
+    _check(lib().ann_measure_mfma_rate(1 if random_operands else 0, int(iters), ctypes.byref(out)))
+    return out.value
 
 
 def ann_timing_enable(on: bool) -> None:

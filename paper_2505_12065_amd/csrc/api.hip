@@ -320,6 +320,28 @@ int ann_timing_read(int32_t kernel, int32_t *launches, double *total_ms) {
     return ANN_OK;
 }
 
+int ann_measure_mfma_rate(int32_t random_operands, int32_t iters, double *tflops) {
+    if (!tflops || iters < 1) return fail(ANN_ERR_INVALID, "ann_measure_mfma_rate: bad arguments");
+    std::lock_guard<std::mutex> lock(g_mu);
+    DeviceState *st = nullptr;
+    if (int rc = device_state(&st)) return rc;
+    if (int rc = grow(&st->ws, &st->ws_bytes, 256)) return rc;
+    hipEvent_t a = pooled_event(), b = pooled_event();
+    if (!a || !b) return fail(ANN_ERR_LAUNCH, "cannot create events");
+    float ms = 0.f;
+    hipError_t e = launch_mfma_rate(random_operands != 0, st->cus, iters, static_cast<float *>(st->ws), nullptr);   // warm-up
+    if (e == hipSuccess) e = hipEventRecord(a, nullptr);
+    if (e == hipSuccess) e = launch_mfma_rate(random_operands != 0, st->cus, iters, static_cast<float *>(st->ws), nullptr);
+    if (e == hipSuccess) e = hipEventRecord(b, nullptr);
+    if (e == hipSuccess) e = hipEventSynchronize(b);
+    if (e == hipSuccess) e = hipEventElapsedTime(&ms, a, b);
+    g_event_pool.push_back(a);
+    g_event_pool.push_back(b);
+    if (int rc = check_launch("mfma_rate_kernel", e)) return rc;
+    *tflops = (double)st->cus * 8.0 * iters * 8.0 * 32768.0 / ((double)ms * 1e9);
+    return ANN_OK;
+}
+
 int ann_release_workspace(void) {
     std::lock_guard<std::mutex> lock(g_mu);
     DeviceState *st = nullptr;

@@ -52,4 +52,38 @@ hipError_t launch_flat_sample_merge(int kp, const Cand *src, int Ps, int B, Cand
     return hipGetLastError();
 }
 
+// ---- measurement support: what the matrix cores of this device sustain --------------------------
+// Eight independent 32x32x16 fp16 accumulators per wave, 8 waves per workgroup, one workgroup per
+// compute unit, operands held in registers (no LDS or memory traffic).  With RANDOM the operand
+// registers hold random fp16 values and differ from one MFMA to the next, as in a real contraction;
+// without, one constant: the difference is what data-dependent power management costs.
+template <bool RANDOM>
+__global__ __launch_bounds__(512) void mfma_rate_kernel(float *out, int iters) {
+    u4 ra[4], rb[2];
+    uint32_t h = threadIdx.x * 2654435761u + blockIdx.x * 40503u + 12345u;
+    auto next = [&]() {
+        h ^= h << 13; h ^= h >> 17; h ^= h << 5;
+        return RANDOM ? ((h & 0x83ff83ffu) | 0x2c002c00u) : 0x211f211fu;   // fp16 pairs of magnitude 1/16 .. 1/8
+    };
+    for (int i = 0; i < 4; ++i) for (int c = 0; c < 4; ++c) ra[i][c] = next();
+    for (int i = 0; i < 2; ++i) for (int c = 0; c < 4; ++c) rb[i][c] = next();
+    f16v acc[8];
+    for (int j = 0; j < 8; ++j) for (int r = 0; r < 16; ++r) acc[j][r] = 0.f;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int j = 0; j < 2; ++j) acc[i * 2 + j] = mfma32<F16>(ra[i], rb[j], acc[i * 2 + j]);
+    }
+    float s = 0.f;
+    for (int j = 0; j < 8; ++j) for (int r = 0; r < 16; ++r) s += acc[j][r];
+    if (s == 12345.678f) out[0] = s;                   // keeps the loop alive, never true in practice
+}
+
+hipError_t launch_mfma_rate(bool random_operands, int cus, int iters, float *sink, hipStream_t stream) {
+    if (random_operands) hipLaunchKernelGGL(mfma_rate_kernel<true>, dim3(cus), dim3(512), 0, stream, sink, iters);
+    else hipLaunchKernelGGL(mfma_rate_kernel<false>, dim3(cus), dim3(512), 0, stream, sink, iters);
+    return hipGetLastError();
+}
+
 }  // namespace ann

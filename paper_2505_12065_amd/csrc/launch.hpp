@@ -48,6 +48,9 @@ hipError_t launch_flat_merge(int kp, const Cand *partial, int P, int B, int k, i
                              hipStream_t stream);
 
 constexpr int GRAPH_EF_DOUBLE = 2048;    // candidate lists up to this length are double-buffered in LDS
+// cus workgroups of 8 waves, each wave iters x 8 MFMA 32x32x16 fp16 (32768 flop each) on register operands
+hipError_t launch_mfma_rate(bool random_operands, int cus, int iters, float *sink, hipStream_t stream);
+
 struct GraphLds {
     // byte offsets into dynamic LDS; all 16-byte aligned
     uint32_t q, ls0, ls1, li0, li1, cs, ci, cpos, cache, ctl, adj, um, rq, co, total;
