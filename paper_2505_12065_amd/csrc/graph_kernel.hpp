@@ -65,8 +65,10 @@ __global__ __launch_bounds__(GRAPH_THREADS) void graph_search_kernel(
     GraphLds L, NonStall ns) {
     extern __shared__ __align__(16) unsigned char smem[];
     u4 *qs = reinterpret_cast<u4 *>(smem + L.q);
-    float *ls[2] = {reinterpret_cast<float *>(smem + L.ls0), reinterpret_cast<float *>(smem + L.ls1)};
-    uint32_t *li[2] = {reinterpret_cast<uint32_t *>(smem + L.li0), reinterpret_cast<uint32_t *>(smem + L.li1)};
+    // the two list buffers, selected by offset arithmetic on the LDS base (an array of pointers
+    // indexed at run time would turn every list access into a generic-address load)
+    auto ls = [&](int which) { return reinterpret_cast<float *>(smem + (which ? L.ls1 : L.ls0)); };
+    auto li = [&](int which) { return reinterpret_cast<uint32_t *>(smem + (which ? L.li1 : L.li0)); };
     float *cs = reinterpret_cast<float *>(smem + L.cs);
     int *ci = reinterpret_cast<int *>(smem + L.ci);
     int *cpos = reinterpret_cast<int *>(smem + L.cpos);
@@ -135,8 +137,8 @@ __global__ __launch_bounds__(GRAPH_THREADS) void graph_search_kernel(
     if (grp == 0) {
         const float s = score_row(entry);
         if (sub == 0) {
-            ls[0][0] = s;
-            li[0][0] = (uint32_t)entry;
+            ls(0)[0] = s;
+            li(0)[0] = (uint32_t)entry;
             cache[((uint32_t)entry * 2654435761u) >> cache_shift] = entry;
             if (NS) atomicOr(&seen_bits[entry >> 5], 1u << (entry & 31));
         }
@@ -155,12 +157,12 @@ __global__ __launch_bounds__(GRAPH_THREADS) void graph_search_kernel(
     for (;;) {
         if (p < 0) break;                                 // nothing left to expand: natural stop
         ++n_expand;
-        const int node = (int)(li[cur][p] & ~EXPANDED);
-        const int node2 = p2 >= 0 ? (int)(li[cur][p2] & ~EXPANDED) : -1;
+        const int node = (int)(li(cur)[p] & ~EXPANDED);
+        const int node2 = p2 >= 0 ? (int)(li(cur)[p2] & ~EXPANDED) : -1;
         const int have = adj_id[0] == node ? 0 : (adj_id[1] == node ? 1 : -1);
         const bool have2 = node2 < 0 || adj_id[0] == node2 || adj_id[1] == node2;
         __syncthreads();                                  // all have read the list and adj_id
-        if (tid == 0) li[cur][p] |= EXPANDED;
+        if (tid == 0) li(cur)[p] |= EXPANDED;
 
         // Read-ahead: the second-best unexpanded entry is the most likely next expansion, so
         // its adjacency row is fetched now, under the gathers of this expansion.  It only
@@ -233,8 +235,8 @@ __global__ __launch_bounds__(GRAPH_THREADS) void graph_search_kernel(
                     for (int j = 0; j < i; ++j) dup |= (int)(ci[j] == v);
                 }
                 if (!dup && s == s) {                      // a NaN score is never listed
-                    pos = list_lower_bound(ls[cur], li[cur], len, s, v);
-                    if (pos >= ef || (pos < len && (int)(li[cur][pos] & ~EXPANDED) == v)) pos = -1;
+                    pos = list_lower_bound(ls(cur), li(cur), len, s, v);
+                    if (pos >= ef || (pos < len && (int)(li(cur)[pos] & ~EXPANDED) == v)) pos = -1;
                 }
             }
             cpos[i] = pos;
@@ -243,7 +245,7 @@ __global__ __launch_bounds__(GRAPH_THREADS) void graph_search_kernel(
         // others (for short rows and lists that is all on wave 0), and handed over in LDS.
         if (NS && wave == GRAPH_WAVES - 1) {
             // best / worst of the list as it stands before this expansion's entries go in
-            const float s_best = ls[cur][0], s_worst = ls[cur][len - 1];
+            const float s_best = ls(cur)[0], s_worst = ls(cur)[len - 1];
             // RQ of slot i, or NaN: no newly scored node there, or -inf: one, but best == worst.
             // An id named more than once in the row is scored by whichever slot won the race
             // for the cache entry (rarely by two); its one sample belongs to the first slot
@@ -279,13 +281,23 @@ __global__ __launch_bounds__(GRAPH_THREADS) void graph_search_kernel(
                         const int4 oq = o4[j >> 2], iq = i4[j >> 2];
                         const int oj = (j & 3) == 0 ? oq.x : (j & 3) == 1 ? oq.y : (j & 3) == 2 ? oq.z : oq.w;
                         const int ij = (j & 3) == 0 ? iq.x : (j & 3) == 1 ? iq.y : (j & 3) == 2 ? iq.z : iq.w;
-                        if (j < lane && oj == me) first = false;
-                        if (ij == me) { scored = true; sv = s4[j >> 2][j & 3]; }
+                        first &= !((j < lane) & (oj == me));
+                        scored |= (ij == me);
+                        sv = (ij == me) ? s4[j >> 2][j & 3] : sv;
                     }
                     r = rq_of(lane, me, first, scored, sv);
                 }
-#pragma unroll
-                for (int i = 0; i < 32; ++i) take(__int_as_float(__builtin_amdgcn_readlane(__float_as_int(r), i)));
+                // only the slots that hold a sample are visited (about a third of them), in slot order
+                // (tests on the bit pattern: not NaN = a newly scored node, finite = with a defined RQ)
+                const uint32_t mag = __float_as_uint(r) & 0x7fffffffu;
+                n_dist += __builtin_popcountll(__builtin_amdgcn_ballot_w64(mag <= 0x7f800000u));
+                uint64_t defined = __builtin_amdgcn_ballot_w64(mag < 0x7f800000u);
+                while (defined != 0) {
+                    const int i = __builtin_ctzll(defined);
+                    defined &= defined - 1;
+                    const float ri = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(r), i));
+                    ema = fmaf(ns.alpha, ri - ema, ema);
+                }
             } else {
                 for (int i = lane; i < RP; i += WAVE) {
                     const int me = co[i];
@@ -372,10 +384,10 @@ __global__ __launch_bounds__(GRAPH_THREADS) void graph_search_kernel(
             }
         }
         if (!inplace) {
-            if (new_at >= 0) { ls[nxt][new_at] = new_s; li[nxt][new_at] = (uint32_t)new_v; }
+            if (new_at >= 0) { ls(nxt)[new_at] = new_s; li(nxt)[new_at] = (uint32_t)new_v; }
             for (int j = tid; j < len; j += GRAPH_THREADS) {
                 const int shift = n_new ? shift_of(j) : 0;
-                if (j + shift < ef) { ls[nxt][j + shift] = ls[cur][j]; li[nxt][j + shift] = li[cur][j]; }
+                if (j + shift < ef) { ls(nxt)[j + shift] = ls(cur)[j]; li(nxt)[j + shift] = li(cur)[j]; }
             }
         } else if (n_new) {
             // Entries below jmin stay.  The others move up by at most RP: chunks of MOVE entries
@@ -389,7 +401,7 @@ __global__ __launch_bounds__(GRAPH_THREADS) void graph_search_kernel(
 #pragma unroll
                 for (int u = 0; u < PER; ++u) {
                     const int j = base + u * GRAPH_THREADS + tid;
-                    if (j < len && j >= (int)jmin) { ms[u] = ls[cur][j]; mi[u] = li[cur][j]; }
+                    if (j < len && j >= (int)jmin) { ms[u] = ls(cur)[j]; mi[u] = li(cur)[j]; }
                 }
                 __syncthreads();
 #pragma unroll
@@ -397,12 +409,12 @@ __global__ __launch_bounds__(GRAPH_THREADS) void graph_search_kernel(
                     const int j = base + u * GRAPH_THREADS + tid;
                     if (j < len && j >= (int)jmin) {
                         const int to = j + shift_of(j);
-                        if (to < ef) { ls[cur][to] = ms[u]; li[cur][to] = mi[u]; }
+                        if (to < ef) { ls(cur)[to] = ms[u]; li(cur)[to] = mi[u]; }
                     }
                 }
             }
             __syncthreads();                              // every old entry is out of the way
-            if (new_at >= 0) { ls[cur][new_at] = new_s; li[cur][new_at] = (uint32_t)new_v; }
+            if (new_at >= 0) { ls(cur)[new_at] = new_s; li(cur)[new_at] = (uint32_t)new_v; }
         }
         len = min(ef, len + n_new);
         cur = nxt;
@@ -419,7 +431,7 @@ __global__ __launch_bounds__(GRAPH_THREADS) void graph_search_kernel(
             p2 = -1;
             for (int base = (int)first & ~(GRAPH_THREADS - 1); base < len; base += GRAPH_THREADS) {
                 const int j = base + tid;
-                const uint64_t m = __builtin_amdgcn_ballot_w64(j < len && !(li[cur][j] & EXPANDED));
+                const uint64_t m = __builtin_amdgcn_ballot_w64(j < len && !(li(cur)[j] & EXPANDED));
                 if (lane == 0) um[wave] = m;
                 __syncthreads();
 #pragma unroll
@@ -449,8 +461,8 @@ __global__ __launch_bounds__(GRAPH_THREADS) void graph_search_kernel(
 
     for (int j = tid; j < k; j += GRAPH_THREADS) {
         const bool has = j < len;
-        ids[(size_t)b * k + j] = has ? (int)(li[cur][j] & ~EXPANDED) : -1;
-        scores[(size_t)b * k + j] = has ? ls[cur][j] : -INFINITY;
+        ids[(size_t)b * k + j] = has ? (int)(li(cur)[j] & ~EXPANDED) : -1;
+        scores[(size_t)b * k + j] = has ? ls(cur)[j] : -INFINITY;
     }
     if (NS && tid == GRAPH_THREADS - WAVE) {
         if (ns.stats) {
