@@ -61,6 +61,7 @@ extern "C" {
 #define ANN_EF_MAX   16384   /* largest candidate list of the graph search (k <= ef) */
 #define ANN_R_MAX    256     /* largest graph out-degree */
 #define ANN_D_MAX    4096    /* largest embedding dimension */
+#define ANN_REQUESTS_MAX 65536 /* largest request batch of ann_priority_order */
 
 /* Library version as major*10000 + minor*100 + patch. */
 int ann_version(void);
@@ -218,6 +219,20 @@ int ann_timing_enable(int32_t on);
 /* Waits for the recorded launches of `kernel` (an ANN_KERNEL_* code) and returns their
  * number and the sum of their durations in milliseconds.  Host pointers. */
 int ann_timing_read(int32_t kernel, int32_t *launches, double *total_ms);
+
+/* Priority levels and execution order of the request scheduler (Section 3.2 "Priority
+ * Scheduling", Eq. 1 and 2).  Metrics of request i: R[i] retrievals completed, W[i] waiting time
+ * of the initial request, C[i] context length; for each metric M and level j in [0, G),
+ * T_{M,j} = min(M) + j/G (max(M) - min(M)); level[i] = the largest j with R[i] > T_{R,j} or
+ * W[i] > T_{W,j} or C[i] > T_{C,j}, 0 if there is none.  order[] lists the requests in execution
+ * order: levels from the highest down, inside a level by the current queueing time Wcur[i],
+ * longest first (equal times in index order).  Thresholds are evaluated in binary64.
+ *
+ *   R, C, level, order   device int32 [n];   W, Wcur   device double [n]
+ *   1 <= n <= ANN_REQUESTS_MAX, 1 <= G <= 1024 (the paper uses G = 6)
+ * Not part of the retrieval path; no workspace; errors as elsewhere. */
+int ann_priority_order(const int32_t *R, const double *W, const int32_t *C, const double *Wcur,
+                       int32_t n, int32_t G, int32_t *level, int32_t *order, void *stream);
 
 /* Measurement support (no paper passage): the dense fp16 MFMA rate the current device sustains
  * on register-resident operands, in TFLOP/s, on the default stream (synchronises it).  With

@@ -61,6 +61,9 @@ def _load():
                                                      c.c_int32, c.c_void_p, c.c_int32, c.c_int32, c.c_int32,
                                                      c.c_float, c.c_int32, c.c_int64, c.c_int64,
                                                      c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_int]
+        lib.oracle_priority_order.restype = c.c_int
+        lib.oracle_priority_order.argtypes = [c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_int32, c.c_int32,
+                                              c.c_void_p, c.c_void_p]
         _lib = lib
     return _lib
 
@@ -156,6 +159,25 @@ def graph_search_nonstall(corpus, graph, entry: int, queries, k: int, ef: int, *
     if rc != 0:
         raise ValueError("oracle_graph_search_nonstall: bad arguments")
     return ids, sc, sc64, stats, ema
+
+
+def priority_order(R, W, C, Wcur, G: int):
+    """Scheduler priority levels (Section 3.2, Eq. 1-2) and execution order.
+    R, C int32 [n]; W, Wcur float64 [n].  Returns (level int32 [n], order int32 [n])."""
+    R = np.ascontiguousarray(R, dtype=np.int32)
+    C = np.ascontiguousarray(C, dtype=np.int32)
+    W = np.ascontiguousarray(W, dtype=np.float64)
+    Wcur = np.ascontiguousarray(Wcur, dtype=np.float64)
+    n = R.shape[0]
+    if not (W.shape == C.shape == Wcur.shape == (n,)):
+        raise ValueError("R, W, C, Wcur must have the same length")
+    level = np.empty(n, np.int32)
+    order = np.empty(n, np.int32)
+    rc = _load().oracle_priority_order(R.ctypes.data, W.ctypes.data, C.ctypes.data, Wcur.ctypes.data, n, G,
+                                       level.ctypes.data, order.ctypes.data)
+    if rc != 0:
+        raise ValueError("oracle_priority_order: bad arguments")
+    return level, order
 
 
 def recall_at_k(approx_ids: np.ndarray, exact_ids: np.ndarray) -> float:

@@ -352,3 +352,45 @@ int oracle_graph_search_nonstall(const void *corpus, int64_t N, int32_t d, int d
     }
     return failed ? -1 : 0;
 }
+
+/*
+ * Priority levels and execution order of the scheduler (Section 3.2, Eq. 1-2).
+ *
+ * Metrics of request i: R_i retrievals completed, W_i waiting time of the initial request,
+ * C_i context length.  For each metric M and level j in [0, G): T_{M,j} = min(M) + j/G (max(M) - min(M)).
+ * level_i = the largest j with R_i > T_{R,j} or W_i > T_{W,j} or C_i > T_{C,j}; 0 if there is none.
+ * Execution order: levels from the highest down; inside a level by the current queueing time
+ * Wcur_i, longest first (reading: equal times in index order).
+ * Arithmetic in binary64, the threshold as one fused multiply-add fma(j/G, max - min, min): the
+ * GPU routine uses the same expression, so the integer decisions are taken in the same precision.
+ */
+int oracle_priority_order(const int32_t *R, const double *W, const int32_t *C, const double *Wcur,
+                          int32_t n, int32_t G, int32_t *level, int32_t *order)
+{
+    if (!R || !W || !C || !Wcur || !level || !order || n < 1 || G < 1) return -1;
+    double mn[3], mx[3];
+    for (int m = 0; m < 3; ++m) { mn[m] = INFINITY; mx[m] = -INFINITY; }
+    for (int32_t i = 0; i < n; ++i) {
+        const double v[3] = {(double)R[i], W[i], (double)C[i]};
+        for (int m = 0; m < 3; ++m) { if (v[m] < mn[m]) mn[m] = v[m]; if (v[m] > mx[m]) mx[m] = v[m]; }
+    }
+    for (int32_t i = 0; i < n; ++i) {
+        const double v[3] = {(double)R[i], W[i], (double)C[i]};
+        int32_t best = 0;
+        for (int32_t j = 0; j < G; ++j)
+            for (int m = 0; m < 3; ++m)
+                if (v[m] > fma((double)j / (double)G, mx[m] - mn[m], mn[m])) best = j;
+        level[i] = best;
+    }
+    /* stable selection: position of i = number of requests that go before it */
+    for (int32_t i = 0; i < n; ++i) {
+        int32_t before = 0;
+        for (int32_t j = 0; j < n; ++j) {
+            if (j == i) continue;
+            if (level[j] > level[i] || (level[j] == level[i] && (Wcur[j] > Wcur[i] || (Wcur[j] == Wcur[i] && j < i))))
+                ++before;
+        }
+        order[before] = i;
+    }
+    return 0;
+}

@@ -24,7 +24,7 @@ EXPORTS = ("ann_version", "ann_last_error", "ann_flat_search_typed", "ann_flat_s
            "ann_set_default_dtype", "ann_flat_workspace_bytes", "ann_release_workspace",
            "ann_graph_search_nonstall_typed", "ann_graph_nonstall_workspace_bytes",
            "ann_graph_search_entries_typed", "ann_gather_ids", "ann_timing_enable", "ann_timing_read",
-           "ann_measure_mfma_rate")
+           "ann_measure_mfma_rate", "ann_priority_order")
 
 
 class AnnError(RuntimeError):
@@ -63,6 +63,7 @@ def lib() -> ctypes.CDLL:
         L.ann_graph_search_entries_typed.argtypes = [vp, i64, i32, i32, vp, i32, vp, vp, i32, i32, i32, vp, vp, vp]
         L.ann_gather_ids.argtypes = [vp, i64, vp, i64, vp, vp]
         L.ann_measure_mfma_rate.argtypes = [i32, i32, c.POINTER(c.c_double)]
+        L.ann_priority_order.argtypes = [vp, vp, vp, vp, i32, i32, vp, vp, vp]
         L.ann_timing_enable.argtypes = [i32]
         L.ann_timing_read.argtypes = [i32, c.POINTER(i32), c.POINTER(c.c_double)]
         L.ann_graph_nonstall_workspace_bytes.argtypes = [i64, i32]
@@ -243,6 +244,21 @@ def ann_gather_ids(table: torch.Tensor, idx: torch.Tensor, *, out=None, stream=N
 
 
 KERNEL_FLAT_STREAM, KERNEL_FLAT_WIDE, KERNEL_FLAT_F32, KERNEL_GRAPH = 0, 1, 2, 3
+
+
+def ann_priority_order(R: torch.Tensor, W: torch.Tensor, C: torch.Tensor, Wcur: torch.Tensor, G: int = 6, *,
+                       stream=None) -> Tuple[torch.Tensor, torch.Tensor]:
+    """Scheduler priority levels and execution order.  R, C int32 [n]; W, Wcur float64 [n]; device tensors."""
+    n = R.numel()
+    for t, dt in ((R, torch.int32), (C, torch.int32), (W, torch.float64), (Wcur, torch.float64)):
+        if t.dtype != dt or t.numel() != n or not t.is_contiguous() or not t.is_cuda:
+            raise ValueError("R, C must be int32 and W, Wcur float64 contiguous device tensors of one length")
+    level = torch.empty(n, dtype=torch.int32, device=R.device)
+    order = torch.empty(n, dtype=torch.int32, device=R.device)
+    with torch.cuda.device(R.device):
+        _check(lib().ann_priority_order(R.data_ptr(), W.data_ptr(), C.data_ptr(), Wcur.data_ptr(), n, int(G),
+                                        level.data_ptr(), order.data_ptr(), _stream(stream)))
+    return level, order
 
 
 def ann_measure_mfma_rate(random_operands: bool, iters: int = 100000) -> float:

@@ -320,6 +320,20 @@ int ann_timing_read(int32_t kernel, int32_t *launches, double *total_ms) {
     return ANN_OK;
 }
 
+int ann_priority_order(const int32_t *R, const double *W, const int32_t *C, const double *Wcur, int32_t n, int32_t G,
+                       int32_t *level, int32_t *order, void *stream) {
+    if (!R || !W || !C || !Wcur || !level || !order) return fail(ANN_ERR_INVALID, "null pointer argument");
+    if (n < 1 || n > ANN_REQUESTS_MAX) return fail(ANN_ERR_INVALID, "n = %d out of range [1, %d]", n, ANN_REQUESTS_MAX);
+    if (G < 1 || G > 1024) return fail(ANN_ERR_INVALID, "G = %d out of range [1, 1024]", G);
+    if ((reinterpret_cast<uintptr_t>(W) | reinterpret_cast<uintptr_t>(Wcur)) & 7)
+        return fail(ANN_ERR_ALIGNMENT, "W and Wcur must be 8-byte aligned");
+    if ((reinterpret_cast<uintptr_t>(R) | reinterpret_cast<uintptr_t>(C) | reinterpret_cast<uintptr_t>(level) |
+         reinterpret_cast<uintptr_t>(order)) & 3)
+        return fail(ANN_ERR_ALIGNMENT, "R, C, level and order must be 4-byte aligned");
+    return check_launch("priority kernels",
+                        launch_priority(R, W, C, Wcur, n, G, level, order, static_cast<hipStream_t>(stream)));
+}
+
 int ann_measure_mfma_rate(int32_t random_operands, int32_t iters, double *tflops) {
     if (!tflops || iters < 1) return fail(ANN_ERR_INVALID, "ann_measure_mfma_rate: bad arguments");
     std::lock_guard<std::mutex> lock(g_mu);

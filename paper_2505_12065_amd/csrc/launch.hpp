@@ -82,4 +82,8 @@ hipError_t launch_graph_search_nonstall(int dtype, const void *X, int64_t N, int
                                         int entry, const void *Q, int B, int k, int ef, int32_t *ids, float *scores,
                                         const GraphLds &L, const NonStall &ns, hipStream_t stream);
 
+// Scheduler priority levels (Section 3.2, Eq. 1-2) and execution order; all arrays device, length n.
+hipError_t launch_priority(const int32_t *R, const double *W, const int32_t *C, const double *Wcur, int n, int G,
+                           int32_t *level, int32_t *order, hipStream_t stream);
+
 }  // namespace ann

@@ -342,3 +342,31 @@ def test_cfg2_scaled_graph(cfg2_scaled, ef):
     say(f"cfg2/10 ef={ef}: strict={strict}/{n} recall@3 gpu={recall(ids.cpu().numpy(), f_ids):.3f} "
         f"oracle={recall(o_ids, f_ids):.3f} n_dist={nd.mean():.0f} n_expand={ne.mean():.0f}")
     assert strict >= n - 2
+
+
+# ------------------------------------------------------------------ scheduler priority levels (Section 3.2)
+
+@pytest.mark.parametrize("n,G", [(1, 6), (5, 6), (257, 6), (3000, 6), (777, 1), (1200, 13)])
+def test_priority_order_matches_oracle(n, G):
+    gen = np.random.default_rng(n * 31 + G)
+    R = gen.integers(0, 9, n).astype(np.int32)
+    C = gen.integers(64, 8192, n).astype(np.int32)
+    W = gen.random(n) * 60.0
+    Wcur = np.round(gen.random(n) * 5.0, 1)                # equal queueing times occur
+    if n > 10:
+        W[3] = W[5]                                       # and equal metric values
+    level, order = ann.ann_priority_order(torch.from_numpy(R).to(DEV), torch.from_numpy(W).to(DEV),
+                                          torch.from_numpy(C).to(DEV), torch.from_numpy(Wcur).to(DEV), G)
+    torch.cuda.synchronize()
+    o_level, o_order = oracle.priority_order(R, W, C, Wcur, G)
+    assert np.array_equal(level.cpu().numpy(), o_level)
+    assert np.array_equal(order.cpu().numpy(), o_order)
+
+
+def test_priority_order_bad_arguments():
+    t = torch.zeros(4, dtype=torch.int32, device=DEV)
+    w = torch.zeros(4, dtype=torch.float64, device=DEV)
+    with pytest.raises(ann.AnnError):
+        ann.ann_priority_order(t, w, t, w, 0)
+    with pytest.raises(ValueError):
+        ann.ann_priority_order(t, w.float(), t, w, 6)

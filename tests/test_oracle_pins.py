@@ -411,3 +411,68 @@ def test_nonstall_exit_returns_the_state_of_the_full_search_at_that_point():
         cut = oracle.graph_search_nonstall(x, g, 0, q[b:b + 1], 3, 32, tau=np.inf, max_expand=int(stats[b, 2]))
         assert np.array_equal(cut[0][0], ids[b]) and np.array_equal(cut[2][0], sc64[b])
         assert cut[3][0, 1] == stats[b, 1]
+
+
+# ---------------------------------------------------------------- priority levels (Section 3.2, Eq. 1-2)
+
+def test_priority_hand_example():
+    rows = {}
+    for line in open(os.path.join(GOLDEN, "priority_levels.txt")):
+        if line.strip() and not line.startswith("#"):
+            k, *v = line.split()
+            rows[k] = v
+    G = int(rows["G"][0])
+    level, order = oracle.priority_order([int(t) for t in rows["R"]], [float(t) for t in rows["W"]],
+                                         [int(t) for t in rows["C"]], [float(t) for t in rows["Wcur"]], G)
+    assert level.tolist() == [int(t) for t in rows["level"]]
+    assert order.tolist() == [int(t) for t in rows["order"]]
+
+
+def test_priority_single_metric_closed_form():
+    """With one metric varying, level = ceil(G (M - min) / range) - 1 for M > min (exact integer
+    arithmetic; values that sit exactly on a threshold are left out)."""
+    n, G = 500, 7
+    R = rng.integers(3, 1000, n).astype(np.int32)
+    R[0], R[1] = 3, 999
+    mn, mx = int(R.min()), int(R.max())
+    const = np.full(n, 4, np.int32)
+    zeros = np.zeros(n)
+    for which in range(3):
+        args = [const, zeros + 2.5, const]
+        args[which] = R if which != 1 else R.astype(np.float64)
+        level, _ = oracle.priority_order(args[0], args[1], args[2], zeros, G)
+        for i in range(n):
+            num = G * (int(R[i]) - mn)
+            if num % (mx - mn) == 0 and num != 0:
+                continue
+            want = 0 if num == 0 else -(-num // (mx - mn)) - 1
+            assert level[i] == want, (which, i, R[i])
+    assert level[1] == G - 1
+
+
+def test_priority_invariants_and_order():
+    n, G = 300, 6
+    R = rng.integers(0, 9, n).astype(np.int32)
+    C = rng.integers(100, 5000, n).astype(np.int32)
+    W = rng.random(n) * 30
+    Wcur = np.round(rng.random(n) * 4, 1)                   # many equal queueing times
+    level, order = oracle.priority_order(R, W, C, Wcur, G)
+    assert level.min() >= 0 and level.max() == G - 1
+    assert sorted(order.tolist()) == list(range(n))
+    assert order.tolist() == sorted(range(n), key=lambda i: (-int(level[i]), -Wcur[i], i))
+    for m in (R, W, C):                                      # the largest value of any metric is top level
+        assert level[int(np.argmax(m))] == G - 1
+    # shifting a metric, or scaling the waiting times by a power of two, changes nothing
+    l2, o2 = oracle.priority_order(R + 5, W * 4 + 16, C + 1000, Wcur * 2, G)
+    assert np.array_equal(l2, level) and np.array_equal(o2, order)
+    # relabelling the requests relabels the result
+    perm = rng.permutation(n)
+    l3, _ = oracle.priority_order(R[perm], W[perm], C[perm], Wcur[perm], G)
+    assert np.array_equal(l3, level[perm])
+    # a request whose three metrics are all at the minimum is at the base level
+    R[7], W[7], C[7] = R.min(), W.min(), C.min()
+    assert oracle.priority_order(R, W, C, Wcur, G)[0][7] == 0
+    # every metric constant: everybody at level 0, order by queueing time only
+    one = np.ones(n, np.int32)
+    l4, o4 = oracle.priority_order(one, np.ones(n), one, Wcur, G)
+    assert not l4.any() and o4.tolist() == sorted(range(n), key=lambda i: (-Wcur[i], i))
