@@ -370,3 +370,32 @@ def test_priority_order_bad_arguments():
         ann.ann_priority_order(t, w, t, w, 0)
     with pytest.raises(ValueError):
         ann.ann_priority_order(t, w.float(), t, w, 6)
+
+
+# ------------------------------------------------------------------ measurement support
+
+def test_kernel_timing_records_main_kernels():
+    K = ann.binding
+    c = synth.make_corpus(40_000, 128, 8, seed=3, dtype=torch.float16, zipf_a=None, sigma=0.3)
+    q = synth.make_queries(c, 200)
+    g = synth.knn_graph(c.x.to(DEV), 8)
+    xd, qd = c.x.to(DEV), q.to(DEV)
+    ann.ann_timing_enable(True)
+    for _ in range(3):
+        ann.ann_flat_search_typed(xd, qd[:16].contiguous(), 3)       # streaming kernel
+        ann.ann_flat_search_typed(xd, qd, 3)                         # matrix-core kernel (+ helpers, not timed)
+        ann.ann_graph_search_typed(xd, g, 0, qd, 3, 16)
+    ann.ann_timing_enable(False)
+    ann.ann_flat_search_typed(xd, qd, 3)                             # not recorded any more
+    for code, launches in ((K.KERNEL_FLAT_STREAM, 3), (K.KERNEL_FLAT_WIDE, 3), (K.KERNEL_GRAPH, 3), (K.KERNEL_FLAT_F32, 0)):
+        n, ms = ann.ann_timing_read(code)
+        assert n == launches and (ms > 0) == (launches > 0), (code, n, ms)
+    ann.ann_timing_enable(True)                                      # switching on again drops the old records
+    ann.ann_timing_enable(False)
+    assert ann.ann_timing_read(K.KERNEL_GRAPH) == (0, 0.0)
+
+
+def test_mfma_rate_measurement_is_plausible():
+    const, rand = ann.ann_measure_mfma_rate(False, 20000), ann.ann_measure_mfma_rate(True, 20000)
+    say(f"box MFMA rate: constant operands {const:.0f} TFLOP/s, random operands {rand:.0f} TFLOP/s")
+    assert 500 < rand <= const * 1.05 and const < 2600
