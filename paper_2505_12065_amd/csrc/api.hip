@@ -98,8 +98,8 @@ hipEvent_t pooled_event() {
 struct TimedScope {
     hipStream_t stream;
     int index = -1;
-    TimedScope(int kernel, hipStream_t s) : stream(s) {
-        if (!g_timing) return;
+    TimedScope(int kernel, hipStream_t s) : stream(s) {     // kernel < 0: not recorded
+        if (!g_timing || kernel < 0) return;
         TimedLaunch t{pooled_event(), pooled_event(), kernel};
         if (!t.a || !t.b) return;
         if (hipEventRecord(t.a, stream) != hipSuccess) { (void)hipGetLastError(); return; }
@@ -148,16 +148,62 @@ struct FlatPlan {
     int sample_tiles;        // > 0: a sampling pass over the first tiles supplies starting thresholds
     int pstride;             // slabs per query in the partial array (P, plus one for the sample)
     size_t sample_ofs, thr_ofs;   // byte offsets of the sample lists and thresholds in the workspace
+    // k > 4 on the matrix-core path: candidate arrays instead of lists, streaming kernel as repair
+    bool emit;
+    int emit_cap;                 // entries of a query's candidate array
+    int sample_P;                 // slabs of the sampling pass
+    int st_P, st_nqg_max;         // geometry of the repair pass (streaming kernel, lists of 16)
+    size_t cnt_ofs, cand_ofs;
     size_t ws_bytes;
 };
 
 constexpr int WIDE_MIN_B = 65;   // smallest batch sent to the matrix-core path
+constexpr int EMIT_CAP = 4096;   // candidate-array entries per query (k > 4), a multiple of 16
+constexpr int EMIT_STRIDE = 64;  // the sampling pass of that path scores every 64th row
+constexpr int64_t EMIT_MIN_N = 128 * 1024;
 
-FlatPlan flat_plan(int cus, int64_t N, int d, int dtype, int B, int k) {
+FlatPlan flat_plan(int cus, int64_t N, int d, int dtype, int B, int k, bool allow_emit = true) {
     FlatPlan pl;
     pl.kp = kp_of(k);
     pl.wide_ntg = 0;
     pl.sample_tiles = 0;
+    pl.emit = false;
+    pl.emit_cap = 0;
+    pl.sample_P = 0;
+    // k > 4 on a large 16-bit corpus: lists of 16 per lane are slow to maintain (and do not fit the
+    // matrix-core kernel's registers), so the main pass keeps no lists; it appends every score that
+    // reaches a lower bound of the query's k-th best to a per-query candidate array.  The bound is
+    // the k-th best of every 64th row (scored exactly by a short first pass), so about 64 k rows per
+    // query pass it; an array that overflows all the same (heavily tied scores) is repaired by the
+    // streaming kernel with lists of 16, which does no work otherwise.
+    if (allow_emit && dtype != ANN_F32 && pl.kp == 16 && N >= EMIT_MIN_N) {
+        const FlatPlan st = flat_plan(cus, N, d, dtype, B, k, false);     // repair pass
+        const FlatPlan m4 = flat_plan(cus, N, d, dtype, B, 4, false);     // geometry of sampling and main pass
+        pl.emit = true;
+        pl.emit_cap = EMIT_CAP;
+        pl.wide_ntg = m4.wide_ntg;
+        pl.P = m4.P;
+        pl.nqg_max = m4.nqg_max;
+        pl.st_P = st.P;
+        pl.st_nqg_max = st.nqg_max;
+        pl.pstride = st.P;
+        const int64_t nv = (N + EMIT_STRIDE - 1) / EMIT_STRIDE;
+        if (pl.wide_ntg > 0) {
+            const int64_t stiles = (nv + 255) / 256;                       // >= 8
+            pl.sample_P = (int)(stiles < pl.P ? stiles : pl.P);
+        } else {
+            const int64_t swaves = (nv + 15) / 16;                         // one 16-row tile per wave at least
+            const int64_t sblocks = (swaves + 7) / 8;
+            pl.sample_P = (int)(sblocks < pl.P ? sblocks : pl.P);
+        }
+        const size_t a16 = 15;
+        pl.sample_ofs = ((size_t)B * st.P * pl.kp * sizeof(Cand) + a16) & ~a16;
+        pl.thr_ofs = pl.sample_ofs + (size_t)B * pl.sample_P * 4 * sizeof(Cand);   // lists of 4 per sample slab
+        pl.cnt_ofs = (pl.thr_ofs + (size_t)B * sizeof(float) + a16) & ~a16;
+        pl.cand_ofs = (pl.cnt_ofs + (size_t)B * sizeof(int) + a16) & ~a16;
+        pl.ws_bytes = pl.cand_ofs + (size_t)B * EMIT_CAP * sizeof(Cand);
+        return pl;
+    }
     if (dtype != ANN_F32 && B >= WIDE_MIN_B && pl.kp == 4 && d % 32 == 0) {
         const int nt = (B + wide_query_tile(B) - 1) / wide_query_tile(B);
         pl.wide_ntg = nt < 8 ? nt : 8;
@@ -201,8 +247,76 @@ FlatPlan flat_plan(int cus, int64_t N, int d, int dtype, int B, int k) {
     return pl;
 }
 
+// 16-bit corpus, streaming kernel over all B queries, 64 at a time (kp 0: candidate-array mode)
+int flat_stream_all(int kp, int nqg_max, int P, const void *X, int64_t N, int d, int dtype, const void *Q, int B,
+                    Cand *partial, const StreamOpts &o, bool timed_launches, hipStream_t stream) {
+    for (int q0 = 0; q0 < B; q0 += 16 * nqg_max) {
+        const int left = B - q0;
+        const int nqg = left > 16 * nqg_max ? nqg_max : (left + 15) / 16;
+        hipError_t e;
+        {
+            TimedScope timed(timed_launches ? ANN_KERNEL_FLAT_STREAM : -1, stream);
+            e = dtype == ANN_F16 ? launch_flat_stream_f16(nqg, kp, X, N, d, Q, B, q0, partial, P, o, stream)
+                                 : launch_flat_stream_bf16(nqg, kp, X, N, d, Q, B, q0, partial, P, o, stream);
+        }
+        if (int rc = check_launch("flat_stream_kernel", e)) return rc;
+    }
+    return ANN_OK;
+}
+
+int flat_search_emit(const FlatPlan &pl, const void *X, int64_t N, int d, int dtype, const void *Q, int B, int k,
+                     int32_t *ids, float *scores, char *ws, hipStream_t stream) {
+    Cand *partial = reinterpret_cast<Cand *>(ws);
+    Cand *sample = reinterpret_cast<Cand *>(ws + pl.sample_ofs);
+    float *thr = reinterpret_cast<float *>(ws + pl.thr_ofs);
+    int *cnt = reinterpret_cast<int *>(ws + pl.cnt_ofs);
+    Cand *cand = reinterpret_cast<Cand *>(ws + pl.cand_ofs);
+    const size_t cnt_words = ((size_t)B + 3) & ~(size_t)3;
+    if (int rc = check_launch("zero_words_kernel", launch_zero_words(reinterpret_cast<uint32_t *>(cnt), cnt_words, stream)))
+        return rc;
+    // sampling pass: every 64th row, the best 4 per slab and query
+    if (pl.wide_ntg > 0) {
+        hipError_t e = launch_flat_wide(dtype, 1, X, N, d, Q, B, sample, pl.sample_P, pl.wide_ntg, 0, nullptr, pl.sample_P,
+                                        0, nullptr, EMIT_STRIDE, stream);
+        if (int rc = check_launch("flat_wide_kernel (sample)", e)) return rc;
+    } else {
+        StreamOpts o;
+        o.row_stride = EMIT_STRIDE;
+        if (int rc = flat_stream_all(4, pl.nqg_max, pl.sample_P, X, N, d, dtype, Q, B, sample, o, false, stream)) return rc;
+    }
+    if (int rc = check_launch("flat_sample_kth_kernel", launch_flat_sample_kth(sample, pl.sample_P, B, k, thr, stream)))
+        return rc;
+    // main pass: candidates
+    if (pl.wide_ntg > 0) {
+        hipError_t e;
+        {
+            TimedScope timed(ANN_KERNEL_FLAT_WIDE, stream);
+            e = launch_flat_wide(dtype, 2, X, N, d, Q, B, cand, pl.P, pl.wide_ntg, 0, thr, pl.emit_cap, 0, cnt, 1, stream);
+        }
+        if (int rc = check_launch("flat_wide_kernel (candidates)", e)) return rc;
+    } else {
+        StreamOpts o;
+        o.thr = thr;
+        o.count = cnt;
+        o.cap = pl.emit_cap;
+        if (int rc = flat_stream_all(0, pl.nqg_max, pl.P, X, N, d, dtype, Q, B, cand, o, true, stream)) return rc;
+    }
+    if (int rc = check_launch("flat_merge_kernel (candidates)",
+                              launch_flat_merge(pl.kp, cand, pl.emit_cap / pl.kp, B, k, ids, scores, cnt, pl.emit_cap, 0,
+                                                stream)))
+        return rc;
+    // repair pass: every launch returns at once unless a candidate array of its queries overflowed
+    StreamOpts o;
+    o.need = cnt;
+    o.need_above = pl.emit_cap;
+    if (int rc = flat_stream_all(pl.kp, pl.st_nqg_max, pl.st_P, X, N, d, dtype, Q, B, partial, o, false, stream)) return rc;
+    return check_launch("flat_merge_kernel (repair)",
+                        launch_flat_merge(pl.kp, partial, pl.st_P, B, k, ids, scores, cnt, pl.emit_cap, 1, stream));
+}
+
 int flat_search_run(const FlatPlan &pl, const void *X, int64_t N, int d, int dtype, const void *Q, int B, int k,
                     int32_t *ids, float *scores, Cand *partial, hipStream_t stream) {
+    if (pl.emit) return flat_search_emit(pl, X, N, d, dtype, Q, B, k, ids, scores, reinterpret_cast<char *>(partial), stream);
     if (dtype == ANN_F32) {
         hipError_t e;
         {
@@ -216,8 +330,8 @@ int flat_search_run(const FlatPlan &pl, const void *X, int64_t N, int d, int dty
         if (pl.sample_tiles > 0) {
             Cand *sample = reinterpret_cast<Cand *>(reinterpret_cast<char *>(partial) + pl.sample_ofs);
             float *thr = reinterpret_cast<float *>(reinterpret_cast<char *>(partial) + pl.thr_ofs);
-            hipError_t e = launch_flat_wide(dtype, true, X, (int64_t)pl.sample_tiles * 256, d, Q, B, sample,
-                                            pl.sample_tiles, pl.wide_ntg, 0, nullptr, pl.sample_tiles, 0, stream);
+            hipError_t e = launch_flat_wide(dtype, 1, X, (int64_t)pl.sample_tiles * 256, d, Q, B, sample,
+                                            pl.sample_tiles, pl.wide_ntg, 0, nullptr, pl.sample_tiles, 0, nullptr, 1, stream);
             if (int rc = check_launch("flat_wide_kernel (sample)", e)) return rc;
             e = launch_flat_sample_merge(pl.kp, sample, pl.sample_tiles, B, partial, pl.pstride, pl.P, thr, stream);
             if (int rc = check_launch("flat_sample_merge_kernel", e)) return rc;
@@ -226,24 +340,14 @@ int flat_search_run(const FlatPlan &pl, const void *X, int64_t N, int d, int dty
         hipError_t e;
         {
             TimedScope timed(ANN_KERNEL_FLAT_WIDE, stream);
-            e = launch_flat_wide(dtype, false, X, N, d, Q, B, partial, pl.P, pl.wide_ntg, pl.sample_tiles, thr0,
-                                 pl.pstride, 0, stream);
+            e = launch_flat_wide(dtype, 0, X, N, d, Q, B, partial, pl.P, pl.wide_ntg, pl.sample_tiles, thr0,
+                                 pl.pstride, 0, nullptr, 1, stream);
         }
         if (int rc = check_launch("flat_wide_kernel", e)) return rc;
     } else {
-        for (int q0 = 0; q0 < B; q0 += 16 * pl.nqg_max) {
-            const int left = B - q0;
-            const int nqg = left > 16 * pl.nqg_max ? pl.nqg_max : (left + 15) / 16;
-            hipError_t e;
-            {
-                TimedScope timed(ANN_KERNEL_FLAT_STREAM, stream);
-                e = dtype == ANN_F16 ? launch_flat_stream_f16(nqg, pl.kp, X, N, d, Q, B, q0, partial, pl.P, stream)
-                                     : launch_flat_stream_bf16(nqg, pl.kp, X, N, d, Q, B, q0, partial, pl.P, stream);
-            }
-            if (int rc = check_launch("flat_stream_kernel", e)) return rc;
-        }
+        if (int rc = flat_stream_all(pl.kp, pl.nqg_max, pl.P, X, N, d, dtype, Q, B, partial, StreamOpts(), true, stream)) return rc;
     }
-    return check_launch("flat_merge_kernel", launch_flat_merge(pl.kp, partial, pl.pstride, B, k, ids, scores, stream));
+    return check_launch("flat_merge_kernel", launch_flat_merge(pl.kp, partial, pl.pstride, B, k, ids, scores, nullptr, 0, 0, stream));
 }
 
 }  // namespace

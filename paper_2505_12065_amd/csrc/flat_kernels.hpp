@@ -24,11 +24,21 @@ constexpr int STREAM_UNROLL = 8;   // 16-byte loads a lane keeps in flight (6..2
 // up with one query (lane % 16) and four rows (4*(lane/16) + i) per tile of 16 rows.
 //   X        [N, d] 16-bit           Q  [B, d] 16-bit (queries q0 .. q0+NQG*16 are used)
 //   partial  [B, P, KP] pairs, P = gridDim.x
-template <class T, int NQG, int KP, bool DFULL>
+//   o        see StreamOpts: gate on overflowed queries, row stride of a sampling pass, and
+//            (EMIT, for k > 4) no lists at all: every (score, row) with score >= o.thr[q] is
+//            appended to the candidate array partial[q * o.cap ..) through o.count[q]
+template <class T, int NQG, int KP, bool DFULL, bool EMIT>
 __global__ __launch_bounds__(512) void flat_stream_kernel(const void *__restrict__ X, int64_t N, int d,
                                                           const void *__restrict__ Q, int B, int q0,
-                                                          Cand *__restrict__ partial) {
+                                                          Cand *__restrict__ partial, StreamOpts o) {
     extern __shared__ __align__(16) unsigned char smem[];
+    if (o.need) {
+        const int q = q0 + (int)threadIdx.x;
+        const int mine = threadIdx.x < NQG * 16 && q < B && o.need[q] > o.need_above;
+        if (!__syncthreads_or(mine)) return;
+    }
+    const int S = o.row_stride;
+    const int64_t NV = (N + S - 1) / S;               // rows 0, S, 2S, ... are "virtual" rows 0 .. NV-1
     u4 *qf = reinterpret_cast<u4 *>(smem);            // [NQG][steps][64]
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, nwaves = blockDim.x >> 6;
     const int steps = (d + 31) >> 5;
@@ -48,14 +58,21 @@ __global__ __launch_bounds__(512) void flat_stream_kernel(const void *__restrict
     TopList<KP> best[NQG];
     float thr[NQG];
 #pragma unroll
-    for (int g = 0; g < NQG; ++g) { best[g].init(); thr[g] = -INFINITY; }
+    for (int g = 0; g < NQG; ++g) {
+        best[g].init();
+        thr[g] = -INFINITY;
+        if constexpr (EMIT) {                         // fixed thresholds; queries past B never emit
+            const int q = q0 + g * 16 + (lane & 15);
+            thr[g] = q < B ? o.thr[q] : INFINITY;
+        }
+    }
 
-    const int64_t ntiles = (N + 15) >> 4;
+    const int64_t ntiles = (NV + 15) >> 4;
     const int kofs = (lane >> 4) * 8;                 // this lane's k offset inside a 32-wide step
     for (int64_t tile = (int64_t)blockIdx.x * nwaves + wave; tile < ntiles; tile += (int64_t)P * nwaves) {
         int64_t row = tile * 16 + (lane & 15);
-        if (row >= N) row = N - 1;                    // tail tile: re-read the last row, masked below
-        const char *rp = static_cast<const char *>(X) + ((size_t)row * d + kofs) * 2;
+        if (row >= NV) row = NV - 1;                  // tail tile: re-read the last row, masked below
+        const char *rp = static_cast<const char *>(X) + ((size_t)row * S * d + kofs) * 2;
         f4 acc[NQG];
 #pragma unroll
         for (int g = 0; g < NQG; ++g) acc[g] = f4{0.f, 0.f, 0.f, 0.f};
@@ -91,18 +108,30 @@ __global__ __launch_bounds__(512) void flat_stream_kernel(const void *__restrict
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
                     const int64_t r = rbase + i;
-                    if (r < N && a[i] >= thr[g] && best[g].admits(a[i], (int)r)) best[g].insert(a[i], (int)r);
+                    if constexpr (EMIT) {
+                        if (r < NV && a[i] >= thr[g]) {
+                            const int q = q0 + g * 16 + (lane & 15);
+                            const int slot = atomicAdd(&o.count[q], 1);
+                            if (slot < o.cap) partial[(size_t)q * o.cap + slot] = Cand{a[i], (int)(r * S)};
+                        }
+                    } else {
+                        const int id = (int)(r * S);
+                        if (r < NV && a[i] >= thr[g] && best[g].admits(a[i], id)) best[g].insert(a[i], id);
+                    }
                 }
-                // the KP-th best of any lane that serves the same query bounds the final
-                // KP-th best from below, so it is a safe rejection threshold for all four
-                float t = best[g].s[KP - 1];
-                t = fmaxf(t, __shfl_xor(t, 16));
-                t = fmaxf(t, __shfl_xor(t, 32));
-                thr[g] = fmaxf(thr[g], t);
+                if constexpr (!EMIT) {
+                    // the KP-th best of any lane that serves the same query bounds the final
+                    // KP-th best from below, so it is a safe rejection threshold for all four
+                    float t = best[g].s[KP - 1];
+                    t = fmaxf(t, __shfl_xor(t, 16));
+                    t = fmaxf(t, __shfl_xor(t, 32));
+                    thr[g] = fmaxf(thr[g], t);
+                }
             }
         });
     }
 
+    if constexpr (EMIT) return;
     // the four lanes that share a query -> one list per wave and query
     __syncthreads();                                   // query fragments are dead from here
     Cand *wl = reinterpret_cast<Cand *>(smem);         // [nwaves][NQG*16][KP]
@@ -234,16 +263,27 @@ __device__ __forceinline__ void gather_best(const Cand *__restrict__ in, int tot
     }
 }
 
+// count == null: query q's input is its P lists of KP.  count given, repair == 0: the input is the
+// candidate array of count[q] entries at partial[q * P * KP ..) and nothing is written when it
+// overflowed (count[q] > P * KP).  count given, repair != 0: P lists as usual, but only the
+// queries whose candidate array overflowed are written.
 template <int KP>
 __global__ __launch_bounds__(256) void flat_merge_kernel(const Cand *__restrict__ partial, int P, int k,
-                                                         int32_t *__restrict__ ids, float *__restrict__ scores) {
+                                                         int32_t *__restrict__ ids, float *__restrict__ scores,
+                                                         const int *__restrict__ count, int cap, int repair) {
     __shared__ Cand wl[4 * KP];
     const int q = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int nwaves = blockDim.x >> 6;
+    int total = P * KP;
+    if (count) {
+        const int n = count[q];
+        if (repair ? n <= cap : n > cap) return;          // uniform for the workgroup
+        if (!repair) total = n;
+    }
     const Cand *in = partial + (size_t)q * P * KP;
     TopList<KP> best;
     best.init();
-    gather_best<KP>(in, P * KP, tid, blockDim.x, best);
+    gather_best<KP>(in, total, tid, blockDim.x, best);
     TopList<KP> wbest;
     group_top<KP, KP, 1, 64>(best, wbest);
     if (lane == 0) {
@@ -287,6 +327,27 @@ __global__ __launch_bounds__(64) void flat_sample_merge_kernel(const Cand *__res
 #pragma unroll
         for (int j = 0; j < KP; ++j) out[j] = Cand{top.s[j], top.id[j]};
         thr[q] = top.id[KP - 1] != EMPTY_ID ? top.s[KP - 1] : -INFINITY;
+    }
+}
+
+// One wavefront per query: the k-th best score among Ps sampled lists of KS entries (src[(q Ps + s) KS ..)),
+// -inf when the sample holds fewer than k rows.  The lists come from disjoint rows, so this is the
+// k-th best of a subset of the corpus: a lower bound of the final k-th best score.
+template <int KS, int KO>
+__global__ __launch_bounds__(64) void flat_sample_kth_kernel(const Cand *__restrict__ src, int Ps, int k,
+                                                             float *__restrict__ thr) {
+    const int q = blockIdx.x, lane = threadIdx.x;
+    TopList<KO> best;
+    best.init();
+    gather_best<KO>(src + (size_t)q * Ps * KS, Ps * KS, lane, 64, best);
+    TopList<KO> top;
+    group_top<KO, KO, 1, 64>(best, top);
+    if (lane == 0) {
+        float t = -INFINITY;
+#pragma unroll
+        for (int j = 0; j < KO; ++j)
+            if (j == k - 1 && top.id[j] != EMPTY_ID) t = top.s[j];
+        thr[q] = t;
     }
 }
 

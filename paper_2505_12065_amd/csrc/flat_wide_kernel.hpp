@@ -91,15 +91,30 @@ __device__ __forceinline__ void lds_barrier() {
 //   the scanned range reach or exceed together with rows inside it, i.e. a lower bound
 //   of the final KP-th best; rows scoring below it are dropped at once.
 //   Slab s of query q is written to partial[(q * pstride + pslot0 + s) * KP ..).
-//   SELECT: threshold-free epilogue (per lane the KP best of its 64 scores by repeated
-//   maximum), constant cost; meant for the short sampling pass that produces thr_init.
-template <class T, int WNF, int NWN, bool SELECT>
+//   MODE WIDE_LISTS: the epilogue described above.
+//   MODE WIDE_SELECT: threshold-free epilogue (per lane the KP best of its 64 scores by repeated
+//   maximum), constant cost; meant for the short sampling pass that produces thr_init.  Only in
+//   this mode, row_stride > 1 scans rows 0, S, 2S, ... instead of every row (tile_begin and the
+//   slabs then count tiles of 256 such rows).
+//   MODE WIDE_EMIT (k > 4): no lists at all.  thr_init[q] must be a lower bound of query q's final
+//   k-th best score (the k-th best of a sample); every (score, row) with score >= thr_init[q] is
+//   appended to the query's candidate array partial[q * pstride ..) through the counter
+//   emit_count[q] (entries beyond pstride are counted but not stored: the caller then knows that
+//   the array overflowed and recomputes that query another way).
+constexpr int WIDE_LISTS = 0, WIDE_SELECT = 1, WIDE_EMIT = 2;
+template <class T, int WNF, int NWN, int MODE>
 __global__ __launch_bounds__(128 * NWN) void flat_wide_kernel(const void *__restrict__ X, int64_t N, int d,
                                                                     const void *__restrict__ Q, int B,
                                                                     Cand *__restrict__ partial, int P, int NTG,
                                                                     int64_t tile_begin,
                                                                     const float *__restrict__ thr_init,
-                                                                    int pstride, int pslot0) {
+                                                                    int pstride, int pslot0,
+                                                                    int *__restrict__ emit_count, int row_stride) {
+    constexpr bool SELECT = MODE == WIDE_SELECT;
+    // WIDE_SELECT may scan every row_stride-th row only (rows 0, S, 2S, ...): all the tiling below
+    // then runs over these NV "virtual" rows, and only addresses and reported ids use S
+    const int S = SELECT ? row_stride : 1;
+    const int64_t NV = SELECT ? (N + S - 1) / S : N;
     using C = WideCfg<WNF, NWN>;
     constexpr int KP = WIDE_KP, NST = WIDE_STAGES, LPW = C::LPW;
     extern __shared__ __align__(16) unsigned char smem[];
@@ -124,7 +139,7 @@ __global__ __launch_bounds__(128 * NWN) void flat_wide_kernel(const void *__rest
     if ((G & 7) == 0) lb = (blockIdx.x & 7) * (G >> 3) + (blockIdx.x >> 3);
     const int ntg = lb % NTG, slab = lb / NTG;
     const int NT = (B + C::BN - 1) / C::BN;
-    const int64_t mtiles = (N + WIDE_BM - 1) / WIDE_BM - tile_begin;
+    const int64_t mtiles = (NV + WIDE_BM - 1) / WIDE_BM - tile_begin;
     const int64_t t0 = tile_begin + mtiles * slab / P, t1 = tile_begin + mtiles * (slab + 1) / P;
     const int total = (int)(t1 - t0) * ksteps;
 
@@ -132,7 +147,15 @@ __global__ __launch_bounds__(128 * NWN) void flat_wide_kernel(const void *__rest
         const int n0 = nt * C::BN;
         TopList<KP> best[WNF];
         float thr[WNF];
-        static_for<WNF>([&](auto jc) { best[decltype(jc)::value].init(); thr[decltype(jc)::value] = -INFINITY; });
+        static_for<WNF>([&](auto jc) {
+            constexpr int j = decltype(jc)::value;
+            best[j].init();
+            thr[j] = -INFINITY;
+            if constexpr (MODE == WIDE_EMIT) {               // fixed thresholds; queries past B never emit
+                const int q = n0 + (wn * WNF + j) * 32 + l32;
+                thr[j] = q < B ? thr_init[q] : INFINITY;
+            }
+        });
         if (tid < C::BN) {
             const int q = n0 + tid < B ? n0 + tid : B - 1;
             thr_l[tid] = float_key(thr_init ? thr_init[q] : -INFINITY);
@@ -152,8 +175,8 @@ __global__ __launch_bounds__(128 * NWN) void flat_wide_kernel(const void *__rest
                 const int blk = wave * LPW + e;
                 if (blk < C::A_FRAGS) {
                     int64_t row = tile * WIDE_BM + blk * 16 + (lane >> 2);
-                    row = row < N ? row : N - 1;
-                    loff[e] = (uint32_t)(row - tile * WIDE_BM) * (uint32_t)(d * 2) + my_chunk * 16;
+                    row = row < NV ? row : NV - 1;
+                    loff[e] = (uint32_t)(row - tile * WIDE_BM) * (uint32_t)(d * 2 * S) + my_chunk * 16;
                 } else {
                     int q = n0 + (blk - C::A_FRAGS) * 16 + (lane >> 2);
                     q = q < B ? q : B - 1;
@@ -162,7 +185,7 @@ __global__ __launch_bounds__(128 * NWN) void flat_wide_kernel(const void *__rest
             }
         };
         lane_offsets(t0);
-        const char *xbase = static_cast<const char *>(X) + (size_t)t0 * WIDE_BM * d * 2;   // tile start + k step
+        const char *xbase = static_cast<const char *>(X) + (size_t)t0 * WIDE_BM * d * 2 * S;   // tile start + k step
         const char *qbase = static_cast<const char *>(Q) + (size_t)n0 * d * 2;
         int iks = 0;                                         // k step of the next stage to issue
         int64_t itile = t0;
@@ -177,8 +200,8 @@ __global__ __launch_bounds__(128 * NWN) void flat_wide_kernel(const void *__rest
             if (++iks == ksteps) {
                 iks = 0;
                 ++itile;
-                xbase += (size_t)WIDE_BM * d * 2;
-                if ((itile + 1) * WIDE_BM > N && itile < t1) lane_offsets(itile);   // ragged last tile
+                xbase += (size_t)WIDE_BM * d * 2 * S;
+                if ((itile + 1) * WIDE_BM > NV && itile < t1) lane_offsets(itile);   // ragged last tile
             }
         };
 
@@ -239,8 +262,8 @@ __global__ __launch_bounds__(128 * NWN) void flat_wide_kernel(const void *__rest
                 cks = 0;
                 const int64_t tile = ctile++;
                 const int rbase = (int)(tile * WIDE_BM) + wm * 128 + 4 * lhi;    // N < 2^31
-                const int nrows = (int)N;
-                if ((tile + 1) * WIDE_BM > N) {               // ragged last tile: rows >= N never score
+                const int nrows = (int)NV;
+                if ((tile + 1) * WIDE_BM > NV) {               // ragged last tile: rows >= N never score
                     static_for<4>([&](auto ic) {
                         constexpr int i = decltype(ic)::value;
                         static_for<WNF>([&](auto jc) {
@@ -251,7 +274,41 @@ __global__ __launch_bounds__(128 * NWN) void flat_wide_kernel(const void *__rest
                         });
                     });
                 }
-                if constexpr (SELECT) {
+                if constexpr (MODE == WIDE_EMIT) {
+                    static_for<WNF>([&](auto jc) {
+                        constexpr int j = decltype(jc)::value;
+                        const float t = thr[j];
+                        float m = acc[0][j][0];
+                        static_for<4>([&](auto ic) {
+#pragma unroll
+                            for (int r = 0; r < 16; ++r) m = fmaxf(m, acc[decltype(ic)::value][j][r]);
+                        });
+                        if (__builtin_amdgcn_ballot_w64(m >= t) != 0) {      // rare: some hundred rows per query in all
+                            const int q = n0 + (wn * WNF + j) * 32 + l32;
+                            uint32_t mask[2] = {0u, 0u};                      // accumulator e passes: bit e
+                            static_for<4>([&](auto ic) {
+                                constexpr int i = decltype(ic)::value;
+#pragma unroll
+                                for (int r = 0; r < 16; ++r) mask[i / 2] |= acc[i][j][r] >= t ? 1u << ((i & 1) * 16 + r) : 0u;
+                            });
+                            uint64_t left = ((uint64_t)mask[1] << 32) | mask[0];
+                            while (left != 0) {
+                                const int e = __builtin_ctzll(left);
+                                left &= left - 1;
+                                float s = 0.f;
+                                static_for<4>([&](auto ic) {
+                                    constexpr int i = decltype(ic)::value;
+#pragma unroll
+                                    for (int r = 0; r < 16; ++r) s = (e == i * 16 + r) ? acc[i][j][r] : s;
+                                });
+                                const int slot = atomicAdd(&emit_count[q], 1);
+                                const int r = e & 15;
+                                if (slot < pstride)
+                                    partial[(size_t)q * pstride + slot] = Cand{s, rbase + (e >> 4) * 32 + 8 * (r >> 2) + (r & 3)};
+                            }
+                        }
+                    });
+                } else if constexpr (SELECT) {
                     static_for<WNF>([&](auto jc) {
                         constexpr int j = decltype(jc)::value;
 #pragma unroll
@@ -276,7 +333,7 @@ __global__ __launch_bounds__(128 * NWN) void flat_wide_kernel(const void *__rest
                             // the first maximum in accumulator order is also the one with the lowest row id
                             const int r = idx & 15;
                             const int row = rbase + (idx >> 4) * 32 + 8 * (r >> 2) + (r & 3);
-                            if (m > -INFINITY && best[j].admits(m, row)) best[j].insert(m, row);
+                            if (m > -INFINITY && best[j].admits(m, row * S)) best[j].insert(m, row * S);
                         }
                     });
                 } else {
@@ -364,6 +421,10 @@ __global__ __launch_bounds__(128 * NWN) void flat_wide_kernel(const void *__rest
             }
         }
 
+        if constexpr (MODE == WIDE_EMIT) {
+            __syncthreads();                                 // thr_l is reused by the next query tile
+            continue;
+        }
         // lanes l and l^32 hold the same queries; then the two wm-waves meet in LDS
         static_for<WNF>([&](auto jc) { best[decltype(jc)::value].merge_xor(32); });
         if (lhi == 0) {

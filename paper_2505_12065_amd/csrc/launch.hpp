@@ -24,28 +24,46 @@ inline hipError_t allow_big_lds(const void *kernel, size_t bytes, size_t *grante
 size_t stream_lds_bytes(int nqg, int steps, int waves, int kp);
 size_t f32_lds_bytes(int d, int waves, int kp);
 
-// dtype: 0 = fp16, 1 = bf16.  nqg in 1..4, kp in {4, 16}.
+// Optional behaviour of a flat_stream_kernel launch.
+struct StreamOpts {
+    const int *need = nullptr;   // [B]: the launch returns at once unless need[q] > need_above for
+    int need_above = 0;          //      one of its queries (repair pass behind the candidate arrays)
+    int row_stride = 1;          // S > 1: only rows 0, S, 2S, ... are scored (sampling pass)
+    const float *thr = nullptr;  // candidate-array mode: [B] lower bounds of the final k-th best score,
+    int *count = nullptr;        //   [B] entry counters (zero on entry; a count past cap means overflow),
+    int cap = 0;                 //   entries per query in the candidate array that `partial` then is
+};
+// nqg in 1..4 query groups of 16 starting at query q0.  kp 4 or 16: lists, partial[B, P, kp].
+// kp 0: candidate-array mode, every (score, row) with score >= o.thr[q] is appended to
+// partial[q o.cap ..) through o.count[q].
 hipError_t launch_flat_stream_f16(int nqg, int kp, const void *X, int64_t N, int d, const void *Q, int B, int q0,
-                                  Cand *partial, int P, hipStream_t stream);
+                                  Cand *partial, int P, const StreamOpts &o, hipStream_t stream);
 hipError_t launch_flat_stream_bf16(int nqg, int kp, const void *X, int64_t N, int d, const void *Q, int B, int q0,
-                                   Cand *partial, int P, hipStream_t stream);
+                                   Cand *partial, int P, const StreamOpts &o, hipStream_t stream);
 // Large batches on the matrix cores (16-bit corpora, d % 32 == 0, lists of 4).
 // Query tile is wide_query_tile(B) queries; gridDim = P slabs x NTG query-tile groups;
 // rows [256 tile_begin, N) are scanned; results go to partial[(q pstride + pslot0 + slab) 4 ..).
-// select = threshold-free epilogue (sampling pass); thr_init = optional per-query lower
-// bounds of the final 4th-best score.
+// mode 0: list epilogue, thr_init = optional per-query lower bounds of the final 4th-best score;
+// mode 1: threshold-free selection epilogue (sampling pass);
+// mode 2 (k > 4): every score >= thr_init[q] is appended to the candidate array
+// partial[q pstride ..) through emit_count[q] (zero on entry; counts past pstride mean overflow).
 int wide_query_tile(int B);
-hipError_t launch_flat_wide(int dtype, bool select, const void *X, int64_t N, int d, const void *Q, int B,
+hipError_t launch_flat_wide(int dtype, int mode, const void *X, int64_t N, int d, const void *Q, int B,
                             Cand *partial, int P, int NTG, int64_t tile_begin, const float *thr_init, int pstride,
-                            int pslot0, hipStream_t stream);
+                            int pslot0, int *emit_count, int row_stride, hipStream_t stream);
+// thr[q] = k-th best score among the Ps sampled lists of 4 of query q (-inf if fewer), k <= 16
+hipError_t launch_flat_sample_kth(const Cand *src, int Ps, int B, int k, float *thr, hipStream_t stream);
 // Per query: merge Ps sampled lists (src[(q Ps + s) kp ..)) into dst[(q pstride + pslot) kp ..)
 // and write the kp-th best score of the merged list (-inf if it has fewer entries) to thr[q].
 hipError_t launch_flat_sample_merge(int kp, const Cand *src, int Ps, int B, Cand *dst, int pstride, int pslot,
                                     float *thr, hipStream_t stream);
 hipError_t launch_flat_f32(int kp, const float *X, int64_t N, int d, const float *Q, int B, Cand *partial, int P,
                            hipStream_t stream);
+// count == null: merge the P lists of every query.  count given, repair == 0: query q's input is
+// its candidate array of count[q] entries (capacity cap = P kp), skipped when it overflowed.
+// count given, repair != 0: merge the P lists, but only of the queries whose array overflowed.
 hipError_t launch_flat_merge(int kp, const Cand *partial, int P, int B, int k, int32_t *ids, float *scores,
-                             hipStream_t stream);
+                             const int *count, int cap, int repair, hipStream_t stream);
 
 constexpr int GRAPH_EF_DOUBLE = 2048;    // candidate lists up to this length are double-buffered in LDS
 // cus workgroups of 8 waves, each wave iters x 8 MFMA 32x32x16 fp16 (32768 flop each) on register operands

@@ -83,6 +83,12 @@ def test_cfg0_graph_fp32(cfg0):
     (300, 4096, 9, 2),              # largest d
     (600_001, 64, 200, 3),          # matrix-core path with the sampling pass, one query tile
     (300_000, 32, 600, 4),          # ... three query tiles
+    (131_072 + 77, 128, 96, 5),     # matrix-core path with candidate arrays (k > 4), 128-query tile
+    (200_003, 64, 300, 16),         # ... two 256-query tiles, k = K_MAX
+    (150_000, 96, 130, 10),         # ... ragged sample tile
+    (131_072, 64, 1, 5),            # streaming path with candidate arrays (k > 4), one query
+    (140_000, 136, 17, 10),         # ... d not a multiple of 32
+    (150_001, 72, 70, 7),           # ... two passes of queries
 ])
 def test_flat_shapes(dtype, N, d, B, k):
     say(f"flat shapes: dtype={dtype} N={N} d={d} B={B} k={k}")
@@ -105,6 +111,35 @@ def test_flat_ties_go_to_lower_id():
     assert float(sc[0, 0]) == float(sc[0, 5])
     o_ids, _, _ = oracle.flat_search(x.numpy(), q.numpy(), 8)
     assert ids.cpu().numpy().tolist() == o_ids.tolist()
+
+
+@pytest.mark.parametrize("dtype", [torch.float16, torch.bfloat16])
+@pytest.mark.parametrize("B,a,b,n_wide,n_stream", [(80, 7, 66, 1, 0), (20, 7, 13, 0, 1)])
+def test_flat_candidate_array_overflow_is_repaired(dtype, B, a, b, n_wide, n_stream):
+    """k > 4 on a large corpus collects, per query, the rows that reach a sampled bound of the
+    k-th best score (large batches on the matrix cores, small ones in the streaming kernel).  Thousands of rows tied at the top overflow that array; such a query is then
+    recomputed by the streaming kernel while the others keep their results.  Rows sorted by
+    cluster (the sample must still represent every cluster) are covered as well."""
+    N, d, k = 140_000, 64, 6
+    c = synth.make_corpus(N, d, 16, seed=31, dtype=dtype, zipf_a=None, sigma=0.3)
+    order = torch.argsort(c.labels.cpu(), stable=True)
+    x = c.x.cpu()[order].contiguous()
+    gen = torch.Generator().manual_seed(3)
+    copies = torch.randperm(N, generator=gen)[:6000]
+    x[copies] = x[int(copies[0])].clone()
+    q = synth.make_queries(c, B).cpu()
+    q[a] = x[int(copies[0])]
+    q[b] = x[int(copies[0])]
+    say(f"flat candidate arrays with 6000 tied rows: dtype={dtype} B={B}")
+    ann.ann_timing_enable(True)
+    ids, sc, (o_ids, o_sc, o_sc64) = flat_both(x, q, k)
+    wide, stream = ann.ann_timing_read(ann.binding.KERNEL_FLAT_WIDE), ann.ann_timing_read(ann.binding.KERNEL_FLAT_STREAM)
+    ann.ann_timing_enable(False)
+    assert wide[0] == n_wide and stream[0] == n_stream          # the main pass; the repair pass is not recorded
+    low = sorted(copies.tolist())[:k]
+    assert ids[a].tolist() == low and ids[b].tolist() == low and o_ids[a].tolist() == low
+    strict, tolerant, n = compare_topk(ids, sc, o_ids, o_sc64, to_np(x), to_np(q), dtype=np_dtype_name(x))
+    assert strict >= n - 2, (strict, n)
 
 
 def test_flat_short_entry_point_and_reuse_of_outputs():
