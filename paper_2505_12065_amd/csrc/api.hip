@@ -145,13 +145,13 @@ int kp_of(int k) { return k <= 4 ? 4 : 16; }
 struct FlatPlan {
     int kp, P, nqg_max;
     int wide_ntg;            // > 0: matrix-core path with this many query-tile groups
-    int sample_tiles;        // > 0: a sampling pass over the first tiles supplies starting thresholds
-    int pstride;             // slabs per query in the partial array (P, plus one for the sample)
+    int pstride;             // slabs per query in the partial array
     size_t sample_ofs, thr_ofs;   // byte offsets of the sample lists and thresholds in the workspace
     // k > 4 on the matrix-core path: candidate arrays instead of lists, streaming kernel as repair
     bool emit;
     int emit_cap;                 // entries of a query's candidate array
-    int sample_P;                 // slabs of the sampling pass
+    int sample_P;                 // > 0: a sampling pass with this many slabs supplies thresholds
+    int sample_skip;              // > 0: the sample is the first sample_skip tiles, which the main pass skips
     int st_P, st_nqg_max;         // geometry of the repair pass (streaming kernel, lists of 16)
     size_t cnt_ofs, cand_ofs;
     size_t ws_bytes;
@@ -159,17 +159,17 @@ struct FlatPlan {
 
 constexpr int WIDE_MIN_B = 65;   // smallest batch sent to the matrix-core path
 constexpr int EMIT_CAP = 4096;   // candidate-array entries per query (k > 4), a multiple of 16
-constexpr int EMIT_STRIDE = 64;  // the sampling pass of that path scores every 64th row
-constexpr int64_t EMIT_MIN_N = 128 * 1024;
+constexpr int SAMPLE_STRIDE = 64; // a sampling pass scores every 64th row
+constexpr int64_t SAMPLE_MIN_N = 64 * 1024, EMIT_MIN_N = 128 * 1024;
 
 FlatPlan flat_plan(int cus, int64_t N, int d, int dtype, int B, int k, bool allow_emit = true) {
     FlatPlan pl;
     pl.kp = kp_of(k);
     pl.wide_ntg = 0;
-    pl.sample_tiles = 0;
     pl.emit = false;
     pl.emit_cap = 0;
     pl.sample_P = 0;
+    pl.sample_skip = 0;
     // k > 4 on a large 16-bit corpus: lists of 16 per lane are slow to maintain (and do not fit the
     // matrix-core kernel's registers), so the main pass keeps no lists; it appends every score that
     // reaches a lower bound of the query's k-th best to a per-query candidate array.  The bound is
@@ -187,7 +187,7 @@ FlatPlan flat_plan(int cus, int64_t N, int d, int dtype, int B, int k, bool allo
         pl.st_P = st.P;
         pl.st_nqg_max = st.nqg_max;
         pl.pstride = st.P;
-        const int64_t nv = (N + EMIT_STRIDE - 1) / EMIT_STRIDE;
+        const int64_t nv = (N + SAMPLE_STRIDE - 1) / SAMPLE_STRIDE;
         if (pl.wide_ntg > 0) {
             const int64_t stiles = (nv + 255) / 256;                       // >= 8
             pl.sample_P = (int)(stiles < pl.P ? stiles : pl.P);
@@ -208,13 +208,21 @@ FlatPlan flat_plan(int cus, int64_t N, int d, int dtype, int B, int k, bool allo
         const int nt = (B + wide_query_tile(B) - 1) / wide_query_tile(B);
         pl.wide_ntg = nt < 8 ? nt : 8;
         int P = cus / pl.wide_ntg;
+        if (wide_query_tile(B) == 128) P *= 2;       // 4-wave workgroups, two per compute unit
         const int64_t mtiles = (N + 255) / 256;
         if (P > mtiles) P = (int)mtiles;
         pl.P = P < 1 ? 1 : P;
         pl.nqg_max = 4;
-        // enough tiles per slab: score one tile per slab first, exactly, and start the main
-        // pass from the sample's k-th best scores (few rows then pass the threshold test)
-        if (mtiles >= 8 * (int64_t)pl.P) pl.sample_tiles = pl.P;
+        // a corpus of some size: score a sample first, exactly, and start the main pass from the k-th
+        // best scores of that sample (few rows then pass the threshold test at all).  Many tiles per
+        // slab: the sample is the first tile of every slab-to-be, kept as one more slab and skipped by
+        // the main pass; otherwise every 64th row, which the main pass scores again.
+        if (mtiles >= 8 * (int64_t)pl.P) {
+            pl.sample_P = pl.sample_skip = pl.P;
+        } else if (N >= SAMPLE_MIN_N) {
+            const int64_t stiles = ((N + SAMPLE_STRIDE - 1) / SAMPLE_STRIDE + 255) / 256;
+            pl.sample_P = (int)(stiles < pl.P ? stiles : pl.P);
+        }
     } else if (dtype == ANN_F32) {
         const int64_t groups = (N + 7) / 8;
         int64_t P = (groups + 3) / 4;
@@ -240,10 +248,10 @@ FlatPlan flat_plan(int cus, int64_t N, int d, int dtype, int B, int k, bool allo
     }
     if (pl.P > P_MAX) pl.P = P_MAX;
     if (pl.P < 1) pl.P = 1;
-    pl.pstride = pl.P + (pl.sample_tiles > 0 ? 1 : 0);
+    pl.pstride = pl.P + (pl.sample_skip > 0 ? 1 : 0);
     pl.sample_ofs = (size_t)B * pl.pstride * pl.kp * sizeof(Cand);
-    pl.thr_ofs = pl.sample_ofs + (size_t)B * pl.sample_tiles * pl.kp * sizeof(Cand);
-    pl.ws_bytes = pl.thr_ofs + (pl.sample_tiles > 0 ? (size_t)B * sizeof(float) : 0);
+    pl.thr_ofs = pl.sample_ofs + (size_t)B * pl.sample_P * 4 * sizeof(Cand);
+    pl.ws_bytes = pl.thr_ofs + (pl.sample_P > 0 ? (size_t)B * sizeof(float) : 0);
     return pl;
 }
 
@@ -277,14 +285,14 @@ int flat_search_emit(const FlatPlan &pl, const void *X, int64_t N, int d, int dt
     // sampling pass: every 64th row, the best 4 per slab and query
     if (pl.wide_ntg > 0) {
         hipError_t e = launch_flat_wide(dtype, 1, X, N, d, Q, B, sample, pl.sample_P, pl.wide_ntg, 0, nullptr, pl.sample_P,
-                                        0, nullptr, EMIT_STRIDE, stream);
+                                        0, nullptr, SAMPLE_STRIDE, stream);
         if (int rc = check_launch("flat_wide_kernel (sample)", e)) return rc;
     } else {
         StreamOpts o;
-        o.row_stride = EMIT_STRIDE;
+        o.row_stride = SAMPLE_STRIDE;
         if (int rc = flat_stream_all(4, pl.nqg_max, pl.sample_P, X, N, d, dtype, Q, B, sample, o, false, stream)) return rc;
     }
-    if (int rc = check_launch("flat_sample_kth_kernel", launch_flat_sample_kth(sample, pl.sample_P, B, k, thr, stream)))
+    if (int rc = check_launch("flat_sample_kth_kernel", launch_flat_sample_kth(sample, pl.sample_P, B, k, thr, nullptr, 0, 0, stream)))
         return rc;
     // main pass: candidates
     if (pl.wide_ntg > 0) {
@@ -327,21 +335,22 @@ int flat_search_run(const FlatPlan &pl, const void *X, int64_t N, int d, int dty
         if (int rc = check_launch("flat_f32_kernel", e)) return rc;
     } else if (pl.wide_ntg > 0) {
         const float *thr0 = nullptr;
-        if (pl.sample_tiles > 0) {
+        if (pl.sample_P > 0) {
             Cand *sample = reinterpret_cast<Cand *>(reinterpret_cast<char *>(partial) + pl.sample_ofs);
             float *thr = reinterpret_cast<float *>(reinterpret_cast<char *>(partial) + pl.thr_ofs);
-            hipError_t e = launch_flat_wide(dtype, 1, X, (int64_t)pl.sample_tiles * 256, d, Q, B, sample,
-                                            pl.sample_tiles, pl.wide_ntg, 0, nullptr, pl.sample_tiles, 0, nullptr, 1, stream);
+            const bool skip = pl.sample_skip > 0;
+            hipError_t e = launch_flat_wide(dtype, 1, X, skip ? (int64_t)pl.sample_skip * 256 : N, d, Q, B, sample, pl.sample_P,
+                                            pl.wide_ntg, 0, nullptr, pl.sample_P, 0, nullptr, skip ? 1 : SAMPLE_STRIDE, stream);
             if (int rc = check_launch("flat_wide_kernel (sample)", e)) return rc;
-            e = launch_flat_sample_merge(pl.kp, sample, pl.sample_tiles, B, partial, pl.pstride, pl.P, thr, stream);
-            if (int rc = check_launch("flat_sample_merge_kernel", e)) return rc;
+            e = launch_flat_sample_kth(sample, pl.sample_P, B, k, thr, skip ? partial : nullptr, pl.pstride, pl.P, stream);
+            if (int rc = check_launch("flat_sample_kth_kernel", e)) return rc;
             thr0 = thr;
         }
         hipError_t e;
         {
             TimedScope timed(ANN_KERNEL_FLAT_WIDE, stream);
-            e = launch_flat_wide(dtype, 0, X, N, d, Q, B, partial, pl.P, pl.wide_ntg, pl.sample_tiles, thr0,
-                                 pl.pstride, 0, nullptr, 1, stream);
+            e = launch_flat_wide(dtype, 0, X, N, d, Q, B, partial, pl.P, pl.wide_ntg, pl.sample_skip, thr0, pl.pstride, 0,
+                                 nullptr, 1, stream);
         }
         if (int rc = check_launch("flat_wide_kernel", e)) return rc;
     } else {

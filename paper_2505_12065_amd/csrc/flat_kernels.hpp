@@ -309,33 +309,15 @@ __global__ __launch_bounds__(256) void flat_merge_kernel(const Cand *__restrict_
     }
 }
 
-// One wavefront per query: the KP best of Ps sampled lists, kept as one more slab of the
-// main partial array; their KP-th best score becomes the query's starting threshold.
-template <int KP>
-__global__ __launch_bounds__(64) void flat_sample_merge_kernel(const Cand *__restrict__ src, int Ps,
-                                                               Cand *__restrict__ dst, int pstride, int pslot,
-                                                               float *__restrict__ thr) {
-    const int q = blockIdx.x, lane = threadIdx.x;
-    const Cand *in = src + (size_t)q * Ps * KP;
-    TopList<KP> best;
-    best.init();
-    gather_best<KP>(in, Ps * KP, lane, 64, best);
-    TopList<KP> top;
-    group_top<KP, KP, 1, 64>(best, top);
-    if (lane == 0) {
-        Cand *out = dst + ((size_t)q * pstride + pslot) * KP;
-#pragma unroll
-        for (int j = 0; j < KP; ++j) out[j] = Cand{top.s[j], top.id[j]};
-        thr[q] = top.id[KP - 1] != EMPTY_ID ? top.s[KP - 1] : -INFINITY;
-    }
-}
-
 // One wavefront per query: the k-th best score among Ps sampled lists of KS entries (src[(q Ps + s) KS ..)),
 // -inf when the sample holds fewer than k rows.  The lists come from disjoint rows, so this is the
-// k-th best of a subset of the corpus: a lower bound of the final k-th best score.
+// k-th best of a subset of the corpus: a lower bound of the final k-th best score.  With dst, the
+// sample's KS best are also kept, as slab pslot of the query's lists dst[(q pstride + pslot) KS ..)
+// (for a sample whose rows the main pass then skips).
 template <int KS, int KO>
 __global__ __launch_bounds__(64) void flat_sample_kth_kernel(const Cand *__restrict__ src, int Ps, int k,
-                                                             float *__restrict__ thr) {
+                                                             float *__restrict__ thr, Cand *__restrict__ dst,
+                                                             int pstride, int pslot) {
     const int q = blockIdx.x, lane = threadIdx.x;
     TopList<KO> best;
     best.init();
@@ -348,6 +330,10 @@ __global__ __launch_bounds__(64) void flat_sample_kth_kernel(const Cand *__restr
         for (int j = 0; j < KO; ++j)
             if (j == k - 1 && top.id[j] != EMPTY_ID) t = top.s[j];
         thr[q] = t;
+        if (dst) {
+#pragma unroll
+            for (int j = 0; j < KS; ++j) dst[((size_t)q * pstride + pslot) * KS + j] = Cand{top.s[j], top.id[j]};
+        }
     }
 }
 

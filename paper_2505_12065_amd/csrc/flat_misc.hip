@@ -45,17 +45,9 @@ hipError_t launch_flat_merge(int kp, const Cand *partial, int P, int B, int k, i
     return hipGetLastError();
 }
 
-hipError_t launch_flat_sample_kth(const Cand *src, int Ps, int B, int k, float *thr, hipStream_t stream) {
-    hipLaunchKernelGGL((flat_sample_kth_kernel<4, 16>), dim3(B), dim3(64), 0, stream, src, Ps, k, thr);
-    return hipGetLastError();
-}
-
-hipError_t launch_flat_sample_merge(int kp, const Cand *src, int Ps, int B, Cand *dst, int pstride, int pslot,
-                                    float *thr, hipStream_t stream) {
-    if (kp == 4)
-        hipLaunchKernelGGL((flat_sample_merge_kernel<4>), dim3(B), dim3(64), 0, stream, src, Ps, dst, pstride, pslot, thr);
-    else
-        hipLaunchKernelGGL((flat_sample_merge_kernel<16>), dim3(B), dim3(64), 0, stream, src, Ps, dst, pstride, pslot, thr);
+hipError_t launch_flat_sample_kth(const Cand *src, int Ps, int B, int k, float *thr, Cand *dst, int pstride, int pslot,
+                                  hipStream_t stream) {
+    hipLaunchKernelGGL((flat_sample_kth_kernel<4, 16>), dim3(B), dim3(64), 0, stream, src, Ps, k, thr, dst, pstride, pslot);
     return hipGetLastError();
 }
 

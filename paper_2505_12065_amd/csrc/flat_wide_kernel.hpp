@@ -41,9 +41,12 @@ struct WideCfg {
     static constexpr int LPW = FRAGS / WAVES;           // fragments loaded per wave and stage
     static_assert(FRAGS % WAVES == 0, "fragments must divide evenly over the waves");
     static constexpr int STAGE_BYTES = FRAGS * 1024;
+    // The 128-query tile has 4 waves only: three stages of 24 KB (and the exchange buffer inside
+    // them) let two such workgroups share a compute unit, so every SIMD still holds two waves.
+    static constexpr int STAGES = NWN == 2 ? 3 : WIDE_STAGES;
     static constexpr int XCH_BYTES = 2 * BN * WIDE_KP * (int)sizeof(Cand);
-    static constexpr int THR_BYTES = BN * 4;
-    static constexpr int DYN_LDS_BYTES = WIDE_STAGES * STAGE_BYTES;
+    static_assert(XCH_BYTES <= STAGES * STAGE_BYTES, "the exchange buffer lives in the stage buffers");
+    static constexpr int DYN_LDS_BYTES = STAGES * STAGE_BYTES;
 };
 
 // order-preserving map float -> int (for atomicMax on thresholds)
@@ -87,9 +90,8 @@ __device__ __forceinline__ void lds_barrier() {
 //   X [N, d], Q [B, d] 16-bit, d a multiple of 32.   partial [B, P, WIDE_KP]
 //   gridDim.x = P * NTG; block -> (slab, query-tile group), same-slab blocks on one XCD
 //   rows [256 tile_begin, N) are scanned, split into P slabs of whole tiles.
-//   thr_init (optional, [B]): per query a score that at least KP corpus rows outside
-//   the scanned range reach or exceed together with rows inside it, i.e. a lower bound
-//   of the final KP-th best; rows scoring below it are dropped at once.
+//   thr_init (optional, [B]): per query a lower bound of its final k-th best score (the k-th best
+//   of a sample of the corpus); rows scoring below it are dropped at once.
 //   Slab s of query q is written to partial[(q * pstride + pslot0 + s) * KP ..).
 //   MODE WIDE_LISTS: the epilogue described above.
 //   MODE WIDE_SELECT: threshold-free epilogue (per lane the KP best of its 64 scores by repeated
@@ -103,7 +105,7 @@ __device__ __forceinline__ void lds_barrier() {
 //   the array overflowed and recomputes that query another way).
 constexpr int WIDE_LISTS = 0, WIDE_SELECT = 1, WIDE_EMIT = 2;
 template <class T, int WNF, int NWN, int MODE>
-__global__ __launch_bounds__(128 * NWN) void flat_wide_kernel(const void *__restrict__ X, int64_t N, int d,
+__global__ __launch_bounds__(128 * NWN, 2) void flat_wide_kernel(const void *__restrict__ X, int64_t N, int d,
                                                                     const void *__restrict__ Q, int B,
                                                                     Cand *__restrict__ partial, int P, int NTG,
                                                                     int64_t tile_begin,
@@ -116,12 +118,12 @@ __global__ __launch_bounds__(128 * NWN) void flat_wide_kernel(const void *__rest
     const int S = SELECT ? row_stride : 1;
     const int64_t NV = SELECT ? (N + S - 1) / S : N;
     using C = WideCfg<WNF, NWN>;
-    constexpr int KP = WIDE_KP, NST = WIDE_STAGES, LPW = C::LPW;
+    constexpr int KP = WIDE_KP, NST = C::STAGES, LPW = C::LPW;
     extern __shared__ __align__(16) unsigned char smem[];
-    unsigned char *stage_mem = smem;                  // dynamic LDS: the stage buffers only
+    unsigned char *stage_mem = smem;                  // dynamic LDS: the stage buffers ...
+    Cand *xch = reinterpret_cast<Cand *>(smem);       // ... reused as [2][BN][KP] once a slab is done
     // separate LDS objects, so that stores to them are known not to touch a stage buffer
     // a direct global->LDS load may still be writing (no wait on those loads is needed)
-    __shared__ Cand xch[2 * C::BN * KP];              // [2][BN][KP]
     __shared__ int thr_l[C::BN];
     __shared__ float wq_s[C::WAVES * WIDE_QCAP];      // per-wave queue of passing scores:
     __shared__ int wq_r[C::WAVES * WIDE_QCAP];        //   score, row id, owning lane
@@ -151,9 +153,11 @@ __global__ __launch_bounds__(128 * NWN) void flat_wide_kernel(const void *__rest
             constexpr int j = decltype(jc)::value;
             best[j].init();
             thr[j] = -INFINITY;
+            const int q = n0 + (wn * WNF + j) * 32 + l32;
             if constexpr (MODE == WIDE_EMIT) {               // fixed thresholds; queries past B never emit
-                const int q = n0 + (wn * WNF + j) * 32 + l32;
                 thr[j] = q < B ? thr_init[q] : INFINITY;
+            } else if (thr_init) {
+                thr[j] = thr_init[q < B ? q : B - 1];
             }
         });
         if (tid < C::BN) {
@@ -223,7 +227,7 @@ __global__ __launch_bounds__(128 * NWN) void flat_wide_kernel(const void *__rest
         int64_t ctile = t0;                                  // tile being computed
         for (int it = 0; it < total; ++it) {
             // stage `it` has landed once only the newer stages' loads are outstanding
-            if (it + 2 < total) wait_vmcnt<2 * LPW>();
+            if (NST >= 4 && it + 2 < total) wait_vmcnt<2 * LPW>();
             else if (it + 1 < total) wait_vmcnt<LPW>();
             else wait_vmcnt<0>();
             lds_barrier();                                   // ... for every wave; buffer (it-1)%NST is free
@@ -340,7 +344,10 @@ __global__ __launch_bounds__(128 * NWN) void flat_wide_kernel(const void *__rest
                 static_for<WNF>([&](auto jc) {
                     constexpr int j = decltype(jc)::value;
                     const int ql = (wn * WNF + j) * 32 + l32;
-                    float t = fmaxf(thr[j], key_float(thr_l[ql]));
+                    // with a sampled threshold the workgroup's own running k-th best (a bound from
+                    // 1/P of the corpus) never overtakes it: the shared word is left alone
+                    float t = thr[j];
+                    if (!thr_init) t = fmaxf(t, key_float(thr_l[ql]));
                     float gm[4];                             // best score of each 32-row block
                     static_for<4>([&](auto ic) {
                         constexpr int i = decltype(ic)::value;
@@ -410,7 +417,10 @@ __global__ __launch_bounds__(128 * NWN) void flat_wide_kernel(const void *__rest
                             // a lane's KP-th best bounds the final KP-th best from below: publish it
                             float mine = best[j].s[KP - 1];
                             mine = fmaxf(mine, __shfl_xor(mine, 32));
-                            if (mine > t) { lds_atomic_max(&thr_l[ql], float_key(mine)); t = mine; }
+                            if (mine > t) {
+                                if (!thr_init) lds_atomic_max(&thr_l[ql], float_key(mine));
+                                t = mine;
+                            }
                             start = stop;
                         } while (start < 64);
                     }
@@ -427,6 +437,7 @@ __global__ __launch_bounds__(128 * NWN) void flat_wide_kernel(const void *__rest
         }
         // lanes l and l^32 hold the same queries; then the two wm-waves meet in LDS
         static_for<WNF>([&](auto jc) { best[decltype(jc)::value].merge_xor(32); });
+        __syncthreads();                                     // every wave is done with the stage buffers
         if (lhi == 0) {
             static_for<WNF>([&](auto jc) {
                 constexpr int j = decltype(jc)::value;

@@ -43,20 +43,18 @@ hipError_t launch_flat_stream_bf16(int nqg, int kp, const void *X, int64_t N, in
 // Large batches on the matrix cores (16-bit corpora, d % 32 == 0, lists of 4).
 // Query tile is wide_query_tile(B) queries; gridDim = P slabs x NTG query-tile groups;
 // rows [256 tile_begin, N) are scanned; results go to partial[(q pstride + pslot0 + slab) 4 ..).
-// mode 0: list epilogue, thr_init = optional per-query lower bounds of the final 4th-best score;
-// mode 1: threshold-free selection epilogue (sampling pass);
+// mode 0: list epilogue, thr_init = optional per-query lower bounds of the final k-th best score;
+// mode 1: threshold-free selection epilogue (sampling pass), rows 0, row_stride, 2 row_stride, ... only;
 // mode 2 (k > 4): every score >= thr_init[q] is appended to the candidate array
 // partial[q pstride ..) through emit_count[q] (zero on entry; counts past pstride mean overflow).
 int wide_query_tile(int B);
 hipError_t launch_flat_wide(int dtype, int mode, const void *X, int64_t N, int d, const void *Q, int B,
                             Cand *partial, int P, int NTG, int64_t tile_begin, const float *thr_init, int pstride,
                             int pslot0, int *emit_count, int row_stride, hipStream_t stream);
-// thr[q] = k-th best score among the Ps sampled lists of 4 of query q (-inf if fewer), k <= 16
-hipError_t launch_flat_sample_kth(const Cand *src, int Ps, int B, int k, float *thr, hipStream_t stream);
-// Per query: merge Ps sampled lists (src[(q Ps + s) kp ..)) into dst[(q pstride + pslot) kp ..)
-// and write the kp-th best score of the merged list (-inf if it has fewer entries) to thr[q].
-hipError_t launch_flat_sample_merge(int kp, const Cand *src, int Ps, int B, Cand *dst, int pstride, int pslot,
-                                    float *thr, hipStream_t stream);
+// thr[q] = k-th best score among the Ps sampled lists of 4 of query q (-inf if fewer), k <= 16;
+// with dst, the 4 best of the sample also become slab pslot of dst[B, pstride, 4]
+hipError_t launch_flat_sample_kth(const Cand *src, int Ps, int B, int k, float *thr, Cand *dst, int pstride, int pslot,
+                                  hipStream_t stream);
 hipError_t launch_flat_f32(int kp, const float *X, int64_t N, int d, const float *Q, int B, Cand *partial, int P,
                            hipStream_t stream);
 // count == null: merge the P lists of every query.  count given, repair == 0: query q's input is
