@@ -170,6 +170,23 @@ def main() -> int:
                 "random_operands_TFLOPs": ann.ann_measure_mfma_rate(True)}
     rooflines["flat_b512"]["box_mfma_rate"] = mfma_box
     rooflines["flat_b512"]["frac_of_box_random_operand_rate"] = rooflines["flat_b512"]["achieved"] / mfma_box["random_operands_TFLOPs"]
+    # context: what the vendor's GEMM (torch.matmul -> hipBLASLt) reaches on this machine for the very same
+    # contraction S = X Q^T, with S written to memory and no top-k at all; comparison only, the product
+    # path never calls it
+    s_out = torch.empty(N, B_LARGE, dtype=x.dtype, device=dev)
+    qt = q_all.t()
+    for _ in range(3):
+        torch.matmul(x, qt, out=s_out)
+    g0, g1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    g0.record()
+    for _ in range(10):
+        torch.matmul(x, qt, out=s_out)
+    g1.record()
+    torch.cuda.synchronize()
+    gemm_ms = g0.elapsed_time(g1) / 10
+    del s_out
+    rooflines["flat_b512"]["vendor_gemm_same_shape"] = {"ms": gemm_ms, "TFLOPs": flat_flops / gemm_ms / 1e9,
+                                                        "note": "torch.matmul, writes S[N,B], no top-k"}
     traffic = measured_traffic()
     for i, (leg, r) in enumerate(rooflines.items()):
         r["frac"] = r["achieved"] / r["peak"]

@@ -255,21 +255,20 @@ FlatPlan flat_plan(int cus, int64_t N, int d, int dtype, int B, int k, bool allo
     return pl;
 }
 
-// 16-bit corpus, streaming kernel over all B queries, 64 at a time (kp 0: candidate-array mode)
+// 16-bit corpus, streaming kernel over all B queries in one launch: groups of 16 nqg_max queries are
+// served one after the other inside the kernel (kp 0: candidate-array mode)
 int flat_stream_all(int kp, int nqg_max, int P, const void *X, int64_t N, int d, int dtype, const void *Q, int B,
-                    Cand *partial, const StreamOpts &o, bool timed_launches, hipStream_t stream) {
-    for (int q0 = 0; q0 < B; q0 += 16 * nqg_max) {
-        const int left = B - q0;
-        const int nqg = left > 16 * nqg_max ? nqg_max : (left + 15) / 16;
-        hipError_t e;
-        {
-            TimedScope timed(timed_launches ? ANN_KERNEL_FLAT_STREAM : -1, stream);
-            e = dtype == ANN_F16 ? launch_flat_stream_f16(nqg, kp, X, N, d, Q, B, q0, partial, P, o, stream)
-                                 : launch_flat_stream_bf16(nqg, kp, X, N, d, Q, B, q0, partial, P, o, stream);
-        }
-        if (int rc = check_launch("flat_stream_kernel", e)) return rc;
+                    Cand *partial, StreamOpts o, bool timed_launch, hipStream_t stream) {
+    const int group = 16 * nqg_max;
+    const int nqg = B > group ? nqg_max : (B + 15) / 16;
+    o.passes = B > group ? (B + group - 1) / group : 1;
+    hipError_t e;
+    {
+        TimedScope timed(timed_launch ? ANN_KERNEL_FLAT_STREAM : -1, stream);
+        e = dtype == ANN_F16 ? launch_flat_stream_f16(nqg, kp, X, N, d, Q, B, 0, partial, P, o, stream)
+                             : launch_flat_stream_bf16(nqg, kp, X, N, d, Q, B, 0, partial, P, o, stream);
     }
-    return ANN_OK;
+    return check_launch("flat_stream_kernel", e);
 }
 
 int flat_search_emit(const FlatPlan &pl, const void *X, int64_t N, int d, int dtype, const void *Q, int B, int k,

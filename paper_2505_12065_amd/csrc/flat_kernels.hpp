@@ -24,19 +24,15 @@ constexpr int STREAM_UNROLL = 8;   // 16-byte loads a lane keeps in flight (6..2
 // up with one query (lane % 16) and four rows (4*(lane/16) + i) per tile of 16 rows.
 //   X        [N, d] 16-bit           Q  [B, d] 16-bit (queries q0 .. q0+NQG*16 are used)
 //   partial  [B, P, KP] pairs, P = gridDim.x
-//   o        see StreamOpts: gate on overflowed queries, row stride of a sampling pass, and
-//            (EMIT, for k > 4) no lists at all: every (score, row) with score >= o.thr[q] is
-//            appended to the candidate array partial[q * o.cap ..) through o.count[q]
+//   o        see StreamOpts: row stride of a sampling pass, and (EMIT, for k > 4) no lists at all:
+//            every (score, row) with score >= o.thr[q] is appended to the candidate array
+//            partial[q * o.cap ..) through o.count[q]
+// One pass of the whole workgroup over its share of the corpus for NQG*16 queries.
 template <class T, int NQG, int KP, bool DFULL, bool EMIT>
-__global__ __launch_bounds__(512) void flat_stream_kernel(const void *__restrict__ X, int64_t N, int d,
-                                                          const void *__restrict__ Q, int B, int q0,
-                                                          Cand *__restrict__ partial, StreamOpts o) {
-    extern __shared__ __align__(16) unsigned char smem[];
-    if (o.need) {
-        const int q = q0 + (int)threadIdx.x;
-        const int mine = threadIdx.x < NQG * 16 && q < B && o.need[q] > o.need_above;
-        if (!__syncthreads_or(mine)) return;
-    }
+__device__ __forceinline__ void flat_stream_pass(const void *__restrict__ X, int64_t N, int d,
+                                                 const void *__restrict__ Q, int B, int q0,
+                                                 Cand *__restrict__ partial, const StreamOpts &o,
+                                                 unsigned char *smem) {
     const int S = o.row_stride;
     const int64_t NV = (N + S - 1) / S;               // rows 0, S, 2S, ... are "virtual" rows 0 .. NV-1
     u4 *qf = reinterpret_cast<u4 *>(smem);            // [NQG][steps][64]
@@ -168,6 +164,25 @@ __global__ __launch_bounds__(512) void flat_stream_kernel(const void *__restrict
 #pragma unroll
             for (int j = 0; j < KP; ++j) out[j] = Cand{fin.s[j], fin.id[j]};
         }
+    }
+}
+
+// o.passes consecutive groups of NQG*16 queries starting at q0, one after the other in one launch.
+// With o.need, a group is skipped unless need[q] > need_above for one of its queries (the repair
+// pass behind the candidate arrays: usually every group is skipped).
+template <class T, int NQG, int KP, bool DFULL, bool EMIT>
+__global__ __launch_bounds__(512) void flat_stream_kernel(const void *__restrict__ X, int64_t N, int d,
+                                                          const void *__restrict__ Q, int B, int q0,
+                                                          Cand *__restrict__ partial, StreamOpts o) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    for (int pass = 0; pass < o.passes; ++pass, q0 += NQG * 16) {
+        if (o.need) {
+            const int q = q0 + (int)threadIdx.x;
+            const int mine = threadIdx.x < NQG * 16 && q < B && o.need[q] > o.need_above;
+            if (!__syncthreads_or(mine)) continue;
+        }
+        if (pass) __syncthreads();                    // the previous pass is done with the LDS
+        flat_stream_pass<T, NQG, KP, DFULL, EMIT>(X, N, d, Q, B, q0, partial, o, smem);
     }
 }
 

@@ -26,8 +26,9 @@ size_t f32_lds_bytes(int d, int waves, int kp);
 
 // Optional behaviour of a flat_stream_kernel launch.
 struct StreamOpts {
-    const int *need = nullptr;   // [B]: the launch returns at once unless need[q] > need_above for
-    int need_above = 0;          //      one of its queries (repair pass behind the candidate arrays)
+    const int *need = nullptr;   // [B]: a group of queries is skipped unless need[q] > need_above for
+    int need_above = 0;          //      one of them (repair pass behind the candidate arrays)
+    int passes = 1;              // consecutive groups of nqg * 16 queries served by the launch, from q0 on
     int row_stride = 1;          // S > 1: only rows 0, S, 2S, ... are scored (sampling pass)
     const float *thr = nullptr;  // candidate-array mode: [B] lower bounds of the final k-th best score,
     int *count = nullptr;        //   [B] entry counters (zero on entry; a count past cap means overflow),
