@@ -47,7 +47,10 @@ hipError_t launch_flat_merge(int kp, const Cand *partial, int P, int B, int k, i
 
 hipError_t launch_flat_sample_kth(const Cand *src, int Ps, int B, int k, float *thr, Cand *dst, int pstride, int pslot,
                                   hipStream_t stream) {
-    hipLaunchKernelGGL((flat_sample_kth_kernel<4, 16>), dim3(B), dim3(64), 0, stream, src, Ps, k, thr, dst, pstride, pslot);
+    if (k <= 4)   // short lists: a fraction of the selection work
+        hipLaunchKernelGGL((flat_sample_kth_kernel<4, 4>), dim3(B), dim3(64), 0, stream, src, Ps, k, thr, dst, pstride, pslot);
+    else
+        hipLaunchKernelGGL((flat_sample_kth_kernel<4, 16>), dim3(B), dim3(64), 0, stream, src, Ps, k, thr, dst, pstride, pslot);
     return hipGetLastError();
 }
 
