@@ -30,13 +30,13 @@ def sample_rows(B, n=12):
     return np.unique(np.concatenate([np.arange(4), np.linspace(4, B - 5, n - 8).astype(int), np.arange(B - 4, B)]))
 
 
-def check_flat_sampled(x, xh, q, B):
+def check_flat_sampled(x, xh, q, B, k=K):
     qb = q[:B].contiguous()
-    ids, sc = ann.ann_flat_search_typed(x, qb, K)
+    ids, sc = ann.ann_flat_search_typed(x, qb, k)
     torch.cuda.synchronize()
     rows = sample_rows(B)
     qh = qb.cpu().numpy()
-    o_ids, _, o_sc64 = oracle.flat_search(xh, qh[rows], K)
+    o_ids, _, o_sc64 = oracle.flat_search(xh, qh[rows], k)
     strict, tolerant, n = compare_topk(ids.cpu().numpy()[rows], sc.cpu().numpy()[rows], o_ids, o_sc64, xh, qh, rows=rows)
     return strict, tolerant, n, ids
 
@@ -56,6 +56,16 @@ def test_cfg1_flat_full_size(cfg1, B):
     c, q, xh = cfg1
     strict, tolerant, n, _ = check_flat_sampled(c.x, xh, q, B)
     say(f"cfg1 flat N=1,000,000 B={B}: oracle on {n} sampled queries, strict={strict} tolerant={tolerant}")
+    assert strict >= n - 1
+
+
+@pytest.mark.parametrize("B,k", [(16, 10), (128, 5), (512, 5), (512, 16)])
+def test_cfg1_flat_full_size_larger_k(cfg1, B, k):
+    """k > 4 (the paper retrieves k = 5): candidate arrays behind a sampled threshold, in the
+    streaming kernel (B = 16) and on the matrix cores."""
+    c, q, xh = cfg1
+    strict, tolerant, n, _ = check_flat_sampled(c.x, xh, q, B, k)
+    say(f"cfg1 flat N=1,000,000 B={B} k={k}: oracle on {n} sampled queries, strict={strict} tolerant={tolerant}")
     assert strict >= n - 1
 
 
@@ -133,6 +143,10 @@ def test_cfg3_flat_full_size():
     for B in (1, 16, 256):
         strict, tolerant, n, _ = check_flat_sampled(c.x, xh, q, B)
         say(f"cfg3 flat N=21,000,000 B={B}: oracle on {n} sampled queries, strict={strict} tolerant={tolerant}")
+        assert strict >= n - 1
+    for B, k in ((16, 10), (256, 5)):
+        strict, tolerant, n, _ = check_flat_sampled(c.x, xh, q, B, k)
+        say(f"cfg3 flat N=21,000,000 B={B} k={k}: oracle on {n} sampled queries, strict={strict} tolerant={tolerant}")
         assert strict >= n - 1
     del xh, c
     torch.cuda.empty_cache()
