@@ -234,11 +234,11 @@ FlatPlan flat_plan(int cus, int64_t N, int d, int dtype, int B, int k, bool allo
         int nqg_max = (int)((LDS_MAX - 16 * 1024) / ((size_t)steps * WAVE * 16));
         pl.nqg_max = nqg_max > 4 ? 4 : nqg_max;
         const int nqg = B > 16 * pl.nqg_max ? pl.nqg_max : (B + 15) / 16;
-        const size_t lds = stream_lds_bytes(nqg, steps, STREAM_THREADS / WAVE, pl.kp);
+        const int wpb = stream_waves(nqg, steps, pl.kp);
+        const size_t lds = stream_lds_bytes(nqg, steps, wpb, pl.kp);
         int occ = (int)(LDS_MAX / lds);
         occ = occ < 1 ? 1 : (occ > 2 ? 2 : occ);     // measured: more resident workgroups do not help
         const int64_t tiles = (N + 15) / 16;
-        const int wpb = STREAM_THREADS / WAVE;
         const int64_t cap = (int64_t)cus * occ;
         // every wave takes whole 16-row tiles in rounds; size the grid so that the last round
         // is as full as the others instead of leaving most of the chip idle

@@ -27,8 +27,8 @@ constexpr int STREAM_UNROLL = 8;   // 16-byte loads a lane keeps in flight (6..2
 //   o        see StreamOpts: row stride of a sampling pass, and (EMIT, for k > 4) no lists at all:
 //            every (score, row) with score >= o.thr[q] is appended to the candidate array
 //            partial[q * o.cap ..) through o.count[q]
-// One pass of the whole workgroup over its share of the corpus for NQG*16 queries.
-template <class T, int NQG, int KP, bool DFULL, bool EMIT>
+// One pass of the whole workgroup (NWV wavefronts) over its share of the corpus for NQG*16 queries.
+template <class T, int NQG, int KP, bool DFULL, bool EMIT, int NWV>
 __device__ __forceinline__ void flat_stream_pass(const void *__restrict__ X, int64_t N, int d,
                                                  const void *__restrict__ Q, int B, int q0,
                                                  Cand *__restrict__ partial, const StreamOpts &o,
@@ -142,14 +142,14 @@ __device__ __forceinline__ void flat_stream_pass(const void *__restrict__ X, int
         }
     });
     __syncthreads();
-    // the block's list of a query: its 8 wave lists spread over 32 lanes (4 lanes per wave
-    // list, KP/4 consecutive entries each), 16 queries per pass of the 512 threads
-    constexpr int NW = STREAM_THREADS / WAVE, LP = KP / 4;
-    static_assert(NW == 8 && KP % 4 == 0, "the final selection assumes 8 wave lists split four ways");
-    const int sub = tid & 31, w = sub >> 2, part = sub & 3;
+    // the block's list of a query: its NWV wave lists spread over 4 NWV lanes (4 lanes per wave
+    // list, KP/4 consecutive entries each), 16 queries per pass of the workgroup
+    constexpr int LP = KP / 4, LG = 4 * NWV;
+    static_assert((NWV == 8 || NWV == 16) && KP % 4 == 0, "the final selection splits every wave list four ways");
+    const int sub = tid & (LG - 1), w = sub >> 2, part = sub & 3;
 #pragma unroll
     for (int pass = 0; pass < NQG; ++pass) {
-        const int qi = pass * 16 + (tid >> 5);
+        const int qi = pass * 16 + tid / LG;
         TopList<LP> mine;
 #pragma unroll
         for (int j = 0; j < LP; ++j) {
@@ -158,7 +158,7 @@ __device__ __forceinline__ void flat_stream_pass(const void *__restrict__ X, int
             mine.id[j] = c.id;
         }
         TopList<KP> fin;
-        group_top<KP, LP, 1, 32>(mine, fin);
+        group_top<KP, LP, 1, LG>(mine, fin);
         if (sub == 0 && q0 + qi < B) {
             Cand *out = partial + ((size_t)(q0 + qi) * P + blockIdx.x) * KP;
 #pragma unroll
@@ -170,8 +170,8 @@ __device__ __forceinline__ void flat_stream_pass(const void *__restrict__ X, int
 // o.passes consecutive groups of NQG*16 queries starting at q0, one after the other in one launch.
 // With o.need, a group is skipped unless need[q] > need_above for one of its queries (the repair
 // pass behind the candidate arrays: usually every group is skipped).
-template <class T, int NQG, int KP, bool DFULL, bool EMIT>
-__global__ __launch_bounds__(512) void flat_stream_kernel(const void *__restrict__ X, int64_t N, int d,
+template <class T, int NQG, int KP, bool DFULL, bool EMIT, int NWV>
+__global__ __launch_bounds__(NWV * 64) void flat_stream_kernel(const void *__restrict__ X, int64_t N, int d,
                                                           const void *__restrict__ Q, int B, int q0,
                                                           Cand *__restrict__ partial, StreamOpts o) {
     extern __shared__ __align__(16) unsigned char smem[];
@@ -182,7 +182,7 @@ __global__ __launch_bounds__(512) void flat_stream_kernel(const void *__restrict
             if (!__syncthreads_or(mine)) continue;
         }
         if (pass) __syncthreads();                    // the previous pass is done with the LDS
-        flat_stream_pass<T, NQG, KP, DFULL, EMIT>(X, N, d, Q, B, q0, partial, o, smem);
+        flat_stream_pass<T, NQG, KP, DFULL, EMIT, NWV>(X, N, d, Q, B, q0, partial, o, smem);
     }
 }
 

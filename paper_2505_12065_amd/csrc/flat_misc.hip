@@ -10,6 +10,10 @@ size_t stream_lds_bytes(int nqg, int steps, int waves, int kp) {
     return q > m ? q : m;
 }
 
+int stream_waves(int nqg, int steps, int kp) {
+    return kp != 16 && stream_lds_bytes(nqg, steps, STREAM_THREADS / WAVE, kp) > LDS_MAX / 2 ? 16 : 8;
+}
+
 size_t f32_lds_bytes(int d, int waves, int kp) {
     size_t q = (size_t)8 * d * 4;
     size_t m = (size_t)waves * 8 * kp * sizeof(Cand);

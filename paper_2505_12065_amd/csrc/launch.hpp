@@ -11,6 +11,10 @@ namespace ann {
 
 constexpr size_t LDS_MAX = 160 * 1024;   // LDS of one gfx950 compute unit
 constexpr int STREAM_THREADS = 512;
+// Wavefronts of a flat_stream_kernel workgroup: 8, or 16 when the queries' LDS leaves room for one
+// workgroup per compute unit only (the corpus loads in flight are what keeps HBM busy); lists
+// of 16 need too many registers for that.
+int stream_waves(int nqg, int steps, int kp);
 
 // A kernel that needs more than 64 KB of dynamic LDS has to be told so; `granted` holds
 // the largest size already granted to that kernel.
