@@ -74,14 +74,17 @@ const char *ann_last_error(void);
  * "vLLM_ENN" configuration of Section 4.1 / Appendix B.3).
  *
  *   corpus  device, [N, d] of `dtype`      N >= 1, N < 2^31
- *   queries device, [B, d] of `dtype`      B >= 1
+ *   queries device, [B, d] of `dtype`      B >= 0 (an empty batch returns ANN_OK at once, here and
+ *                                          in every other search entry point)
  *   k       1 <= k <= min(N, ANN_K_MAX)
  *   ids     device, [B, k] int32  (written)
  *   scores  device, [B, k] float  (written)
  *
  * Every corpus row is scored against every query; the score matrix is never
- * materialised.  Uses the library workspace of the current device
- * (B * P * k * 8 bytes, P = number of corpus slabs, at most 2048).
+ * materialised.  Uses the library workspace of the current device: per query P
+ * lists of 4 or 16 (score, id) pairs (P = number of corpus slabs, at most 2048) and,
+ * for k > 4 on corpora of 128 Ki rows or more, a candidate array of 4096 pairs;
+ * ann_flat_workspace_bytes gives the exact size.
  */
 int ann_flat_search_typed(const void *corpus, int64_t N, int32_t d, int32_t dtype,
                           const void *queries, int32_t B, int32_t k,

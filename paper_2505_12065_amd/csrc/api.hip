@@ -434,6 +434,7 @@ int ann_timing_read(int32_t kernel, int32_t *launches, double *total_ms) {
 
 int ann_priority_order(const int32_t *R, const double *W, const int32_t *C, const double *Wcur, int32_t n, int32_t G,
                        int32_t *level, int32_t *order, void *stream) {
+    if (n == 0) return ANN_OK;
     if (!R || !W || !C || !Wcur || !level || !order) return fail(ANN_ERR_INVALID, "null pointer argument");
     if (n < 1 || n > ANN_REQUESTS_MAX) return fail(ANN_ERR_INVALID, "n = %d out of range [1, %d]", n, ANN_REQUESTS_MAX);
     if (G < 1 || G > 1024) return fail(ANN_ERR_INVALID, "G = %d out of range [1, 1024]", G);
@@ -483,6 +484,7 @@ int ann_release_workspace(void) {
 
 int ann_flat_search_typed(const void *corpus, int64_t N, int32_t d, int32_t dtype, const void *queries,
                           int32_t B, int32_t k, int32_t *ids, float *scores, void *stream) {
+    if (B == 0) return ANN_OK;                            // an empty batch: nothing to do
     if (int rc = check_common(corpus, N, d, dtype, queries, B, k, ids, scores)) return rc;
     if (k > ANN_K_MAX) return fail(ANN_ERR_INVALID, "k = %d exceeds ANN_K_MAX = %d", k, ANN_K_MAX);
     std::lock_guard<std::mutex> lock(g_mu);
@@ -526,6 +528,7 @@ int ann_graph_search_nonstall_typed(const void *corpus, int64_t N, int32_t d, in
                                     const int32_t *entries, float tau, int32_t window,
                                     const int32_t *engine_ready, int32_t *ids, float *scores, int32_t *stats,
                                     float *ema, void *stream) {
+    if (B == 0) return ANN_OK;                            // an empty batch: nothing to do
     GraphLds L;
     if (int rc = check_graph(corpus, N, d, dtype, graph, R, entries ? 0 : entry, queries, B, k, ef, ids, scores, &L))
         return rc;
@@ -589,6 +592,7 @@ static int graph_search_any(const void *corpus, int64_t N, int32_t d, int32_t dt
 int ann_graph_search_typed(const void *corpus, int64_t N, int32_t d, int32_t dtype, const int32_t *graph,
                            int32_t R, int32_t entry, const void *queries, int32_t B, int32_t k, int32_t ef,
                            int32_t *ids, float *scores, void *stream) {
+    if (B == 0) return ANN_OK;                            // an empty batch: nothing to do
     GraphLds L;
     if (int rc = check_graph(corpus, N, d, dtype, graph, R, entry, queries, B, k, ef, ids, scores, &L)) return rc;
     return graph_search_any(corpus, N, d, dtype, graph, R, entry, nullptr, queries, B, k, ef, ids, scores, L,
@@ -598,6 +602,7 @@ int ann_graph_search_typed(const void *corpus, int64_t N, int32_t d, int32_t dty
 int ann_graph_search_entries_typed(const void *corpus, int64_t N, int32_t d, int32_t dtype, const int32_t *graph,
                                    int32_t R, const int32_t *entries, const void *queries, int32_t B, int32_t k,
                                    int32_t ef, int32_t *ids, float *scores, void *stream) {
+    if (B == 0) return ANN_OK;                            // an empty batch: nothing to do
     if (!entries) return fail(ANN_ERR_INVALID, "null entries pointer");
     if (reinterpret_cast<uintptr_t>(entries) & 3) return fail(ANN_ERR_ALIGNMENT, "entries must be 4-byte aligned");
     GraphLds L;
@@ -607,6 +612,7 @@ int ann_graph_search_entries_typed(const void *corpus, int64_t N, int32_t d, int
 }
 
 int ann_gather_ids(const int32_t *table, int64_t M, const int32_t *idx, int64_t n, int32_t *out, void *stream) {
+    if (n == 0) return ANN_OK;
     if (!table || !idx || !out) return fail(ANN_ERR_INVALID, "null pointer argument");
     if (M < 1 || n < 1) return fail(ANN_ERR_INVALID, "M = %lld, n = %lld out of range", (long long)M, (long long)n);
     if ((reinterpret_cast<uintptr_t>(table) | reinterpret_cast<uintptr_t>(idx) | reinterpret_cast<uintptr_t>(out)) & 3)

@@ -58,7 +58,8 @@ def test_argument_errors_are_reported_without_a_device():
     assert flat(lib, scores=None) == E
     assert flat(lib, N=0) == E
     assert flat(lib, N=2 ** 31) == E
-    assert flat(lib, B=0) == E
+    assert flat(lib, B=0) == 0                      # an empty batch is a no-op, not an error
+    assert flat(lib, B=-1) == E
     assert flat(lib, k=0) == E
     assert flat(lib, k=101) == E                      # k > N
     assert flat(lib, N=1000, k=binding.ANN_K_MAX + 1) == E

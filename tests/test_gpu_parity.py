@@ -190,6 +190,31 @@ def test_error_codes_on_device():
     ann.ann_unregister_corpus(x)
 
 
+def test_empty_batches_are_no_ops():
+    """B = 0 (and n = 0 for the helpers) returns at once with success, launches nothing and
+    touches nothing, whatever the other arguments are."""
+    x = torch.zeros(100, 64, dtype=torch.float16, device=DEV)
+    g = torch.zeros(100, 4, dtype=torch.int32, device=DEV)
+    q0 = torch.zeros(0, 64, dtype=torch.float16, device=DEV)
+    ann.ann_timing_enable(True)
+    ids, sc = ann.ann_flat_search_typed(x, q0, 3)
+    assert ids.shape == (0, 3) and sc.shape == (0, 3)
+    ids, sc = ann.ann_graph_search_typed(x, g, 0, q0, 3, 8)
+    assert ids.shape == (0, 3)
+    e0 = torch.zeros(0, dtype=torch.int32, device=DEV)
+    ids, sc = ann.ann_graph_search_entries_typed(x, g, e0, q0, 3, 8)
+    assert ids.shape == (0, 3)
+    out = ann.ann_graph_search_nonstall_typed(x, g, 0, q0, 3, 8)
+    assert out[0].shape == (0, 3) and out[2].shape == (0, 3) and out[3].shape == (0,)
+    assert ann.ann_gather_ids(torch.arange(5, dtype=torch.int32, device=DEV), e0).shape == (0,)
+    torch.cuda.synchronize()
+    for code in (ann.binding.KERNEL_FLAT_STREAM, ann.binding.KERNEL_FLAT_WIDE, ann.binding.KERNEL_GRAPH):
+        assert ann.ann_timing_read(code)[0] == 0
+    ann.ann_timing_enable(False)
+    lib = ann.binding.lib()
+    assert lib.ann_flat_search_typed(None, 0, 0, 0, None, 0, 0, None, None, None) == 0      # nothing is looked at
+
+
 # ------------------------------------------------------------------ configuration 1 (flat, fp16, d = 768)
 
 @pytest.fixture(scope="module")
