@@ -241,6 +241,13 @@ def main() -> int:
                                   "hbm_frac": flat_bytes / ms / 1e6 / HBM_PEAK_GBS,
                                   "mfma_TFLOPs": 2.0 * B * N * d / ms / 1e9,
                                   "mfma_frac": 2.0 * B * N * d / ms / 1e9 / MFMA_F16_PEAK_TFLOPS})
+        # the paper retrieves k = 5 (Appendix B.3); batches between the configuration's sizes too
+        sweep["flat_other"] = []
+        for B, kk in ((1, 5), (16, 5), (128, 3), (128, 5), (512, 5), (512, 16)):
+            qb = q_all[:B].contiguous()
+            ms = timed(lambda: ann.ann_flat_search_typed(x, qb, kk))
+            sweep["flat_other"].append({"B": B, "k": kk, "ms": ms, "qps": B / ms * 1e3, "hbm_GBs": flat_bytes / ms / 1e6,
+                                        "mfma_TFLOPs": 2.0 * B * N * d / ms / 1e9})
         exact = out[B_LARGE][0].cpu().numpy()
 
         def recall3(ids, ref):
