@@ -278,9 +278,6 @@ int flat_search_emit(const FlatPlan &pl, const void *X, int64_t N, int d, int dt
     float *thr = reinterpret_cast<float *>(ws + pl.thr_ofs);
     int *cnt = reinterpret_cast<int *>(ws + pl.cnt_ofs);
     Cand *cand = reinterpret_cast<Cand *>(ws + pl.cand_ofs);
-    const size_t cnt_words = ((size_t)B + 3) & ~(size_t)3;
-    if (int rc = check_launch("zero_words_kernel", launch_zero_words(reinterpret_cast<uint32_t *>(cnt), cnt_words, stream)))
-        return rc;
     // sampling pass: every 64th row, the best 4 per slab and query
     if (pl.wide_ntg > 0) {
         hipError_t e = launch_flat_wide(dtype, 1, X, N, d, Q, B, sample, pl.sample_P, pl.wide_ntg, 0, nullptr, pl.sample_P,
@@ -291,7 +288,7 @@ int flat_search_emit(const FlatPlan &pl, const void *X, int64_t N, int d, int dt
         o.row_stride = SAMPLE_STRIDE;
         if (int rc = flat_stream_all(4, pl.nqg_max, pl.sample_P, X, N, d, dtype, Q, B, sample, o, false, stream)) return rc;
     }
-    if (int rc = check_launch("flat_sample_kth_kernel", launch_flat_sample_kth(sample, pl.sample_P, B, k, thr, nullptr, 0, 0, stream)))
+    if (int rc = check_launch("flat_sample_kth_kernel", launch_flat_sample_kth(sample, pl.sample_P, B, k, thr, nullptr, 0, 0, cnt, stream)))
         return rc;
     // main pass: candidates
     if (pl.wide_ntg > 0) {
@@ -308,17 +305,13 @@ int flat_search_emit(const FlatPlan &pl, const void *X, int64_t N, int d, int dt
         o.cap = pl.emit_cap;
         if (int rc = flat_stream_all(0, pl.nqg_max, pl.P, X, N, d, dtype, Q, B, cand, o, true, stream)) return rc;
     }
-    if (int rc = check_launch("flat_merge_kernel (candidates)",
-                              launch_flat_merge(pl.kp, cand, pl.emit_cap / pl.kp, B, k, ids, scores, cnt, pl.emit_cap, 0,
-                                                stream)))
-        return rc;
-    // repair pass: every launch returns at once unless a candidate array of its queries overflowed
+    // repair pass: returns at once unless a candidate array overflowed
     StreamOpts o;
     o.need = cnt;
     o.need_above = pl.emit_cap;
     if (int rc = flat_stream_all(pl.kp, pl.st_nqg_max, pl.st_P, X, N, d, dtype, Q, B, partial, o, false, stream)) return rc;
-    return check_launch("flat_merge_kernel (repair)",
-                        launch_flat_merge(pl.kp, partial, pl.st_P, B, k, ids, scores, cnt, pl.emit_cap, 1, stream));
+    return check_launch("flat_merge_kernel",
+                        launch_flat_merge(pl.kp, partial, pl.st_P, B, k, ids, scores, cnt, cand, pl.emit_cap, stream));
 }
 
 int flat_search_run(const FlatPlan &pl, const void *X, int64_t N, int d, int dtype, const void *Q, int B, int k,
@@ -341,7 +334,8 @@ int flat_search_run(const FlatPlan &pl, const void *X, int64_t N, int d, int dty
             hipError_t e = launch_flat_wide(dtype, 1, X, skip ? (int64_t)pl.sample_skip * 256 : N, d, Q, B, sample, pl.sample_P,
                                             pl.wide_ntg, 0, nullptr, pl.sample_P, 0, nullptr, skip ? 1 : SAMPLE_STRIDE, stream);
             if (int rc = check_launch("flat_wide_kernel (sample)", e)) return rc;
-            e = launch_flat_sample_kth(sample, pl.sample_P, B, k, thr, skip ? partial : nullptr, pl.pstride, pl.P, stream);
+            e = launch_flat_sample_kth(sample, pl.sample_P, B, k, thr, skip ? partial : nullptr, pl.pstride, pl.P, nullptr,
+                                       stream);
             if (int rc = check_launch("flat_sample_kth_kernel", e)) return rc;
             thr0 = thr;
         }
@@ -355,7 +349,7 @@ int flat_search_run(const FlatPlan &pl, const void *X, int64_t N, int d, int dty
     } else {
         if (int rc = flat_stream_all(pl.kp, pl.nqg_max, pl.P, X, N, d, dtype, Q, B, partial, StreamOpts(), true, stream)) return rc;
     }
-    return check_launch("flat_merge_kernel", launch_flat_merge(pl.kp, partial, pl.pstride, B, k, ids, scores, nullptr, 0, 0, stream));
+    return check_launch("flat_merge_kernel", launch_flat_merge(pl.kp, partial, pl.pstride, B, k, ids, scores, nullptr, nullptr, 0, stream));
 }
 
 }  // namespace

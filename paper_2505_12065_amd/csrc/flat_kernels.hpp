@@ -278,24 +278,26 @@ __device__ __forceinline__ void gather_best(const Cand *__restrict__ in, int tot
     }
 }
 
-// count == null: query q's input is its P lists of KP.  count given, repair == 0: the input is the
-// candidate array of count[q] entries at partial[q * P * KP ..) and nothing is written when it
-// overflowed (count[q] > P * KP).  count given, repair != 0: P lists as usual, but only the
-// queries whose candidate array overflowed are written.
+// count == null: query q's input is its P lists of KP at partial[q * P * KP ..).  count given: the
+// input is the candidate array of count[q] entries at cand[q * cap ..), unless it overflowed
+// (count[q] > cap): then the P lists, which the repair pass has filled for exactly those queries.
 template <int KP>
 __global__ __launch_bounds__(256) void flat_merge_kernel(const Cand *__restrict__ partial, int P, int k,
                                                          int32_t *__restrict__ ids, float *__restrict__ scores,
-                                                         const int *__restrict__ count, int cap, int repair) {
+                                                         const int *__restrict__ count, const Cand *__restrict__ cand,
+                                                         int cap) {
     __shared__ Cand wl[4 * KP];
     const int q = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int nwaves = blockDim.x >> 6;
     int total = P * KP;
-    if (count) {
-        const int n = count[q];
-        if (repair ? n <= cap : n > cap) return;          // uniform for the workgroup
-        if (!repair) total = n;
-    }
     const Cand *in = partial + (size_t)q * P * KP;
+    if (count) {
+        const int n = count[q];                           // uniform for the workgroup
+        if (n <= cap) {
+            total = n;
+            in = cand + (size_t)q * cap;
+        }
+    }
     TopList<KP> best;
     best.init();
     gather_best<KP>(in, total, tid, blockDim.x, best);
@@ -328,11 +330,11 @@ __global__ __launch_bounds__(256) void flat_merge_kernel(const Cand *__restrict_
 // -inf when the sample holds fewer than k rows.  The lists come from disjoint rows, so this is the
 // k-th best of a subset of the corpus: a lower bound of the final k-th best score.  With dst, the
 // sample's KS best are also kept, as slab pslot of the query's lists dst[(q pstride + pslot) KS ..)
-// (for a sample whose rows the main pass then skips).
+// (for a sample whose rows the main pass then skips).  With count, count[q] is set to 0.
 template <int KS, int KO>
 __global__ __launch_bounds__(64) void flat_sample_kth_kernel(const Cand *__restrict__ src, int Ps, int k,
                                                              float *__restrict__ thr, Cand *__restrict__ dst,
-                                                             int pstride, int pslot) {
+                                                             int pstride, int pslot, int *__restrict__ count) {
     const int q = blockIdx.x, lane = threadIdx.x;
     TopList<KO> best;
     best.init();
@@ -345,6 +347,7 @@ __global__ __launch_bounds__(64) void flat_sample_kth_kernel(const Cand *__restr
         for (int j = 0; j < KO; ++j)
             if (j == k - 1 && top.id[j] != EMPTY_ID) t = top.s[j];
         thr[q] = t;
+        if (count) count[q] = 0;                      // the query's candidate array starts empty
         if (dst) {
 #pragma unroll
             for (int j = 0; j < KS; ++j) dst[((size_t)q * pstride + pslot) * KS + j] = Cand{top.s[j], top.id[j]};

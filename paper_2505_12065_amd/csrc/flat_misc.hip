@@ -38,23 +38,24 @@ hipError_t launch_flat_f32(int kp, const float *X, int64_t N, int d, const float
 }
 
 hipError_t launch_flat_merge(int kp, const Cand *partial, int P, int B, int k, int32_t *ids, float *scores,
-                             const int *count, int cap, int repair, hipStream_t stream) {
-    const int threads = P * kp <= 512 ? 64 : 256;       // one batch of loads per lane where possible
+                             const int *count, const Cand *cand, int cap, hipStream_t stream) {
+    const int threads = !count && P * kp <= 512 ? 64 : 256;       // one batch of loads per lane where possible
     if (kp == 4)
         hipLaunchKernelGGL((flat_merge_kernel<4>), dim3(B), dim3(threads), 0, stream, partial, P, k, ids, scores, count,
-                           cap, repair);
+                           cand, cap);
     else
         hipLaunchKernelGGL((flat_merge_kernel<16>), dim3(B), dim3(threads), 0, stream, partial, P, k, ids, scores, count,
-                           cap, repair);
+                           cand, cap);
     return hipGetLastError();
 }
 
 hipError_t launch_flat_sample_kth(const Cand *src, int Ps, int B, int k, float *thr, Cand *dst, int pstride, int pslot,
-                                  hipStream_t stream) {
+                                  int *count, hipStream_t stream) {
     if (k <= 4)   // short lists: a fraction of the selection work
-        hipLaunchKernelGGL((flat_sample_kth_kernel<4, 4>), dim3(B), dim3(64), 0, stream, src, Ps, k, thr, dst, pstride, pslot);
+        hipLaunchKernelGGL((flat_sample_kth_kernel<4, 4>), dim3(B), dim3(64), 0, stream, src, Ps, k, thr, dst, pstride, pslot, count);
     else
-        hipLaunchKernelGGL((flat_sample_kth_kernel<4, 16>), dim3(B), dim3(64), 0, stream, src, Ps, k, thr, dst, pstride, pslot);
+        hipLaunchKernelGGL((flat_sample_kth_kernel<4, 16>), dim3(B), dim3(64), 0, stream, src, Ps, k, thr, dst, pstride, pslot,
+                           count);
     return hipGetLastError();
 }
 

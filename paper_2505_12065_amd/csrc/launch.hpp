@@ -57,16 +57,15 @@ hipError_t launch_flat_wide(int dtype, int mode, const void *X, int64_t N, int d
                             Cand *partial, int P, int NTG, int64_t tile_begin, const float *thr_init, int pstride,
                             int pslot0, int *emit_count, int row_stride, hipStream_t stream);
 // thr[q] = k-th best score among the Ps sampled lists of 4 of query q (-inf if fewer), k <= 16;
-// with dst, the 4 best of the sample also become slab pslot of dst[B, pstride, 4]
+// with dst, the 4 best of the sample also become slab pslot of dst[B, pstride, 4]; with count, count[q] = 0
 hipError_t launch_flat_sample_kth(const Cand *src, int Ps, int B, int k, float *thr, Cand *dst, int pstride, int pslot,
-                                  hipStream_t stream);
+                                  int *count, hipStream_t stream);
 hipError_t launch_flat_f32(int kp, const float *X, int64_t N, int d, const float *Q, int B, Cand *partial, int P,
                            hipStream_t stream);
-// count == null: merge the P lists of every query.  count given, repair == 0: query q's input is
-// its candidate array of count[q] entries (capacity cap = P kp), skipped when it overflowed.
-// count given, repair != 0: merge the P lists, but only of the queries whose array overflowed.
+// count == null: merge the P lists of every query.  count given: query q's input is its candidate
+// array cand[q cap ..) of count[q] entries, or, when that overflowed, its P lists (repair pass).
 hipError_t launch_flat_merge(int kp, const Cand *partial, int P, int B, int k, int32_t *ids, float *scores,
-                             const int *count, int cap, int repair, hipStream_t stream);
+                             const int *count, const Cand *cand, int cap, hipStream_t stream);
 
 constexpr int GRAPH_EF_DOUBLE = 2048;    // candidate lists up to this length are double-buffered in LDS
 // cus workgroups of 8 waves, each wave iters x 8 MFMA 32x32x16 fp16 (32768 flop each) on register operands
