@@ -20,6 +20,11 @@
  *     synchronised `stream`.  No entry point synchronises the device except
  *     when the library-owned workspace has to grow (first call, or a larger
  *     B*k than any call before on this device).
+ *   - One workspace per device: calls that use it (the flat search, the graph
+ *     search with ef > 2048, the non-stall graph search) are safe one after the
+ *     other on one stream, or on several streams if the caller orders them; two
+ *     of them running at once on one device race on the workspace.  The plain
+ *     graph search with ef <= 2048 uses no workspace and may overlap anything.
  *   - corpus  [N, d] row-major, contiguous, 16-byte aligned base.
  *     queries [B, d] row-major, same element type as the corpus.
  *     graph   [N, R] row-major int32; a slot < 0 or >= N is empty and skipped.
