@@ -38,15 +38,29 @@ constexpr int ROWS_PER_PASS = GRAPH_THREADS / LANES_PER_ROW;   // 32 neighbours 
 constexpr uint32_t EXPANDED = 0x80000000u;
 constexpr int RMAX_LDS = 256;                                  // row stride of the read-ahead buffers (>= R)
 
-// number of entries of the ordered list (s[0..len), id[0..len)) that precede (v, vid)
-__device__ __forceinline__ int list_lower_bound(const float *s, const uint32_t *id, int len, float v, int vid) {
-    int lo = 0, hi = len;
-    while (lo < hi) {
-        const int mid = (lo + hi) >> 1;
-        if (precedes(s[mid], (int)(id[mid] & ~EXPANDED), v, vid)) lo = mid + 1;
-        else hi = mid;
+// Number of entries of the ordered list (s[0..len), id[0..len)) that precede (v, vid), found by
+// the 8 lanes of a row group together: every round each lane probes one entry, which
+// cuts the range to a ninth, so a list of 512 entries takes 3 LDS round trips and a last one over
+// at most 8 neighbouring entries, where a binary search takes 9 or 10.  All lanes of the group must
+// call it with the same arguments; all get the result.
+__device__ __forceinline__ int group_lower_bound(const float *s, const uint32_t *id, int len, float v, int vid,
+                                                 int sub, int lane) {
+    const int gshift = lane & ~(LANES_PER_ROW - 1);
+    int lo = 0, hi = len;                                 // the answer lies in [lo, hi]
+    while (hi - lo > LANES_PER_ROW) {
+        const int w = hi - lo;                            // >= 9: the probes are distinct and inside (lo, hi)
+        const int m = lo + ((sub + 1) * w) / (LANES_PER_ROW + 1);
+        const bool pr = precedes(s[m], (int)(id[m] & ~EXPANDED), v, vid);
+        const int c = __builtin_popcount((unsigned)(__builtin_amdgcn_ballot_w64(pr) >> gshift) & 0xffu);
+        // entries are ordered, so exactly the first c probes precede (v, vid)
+        const int nlo = c > 0 ? lo + (c * w) / (LANES_PER_ROW + 1) + 1 : lo;
+        const int nhi = c < LANES_PER_ROW ? lo + ((c + 1) * w) / (LANES_PER_ROW + 1) : hi;
+        lo = nlo;
+        hi = nhi;
     }
-    return lo;
+    const int m = lo + sub;
+    const bool pr = m < hi && precedes(s[m], (int)(id[m] & ~EXPANDED), v, vid);
+    return lo + __builtin_popcount((unsigned)(__builtin_amdgcn_ballot_w64(pr) >> gshift) & 0xffu);
 }
 
 // precedes() as 0 / 1 without short-circuit evaluation (no branches in unrolled loops)
@@ -196,9 +210,19 @@ __global__ __launch_bounds__(GRAPH_THREADS) void graph_search_kernel(
                 if (fresh && ((seen >> (v & 31)) & 1u)) fresh = 0;
                 if (fresh && sub == 0) atomicOr(&seen_bits[v >> 5], 1u << (v & 31));
             }
+            // Where would it go?  pos = entries of the list that precede it, or -1 when it does not
+            // make it into the best ef or is in the list already (the cache may have forgotten it).
+            // Found here, by the row group that scored it, while the list is at rest; ids named by
+            // two slots are sorted out after the barrier.
+            int pos = -1;
+            if (fresh && s == s) {                         // a NaN score is never listed
+                pos = group_lower_bound(ls(cur), li(cur), len, s, v, sub, lane);
+                if (pos >= ef || (pos < len && (int)(li(cur)[pos] & ~EXPANDED) == v)) pos = -1;
+            }
             if (sub == 0) {
                 cs[slot] = s;
                 ci[slot] = fresh ? v : -1;
+                cpos[slot] = pos;
                 if (NS) co[slot] = (unsigned)v < (unsigned)N ? v : -1;
             }
         }
@@ -209,16 +233,13 @@ __global__ __launch_bounds__(GRAPH_THREADS) void graph_search_kernel(
         }
         __syncthreads();
 
-        // where would each scored neighbour go?  cpos = entries of the list that precede it,
-        // or -1 when it is a duplicate or does not make it into the best ef
+        // an id named by an earlier slot as well is taken once: cpos = -1 for the later slot
         // (the loops over the scored neighbours read them with wide, unconditional LDS loads and
         // use branch-free arithmetic: a short-circuit "j < i && ci[j] == v" compiles into one
         // predicated load-and-wait per j, i.e. 32 LDS round trips in a row)
         for (int i = tid; i < RP; i += GRAPH_THREADS) {
             const int v = ci[i];
-            int pos = -1;
             if (v >= 0) {
-                const float s = cs[i];
                 int dup = 0;
                 if constexpr (RPT == 32) {
                     int4 c4[8];
@@ -234,12 +255,8 @@ __global__ __launch_bounds__(GRAPH_THREADS) void graph_search_kernel(
                 } else {
                     for (int j = 0; j < i; ++j) dup |= (int)(ci[j] == v);
                 }
-                if (!dup && s == s) {                      // a NaN score is never listed
-                    pos = list_lower_bound(ls(cur), li(cur), len, s, v);
-                    if (pos >= ef || (pos < len && (int)(li(cur)[pos] & ~EXPANDED) == v)) pos = -1;
-                }
+                if (dup) cpos[i] = -1;
             }
-            cpos[i] = pos;
         }
         // The moving average is kept by the last wave alone, beside the list work of the
         // others (for short rows and lists that is all on wave 0), and handed over in LDS.
