@@ -337,7 +337,6 @@ __global__ __launch_bounds__(GRAPH_THREADS) void graph_search_kernel(
         // number of new entries that precede it.  Lists of up to 2048 entries are double-buffered
         // (merged into the other buffer); longer ones have one buffer and are merged in place.
         const bool inplace = L.ls1 == L.ls0;
-        const int nxt = inplace ? cur : cur ^ 1;
         int n_new = 0;
         unsigned jmin = 0xffffffffu;                      // lowest position a new entry takes
         int4 p4[RPT == 32 ? 8 : 1];                       // R <= 32: every thread holds the 32 positions
@@ -355,6 +354,8 @@ __global__ __launch_bounds__(GRAPH_THREADS) void graph_search_kernel(
                 jmin = min(jmin, (unsigned)cpos[i]);
             }
         }
+        // nothing to insert (most expansions once the list has settled): the list stays where it is
+        const int nxt = inplace || n_new == 0 ? cur : cur ^ 1;
         // number of new entries at or before list position j (a position is in 0 .. j exactly
         // when, as an unsigned number, it is <= j; -1 is not)
         auto shift_of = [&](int j) {
@@ -373,7 +374,7 @@ __global__ __launch_bounds__(GRAPH_THREADS) void graph_search_kernel(
         int new_at = -1;
         float new_s = 0.f;
         int new_v = 0;
-        if (tid < RP) {
+        if (n_new != 0 && tid < RP) {
             const int pos = cpos[tid];
             if (pos >= 0) {
                 new_s = cs[tid];
@@ -400,10 +401,10 @@ __global__ __launch_bounds__(GRAPH_THREADS) void graph_search_kernel(
                 if (pos + r < ef) new_at = pos + r;
             }
         }
-        if (!inplace) {
+        if (!inplace && n_new != 0) {
             if (new_at >= 0) { ls(nxt)[new_at] = new_s; li(nxt)[new_at] = (uint32_t)new_v; }
             for (int j = tid; j < len; j += GRAPH_THREADS) {
-                const int shift = n_new ? shift_of(j) : 0;
+                const int shift = shift_of(j);
                 if (j + shift < ef) { ls(nxt)[j + shift] = ls(cur)[j]; li(nxt)[j + shift] = li(cur)[j]; }
             }
         } else if (n_new) {
@@ -435,14 +436,31 @@ __global__ __launch_bounds__(GRAPH_THREADS) void graph_search_kernel(
         }
         len = min(ef, len + n_new);
         cur = nxt;
-        __syncthreads();
+        if (NS || n_new != 0) __syncthreads();            // an untouched list needs no barrier (n_new is uniform)
 
         // Best and second-best unexpanded entries of the new list: one ballot per 64 entries.
         // Everything before the entry just expanded was expanded already, and the merge has not
         // touched the list before its lowest insertion, so the scan starts at the lower of the
         // two and goes on, 256 entries per round, only until two are found (one round as a rule,
         // whatever the length of the list).
-        {
+        if (len <= GRAPH_THREADS) {
+            // short list: every wave looks at all of it itself (up to four entries per lane, read
+            // together), so no exchange between the waves and no second barrier is needed
+            p = -1;
+            p2 = -1;
+            uint32_t e4[GRAPH_WAVES];
+#pragma unroll
+            for (int w = 0; w < GRAPH_WAVES; ++w) e4[w] = w * 64 < len ? li(cur)[min(w * 64 + lane, len - 1)] : EXPANDED;
+#pragma unroll
+            for (int w = 0; w < GRAPH_WAVES; ++w) {
+                uint64_t mw = __builtin_amdgcn_ballot_w64(w * 64 + lane < len && !(e4[w] & EXPANDED));
+                while (mw != 0 && p2 < 0) {
+                    const int jj = w * 64 + __builtin_ctzll(mw);
+                    mw &= mw - 1;
+                    if (p < 0) p = jj; else p2 = jj;
+                }
+            }
+        } else {
             const unsigned first = min((unsigned)p, jmin);
             p = -1;
             p2 = -1;
