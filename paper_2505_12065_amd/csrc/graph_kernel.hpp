@@ -111,6 +111,7 @@ __global__ __launch_bounds__(GRAPH_THREADS) void graph_search_kernel(
     }
     const int nch = d * T::bytes / 16;                    // 16-byte chunks per row
     const int RP = RPT ? RPT : (int)L.rp;
+    constexpr bool ROWDUP = !NS && RPT == 32;             // duplicate ids of a row are settled while scoring
     const uint32_t cache_shift = 32u - L.cache_bits;
     uint32_t *seen_bits = NS ? ns.visited + (size_t)b * ns.words : nullptr;   // zero on entry
 
@@ -189,6 +190,21 @@ __global__ __launch_bounds__(GRAPH_THREADS) void graph_search_kernel(
             const int slot = base + grp;
             int v = -1;
             if (slot < R) v = have >= 0 ? adj[have * RMAX_LDS + slot] : graph[(size_t)node * R + slot];
+            if constexpr (ROWDUP) {
+                // An id that an earlier slot of the row names as well is left to that slot.  The 8
+                // lanes of the group look at 4 slots each (read together with v: no extra round
+                // trip), which settles duplicates here and saves a pass and a barrier after scoring.
+                int dup = 0;
+#pragma unroll
+                for (int t = 0; t < 4; ++t) {
+                    const int idx = sub * 4 + t;
+                    int o = -1;
+                    if (idx < R && idx < slot) o = have >= 0 ? adj[have * RMAX_LDS + idx] : graph[(size_t)node * R + idx];
+                    dup |= (int)(idx < slot) & (int)(o == v);
+                }
+                const unsigned grp_bits = (unsigned)(__builtin_amdgcn_ballot_w64(dup != 0) >> (lane & ~(LANES_PER_ROW - 1))) & 0xffu;
+                if (grp_bits != 0) v = -1;
+            }
             int fresh = 0;
             if ((unsigned)v < (unsigned)N) {
                 if (sub == 0) {
@@ -237,6 +253,7 @@ __global__ __launch_bounds__(GRAPH_THREADS) void graph_search_kernel(
         // (the loops over the scored neighbours read them with wide, unconditional LDS loads and
         // use branch-free arithmetic: a short-circuit "j < i && ci[j] == v" compiles into one
         // predicated load-and-wait per j, i.e. 32 LDS round trips in a row)
+        if constexpr (!ROWDUP)
         for (int i = tid; i < RP; i += GRAPH_THREADS) {
             const int v = ci[i];
             if (v >= 0) {
@@ -331,7 +348,7 @@ __global__ __launch_bounds__(GRAPH_THREADS) void graph_search_kernel(
             }
             if (lane == 0) ema_s[0] = ema;
         }
-        __syncthreads();
+        if constexpr (!ROWDUP) __syncthreads();
 
         // merge: new entries go to pos + (rank among the new entries), old entry j moves up by the
         // number of new entries that precede it.  Lists of up to 2048 entries are double-buffered
