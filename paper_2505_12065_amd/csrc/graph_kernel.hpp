@@ -387,34 +387,39 @@ __global__ __launch_bounds__(GRAPH_THREADS) void graph_search_kernel(
             }
             return shift;
         };
-        // the new entry of this thread (slot tid, RP <= GRAPH_THREADS): final position or -1
+        // the new entry of this thread: final position or -1
         int new_at = -1;
         float new_s = 0.f;
         int new_v = 0;
-        if (n_new != 0 && tid < RP) {
+        if constexpr (RPT == 32) {
+            // row group g places scored neighbour g: each of its 8 lanes compares it with 4 of the
+            // 32 neighbours (one wide read each of scores, ids, positions), the counts are added
+            // up by shuffles, the group's first lane writes the entry
+            if (n_new != 0) {
+                const int pos = cpos[grp];
+                if (pos >= 0) {                            // the same for the 8 lanes of the group
+                    new_s = cs[grp];
+                    new_v = ci[grp];
+                    const f4 sq = reinterpret_cast<const f4 *>(cs)[sub];
+                    const int4 cq = reinterpret_cast<const int4 *>(ci)[sub];
+                    const int4 pq = reinterpret_cast<const int4 *>(cpos)[sub];
+                    int r = ((int)(pq.x >= 0) & precedes01(sq[0], cq.x, new_s, new_v)) +
+                            ((int)(pq.y >= 0) & precedes01(sq[1], cq.y, new_s, new_v)) +
+                            ((int)(pq.z >= 0) & precedes01(sq[2], cq.z, new_s, new_v)) +
+                            ((int)(pq.w >= 0) & precedes01(sq[3], cq.w, new_s, new_v));
+                    r += __shfl_xor(r, 1);
+                    r += __shfl_xor(r, 2);
+                    r += __shfl_xor(r, 4);
+                    if (sub == 0 && pos + r < ef) new_at = pos + r;
+                }
+            }
+        } else if (n_new != 0 && tid < RP) {              // slot tid, RP <= GRAPH_THREADS
             const int pos = cpos[tid];
             if (pos >= 0) {
                 new_s = cs[tid];
                 new_v = ci[tid];
                 int r = 0;
-                if constexpr (RPT == 32) {
-                    f4 s4[8];
-                    int4 c4[8];
-#pragma unroll
-                    for (int u = 0; u < 8; ++u) {
-                        s4[u] = reinterpret_cast<const f4 *>(cs)[u];
-                        c4[u] = reinterpret_cast<const int4 *>(ci)[u];
-                    }
-#pragma unroll
-                    for (int u = 0; u < 8; ++u) {
-                        r += (int)(p4[u].x >= 0) & precedes01(s4[u][0], c4[u].x, new_s, new_v);
-                        r += (int)(p4[u].y >= 0) & precedes01(s4[u][1], c4[u].y, new_s, new_v);
-                        r += (int)(p4[u].z >= 0) & precedes01(s4[u][2], c4[u].z, new_s, new_v);
-                        r += (int)(p4[u].w >= 0) & precedes01(s4[u][3], c4[u].w, new_s, new_v);
-                    }
-                } else {
-                    for (int j = 0; j < RP; ++j) r += (int)(cpos[j] >= 0) & precedes01(cs[j], ci[j], new_s, new_v);
-                }
+                for (int j = 0; j < RP; ++j) r += (int)(cpos[j] >= 0) & precedes01(cs[j], ci[j], new_s, new_v);
                 if (pos + r < ef) new_at = pos + r;
             }
         }
