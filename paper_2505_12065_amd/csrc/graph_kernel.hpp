@@ -358,12 +358,17 @@ __global__ __launch_bounds__(GRAPH_THREADS) void graph_search_kernel(
         unsigned jmin = 0xffffffffu;                      // lowest position a new entry takes
         int4 p4[RPT == 32 ? 8 : 1];                       // R <= 32: every thread holds the 32 positions
         if constexpr (RPT == 32) {
+            // how many: one position per lane and a lane mask; the 32 positions themselves are
+            // only fetched when something is inserted, their minimum only where it is used
+            n_new = __builtin_popcount((uint32_t)__builtin_amdgcn_ballot_w64(cpos[lane & 31] >= 0));
+            if (n_new != 0) {
 #pragma unroll
-            for (int u = 0; u < 8; ++u) p4[u] = reinterpret_cast<const int4 *>(cpos)[u];
+                for (int u = 0; u < 8; ++u) p4[u] = reinterpret_cast<const int4 *>(cpos)[u];
+                if (inplace || len > GRAPH_THREADS) {
 #pragma unroll
-            for (int u = 0; u < 8; ++u) {
-                n_new += (int)(p4[u].x >= 0) + (int)(p4[u].y >= 0) + (int)(p4[u].z >= 0) + (int)(p4[u].w >= 0);
-                jmin = min(min(jmin, (unsigned)p4[u].x), min((unsigned)p4[u].y, min((unsigned)p4[u].z, (unsigned)p4[u].w)));
+                    for (int u = 0; u < 8; ++u)
+                        jmin = min(min(jmin, (unsigned)p4[u].x), min((unsigned)p4[u].y, min((unsigned)p4[u].z, (unsigned)p4[u].w)));
+                }
             }
         } else {
             for (int i = 0; i < RP; ++i) {
