@@ -68,6 +68,63 @@ __device__ __forceinline__ int precedes01(float s, int id, float s2, int id2) {
     return (int)(s > s2) | ((int)(s == s2) & (int)(id < id2));
 }
 
+// Sum over the 8 lanes of a row group, every lane gets it.  Three data-parallel-primitive moves
+// (swap with the neighbour, swap the pairs of a quad, mirror the group of 8) in place of three
+// trips through the LDS crossbar.  After the first two steps the four lanes of a quad hold the
+// same bits (a + b and b + a are the same number), so the mirror step adds the same two quad
+// sums in every lane: the result is bit for bit that of a butterfly over lanes ^1, ^2, ^4.
+template <int CTRL>
+__device__ __forceinline__ int dpp_move(int x) {
+    return __builtin_amdgcn_update_dpp(x, x, CTRL, 0xf, 0xf, false);
+}
+constexpr int DPP_SWAP1 = 0xB1;                           // quad_perm [1,0,3,2]
+constexpr int DPP_SWAP2 = 0x4E;                           // quad_perm [2,3,0,1]
+constexpr int DPP_HALF_MIRROR = 0x141;                    // lane i of each 8 <- lane 7 - i
+__device__ __forceinline__ float group_sum(float x) {
+    x += __int_as_float(dpp_move<DPP_SWAP1>(__float_as_int(x)));
+    x += __int_as_float(dpp_move<DPP_SWAP2>(__float_as_int(x)));
+    x += __int_as_float(dpp_move<DPP_HALF_MIRROR>(__float_as_int(x)));
+    return x;
+}
+__device__ __forceinline__ int group_sum(int x) {
+    x += dpp_move<DPP_SWAP1>(x);
+    x += dpp_move<DPP_SWAP2>(x);
+    x += dpp_move<DPP_HALF_MIRROR>(x);
+    return x;
+}
+
+// The same count for lists of up to 512 entries, in at most two LDS round trips.  First the 8
+// lanes probe the last entries of the 8 blocks of 64 (skipped for lists of up to 64), which
+// names the block the answer lies in; then every lane reads 8 neighbouring entries of that
+// block with wide loads and counts.  *listed is set when the block holds `vid` itself: the node
+// is in the list already (then it sits exactly at the returned position).  Reads may run up to
+// 63 entries past `len` (never past the end of LDS: the list buffers are not the last region);
+// what they return is masked out.
+__device__ __forceinline__ int group_lower_bound_512(const float *s, const uint32_t *id, int len, float v, int vid,
+                                                     int sub, int lane, bool *listed) {
+    const int gshift = lane & ~(LANES_PER_ROW - 1);
+    int blk = 0;
+    if (len > 64) {
+        const int m = 64 * sub + 63;
+        const bool pr = m < len && precedes(s[m], (int)(id[m] & ~EXPANDED), v, vid);
+        blk = __builtin_popcount((unsigned)(__builtin_amdgcn_ballot_w64(pr) >> gshift) & 0xffu);
+        if (blk == LANES_PER_ROW) { *listed = false; return 512; }
+    }
+    const int j0 = 64 * blk + 8 * sub;
+    const f4 sa = *reinterpret_cast<const f4 *>(s + j0), sb = *reinterpret_cast<const f4 *>(s + j0 + 4);
+    const int4 ia = *reinterpret_cast<const int4 *>(id + j0), ib = *reinterpret_cast<const int4 *>(id + j0 + 4);
+    int cnt = 0, same = 0;
+    auto one = [&](float es, int e, int j) {
+        const int eid = e & (int)~EXPANDED;
+        cnt += (int)(j < len) & precedes01(es, eid, v, vid);
+        same |= (int)(j < len) & (int)(eid == vid);
+    };
+    one(sa[0], ia.x, j0 + 0); one(sa[1], ia.y, j0 + 1); one(sa[2], ia.z, j0 + 2); one(sa[3], ia.w, j0 + 3);
+    one(sb[0], ib.x, j0 + 4); one(sb[1], ib.y, j0 + 5); one(sb[2], ib.z, j0 + 6); one(sb[3], ib.w, j0 + 7);
+    *listed = ((unsigned)(__builtin_amdgcn_ballot_w64(same != 0) >> gshift) & 0xffu) != 0;
+    return 64 * blk + group_sum(cnt);
+}
+
 // RPT: number of graph slots rounded up to 32 when it is known at compile time (32 for
 // R <= 32: the short loops over the scored neighbours are then fully unrolled and their
 // LDS reads issued together), 0 = taken from the layout at run time.
@@ -123,29 +180,67 @@ __global__ __launch_bounds__(GRAPH_THREADS) void graph_search_kernel(
     const int sub = lane & (LANES_PER_ROW - 1);           // lane's position inside its row group
     const int grp = wave * (WAVE / LANES_PER_ROW) + lane / LANES_PER_ROW;   // 0..31
 
+    // The lane's share of the first 128 chunks of the query (chunks sub, sub + 8, ...) stays in
+    // registers for the whole search: up to 1024 16-bit dimensions are scored without reading
+    // the query from LDS at all.
+    constexpr int BLK = 16 * LANES_PER_ROW;               // chunks per block of 16 loads per lane
+    u4 qr[16];
+#pragma unroll
+    for (int u = 0; u < 16; ++u) qr[u] = qs[min(sub + u * LANES_PER_ROW, nch - 1)];
+
     // <q, x_v> by the 8 lanes of a row group; every lane of the group gets the sum.  All
     // of a lane's 16-byte loads of the row are issued before the first one is used, so a
-    // whole expansion costs one memory latency, not one per batch of loads.
+    // whole expansion costs one memory latency, not one per batch of loads.  Loads and
+    // products come in runs of four with one scalar test each (is any of the run's 32
+    // chunks inside the row?); a lane whose chunk lies past the end of the row loads the
+    // row's last chunk instead and leaves the product out of the sum (`lim` is re-derived
+    // per call on purpose: sixteen loop-invariant lane masks would not fit the scalar registers).
     auto score_row = [&](int v) -> float {
         const char *rp = static_cast<const char *>(X) + (size_t)v * nch * 16;
         float acc = 0.f;
-        for (int c0 = sub; c0 < nch; c0 += 16 * LANES_PER_ROW) {
-            u4 x[16];
+        u4 x[16];
+        int lim = nch - sub;                              // chunk sub + 8u is in the row iff 8u < lim
+        asm volatile("" : "+v"(lim));
 #pragma unroll
-            for (int u = 0; u < 16; ++u) {
-                const int c = c0 + u * LANES_PER_ROW;
-                x[u] = c < nch ? load_chunk(rp + (size_t)c * 16) : zero_chunk();
+        for (int g = 0; g < 4; ++g)
+            if (g * 4 * LANES_PER_ROW < nch) {
+#pragma unroll
+                for (int u = 4 * g; u < 4 * g + 4; ++u)
+                    x[u] = load_chunk(rp + (size_t)(sub + min(u * LANES_PER_ROW, lim - 1)) * 16);
             }
 #pragma unroll
-            for (int u = 0; u < 16; ++u) {
-                const int c = c0 + u * LANES_PER_ROW;
-                if (c < nch) acc = dot_chunk<T>(x[u], qs[c], acc);
+        for (int g = 0; g < 4; ++g)
+            if (g * 4 * LANES_PER_ROW < nch) {
+#pragma unroll
+                for (int u = 4 * g; u < 4 * g + 4; ++u) {
+                    const float t = dot_chunk<T>(x[u], qr[u], acc);
+                    acc = u * LANES_PER_ROW < lim ? t : acc;
+                }
             }
+        for (int cb = BLK; cb < nch; cb += BLK / 2) {     // longer rows: the query comes from LDS
+            u4 qv[8];
+            lim -= cb == BLK ? BLK : BLK / 2;
+#pragma unroll
+            for (int g = 0; g < 2; ++g)
+                if (cb + g * 4 * LANES_PER_ROW < nch) {
+#pragma unroll
+                    for (int u = 4 * g; u < 4 * g + 4; ++u) {
+                        const int c = cb + sub + min(u * LANES_PER_ROW, lim - 1);
+                        x[u] = load_chunk(rp + (size_t)c * 16);
+                        qv[u] = qs[c];
+                    }
+                }
+#pragma unroll
+            for (int g = 0; g < 2; ++g)
+                if (cb + g * 4 * LANES_PER_ROW < nch) {
+#pragma unroll
+                    for (int u = 4 * g; u < 4 * g + 4; ++u) {
+                        const float t = dot_chunk<T>(x[u], qv[u], acc);
+                        acc = u * LANES_PER_ROW < lim ? t : acc;
+                    }
+                }
         }
-        acc += __shfl_xor(acc, 1);
-        acc += __shfl_xor(acc, 2);
-        acc += __shfl_xor(acc, 4);
-        return acc;
+        return group_sum(acc);
     };
 
     // list <- [(score(entry), entry)]
@@ -175,6 +270,7 @@ __global__ __launch_bounds__(GRAPH_THREADS) void graph_search_kernel(
         const int node = (int)(li(cur)[p] & ~EXPANDED);
         const int node2 = p2 >= 0 ? (int)(li(cur)[p2] & ~EXPANDED) : -1;
         const int have = adj_id[0] == node ? 0 : (adj_id[1] == node ? 1 : -1);
+        const int have_u = __builtin_amdgcn_readfirstlane(have);   // the same in all lanes
         const bool have2 = node2 < 0 || adj_id[0] == node2 || adj_id[1] == node2;
         __syncthreads();                                  // all have read the list and adj_id
         if (tid == 0) li(cur)[p] |= EXPANDED;
@@ -188,31 +284,38 @@ __global__ __launch_bounds__(GRAPH_THREADS) void graph_search_kernel(
         // score the unseen neighbours of `node`, 32 graph slots per pass
         for (int base = 0; base < RP; base += ROWS_PER_PASS) {
             const int slot = base + grp;
-            int v = -1;
-            if (slot < R) v = have >= 0 ? adj[have * RMAX_LDS + slot] : graph[(size_t)node * R + slot];
+            // The row comes from LDS if it was read ahead, else from the graph; the two cases are
+            // kept apart (one address space each, plain LDS and global loads) and every read is
+            // unconditional, with a clamped index, so that all of them are in flight together.
+            int v, o4[4];
+            const int vslot = min(slot, R - 1);
+            if (have_u >= 0) {
+                const int *row = adj + have_u * RMAX_LDS;
+                v = row[vslot];
+#pragma unroll
+                for (int t = 0; t < 4; ++t) o4[t] = row[min(sub * 4 + t, R - 1)];
+            } else {
+                const int32_t *row = graph + (size_t)node * R;
+                v = row[vslot];
+#pragma unroll
+                for (int t = 0; t < 4; ++t) o4[t] = row[min(sub * 4 + t, R - 1)];
+            }
+            if (slot >= R) v = -1;
             if constexpr (ROWDUP) {
                 // An id that an earlier slot of the row names as well is left to that slot.  The 8
                 // lanes of the group look at 4 slots each (read together with v: no extra round
                 // trip), which settles duplicates here and saves a pass and a barrier after scoring.
                 int dup = 0;
 #pragma unroll
-                for (int t = 0; t < 4; ++t) {
-                    const int idx = sub * 4 + t;
-                    int o = -1;
-                    if (idx < R && idx < slot) o = have >= 0 ? adj[have * RMAX_LDS + idx] : graph[(size_t)node * R + idx];
-                    dup |= (int)(idx < slot) & (int)(o == v);
-                }
+                for (int t = 0; t < 4; ++t) dup |= (int)(sub * 4 + t < min(slot, R)) & (int)(o4[t] == v);
                 const unsigned grp_bits = (unsigned)(__builtin_amdgcn_ballot_w64(dup != 0) >> (lane & ~(LANES_PER_ROW - 1))) & 0xffu;
                 if (grp_bits != 0) v = -1;
             }
-            int fresh = 0;
-            if ((unsigned)v < (unsigned)N) {
-                if (sub == 0) {
-                    const int old = atomicExch(&cache[((uint32_t)v * 2654435761u) >> cache_shift], v);
-                    fresh = old != v;
-                }
-                fresh = __shfl(fresh, lane & ~(LANES_PER_ROW - 1));
-            }
+            // the group's first lane asks the cache; its answer reaches the others as a lane mask
+            bool first_time = false;
+            if ((unsigned)v < (unsigned)N && sub == 0)
+                first_time = atomicExch(&cache[((uint32_t)v * 2654435761u) >> cache_shift], v) != v;
+            int fresh = (int)((__builtin_amdgcn_ballot_w64(first_time) >> (lane & ~(LANES_PER_ROW - 1))) & 1u);
             // The exact visited bit is read with the row (one round trip for both) and set
             // afterwards by an atomic that returns nothing.  The read bypasses the vector L1;
             // the atomics of earlier expansions completed before the barriers in between.
@@ -222,8 +325,8 @@ __global__ __launch_bounds__(GRAPH_THREADS) void graph_search_kernel(
             float s = 0.f;
             if (fresh) s = score_row(v);
             if (NS) {                                     // the cache may have forgotten v: the bitset has not
-                seen = __shfl(seen, lane & ~(LANES_PER_ROW - 1));
-                if (fresh && ((seen >> (v & 31)) & 1u)) fresh = 0;
+                const bool was_seen = sub == 0 && fresh && ((seen >> (v & 31)) & 1u);
+                if ((__builtin_amdgcn_ballot_w64(was_seen) >> (lane & ~(LANES_PER_ROW - 1))) & 1u) fresh = 0;
                 if (fresh && sub == 0) atomicOr(&seen_bits[v >> 5], 1u << (v & 31));
             }
             // Where would it go?  pos = entries of the list that precede it, or -1 when it does not
@@ -232,8 +335,14 @@ __global__ __launch_bounds__(GRAPH_THREADS) void graph_search_kernel(
             // two slots are sorted out after the barrier.
             int pos = -1;
             if (fresh && s == s) {                         // a NaN score is never listed
-                pos = group_lower_bound(ls(cur), li(cur), len, s, v, sub, lane);
-                if (pos >= ef || (pos < len && (int)(li(cur)[pos] & ~EXPANDED) == v)) pos = -1;
+                if (len <= 512) {
+                    bool listed;
+                    pos = group_lower_bound_512(ls(cur), li(cur), len, s, v, sub, lane, &listed);
+                    if (pos >= ef || listed) pos = -1;
+                } else {
+                    pos = group_lower_bound(ls(cur), li(cur), len, s, v, sub, lane);
+                    if (pos >= ef || (pos < len && (int)(li(cur)[pos] & ~EXPANDED) == v)) pos = -1;
+                }
             }
             if (sub == 0) {
                 cs[slot] = s;
@@ -412,9 +521,7 @@ __global__ __launch_bounds__(GRAPH_THREADS) void graph_search_kernel(
                             ((int)(pq.y >= 0) & precedes01(sq[1], cq.y, new_s, new_v)) +
                             ((int)(pq.z >= 0) & precedes01(sq[2], cq.z, new_s, new_v)) +
                             ((int)(pq.w >= 0) & precedes01(sq[3], cq.w, new_s, new_v));
-                    r += __shfl_xor(r, 1);
-                    r += __shfl_xor(r, 2);
-                    r += __shfl_xor(r, 4);
+                    r = group_sum(r);
                     if (sub == 0 && pos + r < ef) new_at = pos + r;
                 }
             }
