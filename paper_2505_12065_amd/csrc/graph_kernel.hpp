@@ -80,6 +80,7 @@ __device__ __forceinline__ int dpp_move(int x) {
 constexpr int DPP_SWAP1 = 0xB1;                           // quad_perm [1,0,3,2]
 constexpr int DPP_SWAP2 = 0x4E;                           // quad_perm [2,3,0,1]
 constexpr int DPP_HALF_MIRROR = 0x141;                    // lane i of each 8 <- lane 7 - i
+constexpr int DPP_MIRROR = 0x140;                         // lane i of each 16 <- lane 15 - i
 __device__ __forceinline__ float group_sum(float x) {
     x += __int_as_float(dpp_move<DPP_SWAP1>(__float_as_int(x)));
     x += __int_as_float(dpp_move<DPP_SWAP2>(__float_as_int(x)));
@@ -130,7 +131,7 @@ __device__ __forceinline__ int group_lower_bound_512(const float *s, const uint3
 // LDS reads issued together), 0 = taken from the layout at run time.
 // NS: with the maturity exit (parameters in `ns`, ignored otherwise).
 template <class T, int RPT, bool NS>
-__global__ __launch_bounds__(GRAPH_THREADS) void graph_search_kernel(
+__global__ __launch_bounds__(GRAPH_THREADS, 2) void graph_search_kernel(
     const void *__restrict__ X, int64_t N, int d, const int32_t *__restrict__ graph, int R, int entry,
     const void *__restrict__ Q, int k, int ef, int32_t *__restrict__ ids, float *__restrict__ scores,
     GraphLds L, NonStall ns) {
@@ -169,6 +170,7 @@ __global__ __launch_bounds__(GRAPH_THREADS) void graph_search_kernel(
     const int nch = d * T::bytes / 16;                    // 16-byte chunks per row
     const int RP = RPT ? RPT : (int)L.rp;
     constexpr bool ROWDUP = !NS && RPT == 32;             // duplicate ids of a row are settled while scoring
+    constexpr bool PIPELINED = ROWDUP;
     const uint32_t cache_shift = 32u - L.cache_bits;
     uint32_t *seen_bits = NS ? ns.visited + (size_t)b * ns.words : nullptr;   // zero on entry
 
@@ -195,19 +197,28 @@ __global__ __launch_bounds__(GRAPH_THREADS) void graph_search_kernel(
     // chunks inside the row?); a lane whose chunk lies past the end of the row loads the
     // row's last chunk instead and leaves the product out of the sum (`lim` is re-derived
     // per call on purpose: sixteen loop-invariant lane masks would not fit the scalar registers).
-    auto score_row = [&](int v) -> float {
+    // (in two halves, so that other work can be put between the loads and their use)
+    auto row_issue = [&](int v, u4 (&x)[16]) {
         const char *rp = static_cast<const char *>(X) + (size_t)v * nch * 16;
-        float acc = 0.f;
-        u4 x[16];
         int lim = nch - sub;                              // chunk sub + 8u is in the row iff 8u < lim
         asm volatile("" : "+v"(lim));
+        const char *rl = rp + sub * 16;
 #pragma unroll
         for (int g = 0; g < 4; ++g)
-            if (g * 4 * LANES_PER_ROW < nch) {
+            if ((g + 1) * 4 * LANES_PER_ROW <= nch) {      // the whole run is inside: constant offsets
+#pragma unroll
+                for (int u = 4 * g; u < 4 * g + 4; ++u) x[u] = load_chunk(rl + u * LANES_PER_ROW * 16);
+            } else if (g * 4 * LANES_PER_ROW < nch) {
 #pragma unroll
                 for (int u = 4 * g; u < 4 * g + 4; ++u)
                     x[u] = load_chunk(rp + (size_t)(sub + min(u * LANES_PER_ROW, lim - 1)) * 16);
             }
+    };
+    auto row_dots = [&](int v, u4 (&x)[16]) -> float {
+        const char *rp = static_cast<const char *>(X) + (size_t)v * nch * 16;
+        float acc = 0.f;
+        int lim = nch - sub;
+        asm volatile("" : "+v"(lim));
 #pragma unroll
         for (int g = 0; g < 4; ++g)
             if (g * 4 * LANES_PER_ROW < nch) {
@@ -242,6 +253,11 @@ __global__ __launch_bounds__(GRAPH_THREADS) void graph_search_kernel(
         }
         return group_sum(acc);
     };
+    auto score_row = [&](int v) -> float {
+        u4 x[16];
+        row_issue(v, x);
+        return row_dots(v, x);
+    };
 
     // list <- [(score(entry), entry)]
     if (grp == 0) {
@@ -260,9 +276,256 @@ __global__ __launch_bounds__(GRAPH_THREADS) void graph_search_kernel(
     __syncthreads();
 
     int cur = 0, len = 1;
-    int p = 0, p2 = -1;                                   // best and second-best unexpanded entries
     float ema = 0.f;                                      // kept by the last wave, copied to the others
     int n_dist = 1, n_expand = 0, early = 0;              // n_dist: last wave only
+    if constexpr (PIPELINED) {
+    // ---- R <= 32, no maturity exit: a software-pipelined loop ------------------------------------
+    // As soon as the neighbours of one expansion are scored, the next node to expand is known: the
+    // better of the best unexpanded list entry and the best newly scored neighbour.  Its rows are
+    // requested at once, and the merge of the current neighbours into the list and the scan for the
+    // following runner-up then run while those rows are on their way.  The order of expansions and
+    // merges, and so the result, is that of the plain loop below.
+    //   per iteration:  scan (runner-up) | products, list positions | barrier | next node, its
+    //                   neighbours filtered, rows requested | merge | barrier
+    // The second barrier waits for LDS traffic only: __syncthreads() would also wait for the rows.
+    auto lds_barrier = [] { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); };
+    const int gbase = lane & ~(LANES_PER_ROW - 1);
+    const bool inplace = L.ls1 == L.ls0;
+    int aid0 = -1, aid1 = -1, tog = 0;                    // whose adjacency rows adj[0], adj[1] hold
+    int node = entry, p = 0;                              // the node being expanded and its list index
+    if (tid == 0) li(0)[0] = (uint32_t)entry | EXPANDED;  // (scans leave entry p out by index as well)
+    u4 x[16];
+    int v = -1, fresh = 0;                                // this group's neighbour of `node`; to be scored?
+
+    // neighbour `grp` of node nd: duplicates within the row and ids the cache knows are dropped,
+    // the row of a remaining one is requested
+    auto request = [&](int nd) {
+        const int have = aid0 == nd ? 0 : (aid1 == nd ? 1 : -1);
+        const int slot = grp;
+        int o4[4];
+        const int vslot = min(slot, R - 1);
+        if (have >= 0) {
+            const int *row = adj + have * RMAX_LDS;
+            v = row[vslot];
+#pragma unroll
+            for (int t = 0; t < 4; ++t) o4[t] = row[min(sub * 4 + t, R - 1)];
+        } else {
+            const int32_t *row = graph + (size_t)nd * R;
+            v = row[vslot];
+#pragma unroll
+            for (int t = 0; t < 4; ++t) o4[t] = row[min(sub * 4 + t, R - 1)];
+        }
+        if (slot >= R) v = -1;
+        int dup = 0;
+#pragma unroll
+        for (int t = 0; t < 4; ++t) dup |= (int)(sub * 4 + t < min(slot, R)) & (int)(o4[t] == v);
+        if (((unsigned)(__builtin_amdgcn_ballot_w64(dup != 0) >> gbase) & 0xffu) != 0) v = -1;
+        bool first_time = false;
+        if ((unsigned)v < (unsigned)N && sub == 0)
+            first_time = atomicExch(&cache[((uint32_t)v * 2654435761u) >> cache_shift], v) != v;
+        fresh = (int)((__builtin_amdgcn_ballot_w64(first_time) >> gbase) & 1u);
+        if (fresh) row_issue(v, x);
+    };
+    request(node);
+
+    for (;;) {
+        // the runner-up: first unexpanded entry other than p (everything before p is expanded)
+        int p2 = -1;
+        if (len <= GRAPH_THREADS) {
+            uint32_t e4[GRAPH_WAVES];
+#pragma unroll
+            for (int w = 0; w < GRAPH_WAVES; ++w) e4[w] = w * 64 < len ? li(cur)[min(w * 64 + lane, len - 1)] : EXPANDED;
+#pragma unroll
+            for (int w = 0; w < GRAPH_WAVES; ++w) {
+                const int j = w * 64 + lane;
+                const uint64_t mw = __builtin_amdgcn_ballot_w64(j < len && j != p && !(e4[w] & EXPANDED));
+                if (mw != 0 && p2 < 0) p2 = w * 64 + __builtin_ctzll(mw);
+            }
+        } else {
+            for (int base = (p + 1) & ~(GRAPH_THREADS - 1); base < len; base += GRAPH_THREADS) {
+                const int j = base + tid;
+                const uint64_t m = __builtin_amdgcn_ballot_w64(j < len && j != p && !(li(cur)[j] & EXPANDED));
+                if (lane == 0) um[wave] = m;
+                lds_barrier();
+#pragma unroll
+                for (int w = 0; w < GRAPH_WAVES; ++w) {
+                    const uint64_t mw = um[w];
+                    if (mw != 0 && p2 < 0) p2 = base + w * 64 + __builtin_ctzll(mw);
+                }
+                if (p2 >= 0) break;
+                lds_barrier();                            // um is rewritten in the next round
+            }
+        }
+        int node2 = -1;
+        float s2 = 0.f;
+        if (p2 >= 0) {
+            node2 = __builtin_amdgcn_readfirstlane((int)(li(cur)[p2] & ~EXPANDED));
+            s2 = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(ls(cur)[p2])));
+        }
+        // Read-ahead: the runner-up is the most likely next expansion, so its adjacency row is
+        // fetched now, behind the rows already requested; it is stored once those are used.
+        const bool have2 = node2 < 0 || aid0 == node2 || aid1 == node2;
+        int ahead = -1;
+        if (!have2 && tid < R) ahead = graph[(size_t)node2 * R + tid];
+
+        // products and list positions of the neighbours of `node`
+        float s = 0.f;
+        if (fresh) s = row_dots(v, x);
+        int pos = -1;
+        if (fresh && s == s) {                             // a NaN score is never listed
+            if (len <= 512) {
+                bool listed;
+                pos = group_lower_bound_512(ls(cur), li(cur), len, s, v, sub, lane, &listed);
+                if (pos >= ef || listed) pos = -1;
+            } else {
+                pos = group_lower_bound(ls(cur), li(cur), len, s, v, sub, lane);
+                if (pos >= ef || (pos < len && (int)(li(cur)[pos] & ~EXPANDED) == v)) pos = -1;
+            }
+        }
+        if (sub == 0) {
+            cs[grp] = s;
+            ci[grp] = fresh ? v : -1;
+            cpos[grp] = pos;
+        }
+        if (!have2) {
+            const int into = aid0 == node ? 0 : (aid1 == node ? 1 : (tog ^= 1));
+            if (tid < R) adj[into * RMAX_LDS + tid] = ahead;
+            if (into == 0) aid0 = node2; else aid1 = node2;
+        }
+        __syncthreads();
+
+        // what is inserted (lane i < 32 of every wave looks at neighbour i) and which node is next
+        const int cl = lane & 31;
+        const float c_s = cs[cl];
+        const int c_v = ci[cl], c_p = cpos[cl];
+        const bool c_ok = lane < 32 && c_p >= 0;
+        const uint32_t new_mask = (uint32_t)__builtin_amdgcn_ballot_w64(c_ok);
+        const int n_new = __builtin_popcount(new_mask);
+        // The best new entry: scores as integers that order the other way round (0.0f is added so
+        // that -0 and +0 get the same one), their minimum over lanes 0 .. 31 by data-parallel moves
+        // inside the rows of 16 lanes and two lane reads; equal scores (rare) are settled by id.
+        int best_v = node2, best_l = -1;
+        if (n_new != 0) {
+            const uint32_t c_u = (uint32_t)__float_as_int(c_s + 0.0f);
+            const uint32_t c_k = c_ok ? ~(c_u ^ ((uint32_t)((int32_t)c_u >> 31) | 0x80000000u)) : 0xffffffffu;
+            uint32_t mk = c_k;
+            mk = min(mk, (uint32_t)dpp_move<DPP_SWAP1>((int)mk));
+            mk = min(mk, (uint32_t)dpp_move<DPP_SWAP2>((int)mk));
+            mk = min(mk, (uint32_t)dpp_move<DPP_HALF_MIRROR>((int)mk));
+            mk = min(mk, (uint32_t)dpp_move<DPP_MIRROR>((int)mk));
+            const uint32_t kmin = min((uint32_t)__builtin_amdgcn_readlane((int)mk, 0), (uint32_t)__builtin_amdgcn_readlane((int)mk, 16));
+            uint64_t m = __builtin_amdgcn_ballot_w64(c_ok && c_k == kmin);
+            int l = __builtin_ctzll(m);
+            int lv = __builtin_amdgcn_readlane(c_v, l);
+            for (m &= m - 1; m != 0; m &= m - 1) {        // several with the best score: lowest id
+                const int l2 = __builtin_ctzll(m), v2 = __builtin_amdgcn_readlane(c_v, l2);
+                if (v2 < lv) { l = l2; lv = v2; }
+            }
+            const float lsc = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(c_s), l));
+            if (node2 < 0 || precedes(lsc, lv, s2, node2)) { best_l = l; best_v = lv; }
+        }
+        if (best_v < 0) break;                            // nothing left to expand: natural stop
+
+        // New entries at or before list position j.  A few insertions (the rule once the list has
+        // settled): their positions are read out of lanes one by one; many: all 32 positions are
+        // held by every thread and compared in one unrolled run.
+        constexpr int FEW = 6;
+        const bool few = n_new <= FEW;
+        int4 p4[8];
+        unsigned jmin = 0xffffffffu;
+        if (n_new != 0 && (!few || inplace)) {
+#pragma unroll
+            for (int u = 0; u < 8; ++u) p4[u] = reinterpret_cast<const int4 *>(cpos)[u];
+            if (inplace) {
+#pragma unroll
+                for (int u = 0; u < 8; ++u)
+                    jmin = min(min(jmin, (unsigned)p4[u].x), min((unsigned)p4[u].y, min((unsigned)p4[u].z, (unsigned)p4[u].w)));
+            }
+        }
+        auto shift_of = [&](int j) {
+            int shift = 0;
+            if (few) {
+                for (uint32_t m = new_mask; m != 0; m &= m - 1)
+                    shift += (int)((unsigned)__builtin_amdgcn_readlane(c_p, __builtin_ctz(m)) <= (unsigned)j);
+            } else {
+#pragma unroll
+                for (int u = 0; u < 8; ++u)
+                    shift += (int)((unsigned)p4[u].x <= (unsigned)j) + (int)((unsigned)p4[u].y <= (unsigned)j) +
+                             (int)((unsigned)p4[u].z <= (unsigned)j) + (int)((unsigned)p4[u].w <= (unsigned)j);
+            }
+            return shift;
+        };
+        // where the next node will be in the merged list: the best new entry goes to its position
+        // as it is (no new entry precedes it), an old one moves up like every old entry
+        // (when an old entry stays the best, every new entry comes after it)
+        const int next_p = best_l >= 0 ? __builtin_amdgcn_readlane(c_p, best_l) : p2;
+
+        request(best_v);
+
+        // merge, as in the plain loop; the entry of the next node is marked as expanded on its way
+        if (n_new != 0) {
+            int new_at = -1;
+            float new_s = 0.f;
+            uint32_t new_e = 0;
+            const int gpos = cpos[grp];
+            if (gpos >= 0) {
+                new_s = cs[grp];
+                const int new_v = ci[grp];
+                const f4 sq = reinterpret_cast<const f4 *>(cs)[sub];
+                const int4 cq = reinterpret_cast<const int4 *>(ci)[sub];
+                const int4 pq = reinterpret_cast<const int4 *>(cpos)[sub];
+                int r = ((int)(pq.x >= 0) & precedes01(sq[0], cq.x, new_s, new_v)) +
+                        ((int)(pq.y >= 0) & precedes01(sq[1], cq.y, new_s, new_v)) +
+                        ((int)(pq.z >= 0) & precedes01(sq[2], cq.z, new_s, new_v)) +
+                        ((int)(pq.w >= 0) & precedes01(sq[3], cq.w, new_s, new_v));
+                r = group_sum(r);
+                if (sub == 0 && gpos + r < ef) new_at = gpos + r;
+                new_e = (uint32_t)new_v | (grp == best_l ? EXPANDED : 0u);
+            }
+            const int old_next = best_l < 0 ? p2 : -1;   // an old entry that becomes the next node
+            if (!inplace) {
+                const int nxt = cur ^ 1;
+                if (new_at >= 0) { ls(nxt)[new_at] = new_s; li(nxt)[new_at] = new_e; }
+                for (int j = tid; j < len; j += GRAPH_THREADS) {
+                    const int to = j + shift_of(j);
+                    if (to < ef) { ls(nxt)[to] = ls(cur)[j]; li(nxt)[to] = li(cur)[j] | (j == old_next ? EXPANDED : 0u); }
+                }
+                cur = nxt;
+            } else {
+                if (tid == 0 && old_next >= 0 && (unsigned)old_next < jmin) li(cur)[old_next] |= EXPANDED;
+                constexpr int PER = 4, MOVE = PER * GRAPH_THREADS;
+                const int lowest = (int)jmin & ~(MOVE - 1);
+                for (int base = (len - 1) & ~(MOVE - 1); base >= lowest; base -= MOVE) {
+                    float ms[PER];
+                    uint32_t mi[PER];
+#pragma unroll
+                    for (int u = 0; u < PER; ++u) {
+                        const int j = base + u * GRAPH_THREADS + tid;
+                        if (j < len && j >= (int)jmin) { ms[u] = ls(cur)[j]; mi[u] = li(cur)[j] | (j == old_next ? EXPANDED : 0u); }
+                    }
+                    __syncthreads();
+#pragma unroll
+                    for (int u = 0; u < PER; ++u) {
+                        const int j = base + u * GRAPH_THREADS + tid;
+                        if (j < len && j >= (int)jmin) {
+                            const int to = j + shift_of(j);
+                            if (to < ef) { ls(cur)[to] = ms[u]; li(cur)[to] = mi[u]; }
+                        }
+                    }
+                }
+                __syncthreads();                          // every old entry is out of the way
+                if (new_at >= 0) { ls(cur)[new_at] = new_s; li(cur)[new_at] = new_e; }
+            }
+            len = min(ef, len + n_new);
+        } else if (tid == 0) {
+            li(cur)[p2] |= EXPANDED;                      // the list stays as it is
+        }
+        lds_barrier();
+        node = best_v;
+        p = next_p;
+    }
+    } else {
+    int p = 0, p2 = -1;                                   // best and second-best unexpanded entries
     float *ema_s = reinterpret_cast<float *>(adj_id + 3);
     for (;;) {
         if (p < 0) break;                                 // nothing left to expand: natural stop
@@ -627,6 +890,8 @@ __global__ __launch_bounds__(GRAPH_THREADS) void graph_search_kernel(
             if (ready) { early = 1; break; }
         }
     }
+
+    }   // plain loop
 
     for (int j = tid; j < k; j += GRAPH_THREADS) {
         const bool has = j < len;
