@@ -126,6 +126,39 @@ __device__ __forceinline__ int group_lower_bound_512(const float *s, const uint3
     return 64 * blk + group_sum(cnt);
 }
 
+// The same again, for the common case that no probed entry has exactly the score v: then ids
+// play no part, and because list positions from `len` up to the next multiple of 64 hold -inf
+// (set when the kernel starts, never written afterwards) the length does not either: two
+// comparisons and two carries per entry.  Any lane that meets the score v itself sends its
+// whole group to the general routine.
+__device__ __forceinline__ int group_lower_bound_fast(const float *s, const uint32_t *id, int len, float v, int vid,
+                                                      int sub, int lane, bool *listed) {
+    const int gshift = lane & ~(LANES_PER_ROW - 1);
+    int blk = 0;
+    bool tie = false;
+    if (len > 64) {
+        const int m = 64 * sub + 63;
+        const float es = s[m];
+        tie = m < len && es == v;
+        blk = __builtin_popcount((unsigned)(__builtin_amdgcn_ballot_w64(m < len && es > v) >> gshift) & 0xffu);
+    }
+    int gt = 0, ge = 0;
+    if (blk < LANES_PER_ROW) {
+        const int j0 = 64 * blk + 8 * sub;
+        const f4 sa = *reinterpret_cast<const f4 *>(s + j0), sb = *reinterpret_cast<const f4 *>(s + j0 + 4);
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            gt += (int)(sa[t] > v) + (int)(sb[t] > v);
+            ge += (int)(sa[t] >= v) + (int)(sb[t] >= v);
+        }
+    }
+    tie |= gt != ge;
+    if (((unsigned)(__builtin_amdgcn_ballot_w64(tie) >> gshift) & 0xffu) != 0)
+        return group_lower_bound_512(s, id, len, v, vid, sub, lane, listed);
+    *listed = false;
+    return 64 * blk + group_sum(gt);
+}
+
 // RPT: number of graph slots rounded up to 32 when it is known at compile time (32 for
 // R <= 32: the short loops over the scored neighbours are then fully unrolled and their
 // LDS reads issued together), 0 = taken from the layout at run time.
@@ -177,6 +210,8 @@ __global__ __launch_bounds__(GRAPH_THREADS, 2) void graph_search_kernel(
     for (int c = tid; c < nch; c += GRAPH_THREADS)
         qs[c] = load_chunk(static_cast<const char *>(Q) + ((size_t)b * nch + c) * 16);
     for (int i = tid; i < (1 << L.cache_bits); i += GRAPH_THREADS) cache[i] = -1;
+    // list scores start as -inf up to the next multiple of 64 entries (see group_lower_bound_fast)
+    for (int i = tid; i < ((ef + 63) & ~63); i += GRAPH_THREADS) { ls(0)[i] = -INFINITY; ls(1)[i] = -INFINITY; }
     __syncthreads();
 
     const int sub = lane & (LANES_PER_ROW - 1);           // lane's position inside its row group
@@ -375,7 +410,7 @@ __global__ __launch_bounds__(GRAPH_THREADS, 2) void graph_search_kernel(
         if (fresh && s == s) {                             // a NaN score is never listed
             if (len <= 512) {
                 bool listed;
-                pos = group_lower_bound_512(ls(cur), li(cur), len, s, v, sub, lane, &listed);
+                pos = group_lower_bound_fast(ls(cur), li(cur), len, s, v, sub, lane, &listed);
                 if (pos >= ef || listed) pos = -1;
             } else {
                 pos = group_lower_bound(ls(cur), li(cur), len, s, v, sub, lane);
@@ -600,7 +635,7 @@ __global__ __launch_bounds__(GRAPH_THREADS, 2) void graph_search_kernel(
             if (fresh && s == s) {                         // a NaN score is never listed
                 if (len <= 512) {
                     bool listed;
-                    pos = group_lower_bound_512(ls(cur), li(cur), len, s, v, sub, lane, &listed);
+                    pos = group_lower_bound_fast(ls(cur), li(cur), len, s, v, sub, lane, &listed);
                     if (pos >= ef || listed) pos = -1;
                 } else {
                     pos = group_lower_bound(ls(cur), li(cur), len, s, v, sub, lane);
