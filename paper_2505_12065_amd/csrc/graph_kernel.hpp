@@ -340,10 +340,16 @@ __global__ __launch_bounds__(GRAPH_THREADS, 2) void graph_search_kernel(
         int o4[4];
         const int vslot = min(slot, R - 1);
         if (have >= 0) {
-            const int *row = adj + have * RMAX_LDS;
+            // (through a pointer that names the LDS address space: with plain pointers the compiler
+            // folds the two cases into loads through a generic address, which are much slower;
+            // one wide read: slots past R are masked below)
+            typedef __attribute__((address_space(3))) const int lds_int;
+            typedef int int4v __attribute__((ext_vector_type(4)));
+            typedef __attribute__((address_space(3))) const int4v lds_int4;
+            lds_int *row = (lds_int *)(adj + have * RMAX_LDS);
             v = row[vslot];
-#pragma unroll
-            for (int t = 0; t < 4; ++t) o4[t] = row[min(sub * 4 + t, R - 1)];
+            const int4v o = *(lds_int4 *)(row + sub * 4);
+            o4[0] = o[0]; o4[1] = o[1]; o4[2] = o[2]; o4[3] = o[3];
         } else {
             const int32_t *row = graph + (size_t)nd * R;
             v = row[vslot];
@@ -462,21 +468,15 @@ __global__ __launch_bounds__(GRAPH_THREADS, 2) void graph_search_kernel(
         if (best_v < 0) break;                            // nothing left to expand: natural stop
 
         // New entries at or before list position j.  A few insertions (the rule once the list has
-        // settled): their positions are read out of lanes one by one; many: all 32 positions are
-        // held by every thread and compared in one unrolled run.
+        // settled): their positions are read out of lanes one by one; many: the 32 positions are
+        // read from LDS (as broadcasts) and compared in one unrolled run.  (Holding the positions
+        // in registers across the merge, next to the rows in flight, would not fit the register file.)
         constexpr int FEW = 6;
         const bool few = n_new <= FEW;
-        int4 p4[8];
-        unsigned jmin = 0xffffffffu;
-        if (n_new != 0 && (!few || inplace)) {
-#pragma unroll
-            for (int u = 0; u < 8; ++u) p4[u] = reinterpret_cast<const int4 *>(cpos)[u];
-            if (inplace) {
-#pragma unroll
-                for (int u = 0; u < 8; ++u)
-                    jmin = min(min(jmin, (unsigned)p4[u].x), min((unsigned)p4[u].y, min((unsigned)p4[u].z, (unsigned)p4[u].w)));
-            }
-        }
+        unsigned jmin = 0xffffffffu;                      // lowest insertion position (long lists only)
+        if (inplace)
+            for (uint32_t m = new_mask; m != 0; m &= m - 1)
+                jmin = min(jmin, (unsigned)__builtin_amdgcn_readlane(c_p, __builtin_ctz(m)));
         auto shift_of = [&](int j) {
             int shift = 0;
             if (few) {
@@ -484,9 +484,11 @@ __global__ __launch_bounds__(GRAPH_THREADS, 2) void graph_search_kernel(
                     shift += (int)((unsigned)__builtin_amdgcn_readlane(c_p, __builtin_ctz(m)) <= (unsigned)j);
             } else {
 #pragma unroll
-                for (int u = 0; u < 8; ++u)
-                    shift += (int)((unsigned)p4[u].x <= (unsigned)j) + (int)((unsigned)p4[u].y <= (unsigned)j) +
-                             (int)((unsigned)p4[u].z <= (unsigned)j) + (int)((unsigned)p4[u].w <= (unsigned)j);
+                for (int u = 0; u < 8; ++u) {
+                    const int4 q4 = reinterpret_cast<const int4 *>(cpos)[u];
+                    shift += (int)((unsigned)q4.x <= (unsigned)j) + (int)((unsigned)q4.y <= (unsigned)j) +
+                             (int)((unsigned)q4.z <= (unsigned)j) + (int)((unsigned)q4.w <= (unsigned)j);
+                }
             }
             return shift;
         };
