@@ -202,8 +202,8 @@ __global__ __launch_bounds__(GRAPH_THREADS, 2) void graph_search_kernel(
     }
     const int nch = d * T::bytes / 16;                    // 16-byte chunks per row
     const int RP = RPT ? RPT : (int)L.rp;
-    constexpr bool ROWDUP = !NS && RPT == 32;             // duplicate ids of a row are settled while scoring
-    constexpr bool PIPELINED = ROWDUP;
+    constexpr bool PIPELINED = RPT == 32;                 // R <= 32: the software-pipelined loop
+    constexpr bool ROWDUP = false;                        // (plain loop) duplicate ids of a row settled while scoring
     const uint32_t cache_shift = 32u - L.cache_bits;
     uint32_t *seen_bits = NS ? ns.visited + (size_t)b * ns.words : nullptr;   // zero on entry
 
@@ -314,7 +314,7 @@ __global__ __launch_bounds__(GRAPH_THREADS, 2) void graph_search_kernel(
     float ema = 0.f;                                      // kept by the last wave, copied to the others
     int n_dist = 1, n_expand = 0, early = 0;              // n_dist: last wave only
     if constexpr (PIPELINED) {
-    // ---- R <= 32, no maturity exit: a software-pipelined loop ------------------------------------
+    // ---- R <= 32: a software-pipelined loop -------------------------------------------------------
     // As soon as the neighbours of one expansion are scored, the next node to expand is known: the
     // better of the best unexpanded list entry and the best newly scored neighbour.  Its rows are
     // requested at once, and the merge of the current neighbours into the list and the scan for the
@@ -331,6 +331,8 @@ __global__ __launch_bounds__(GRAPH_THREADS, 2) void graph_search_kernel(
     if (tid == 0) li(0)[0] = (uint32_t)entry | EXPANDED;  // (scans leave entry p out by index as well)
     u4 x[16];
     int v = -1, fresh = 0;                                // this group's neighbour of `node`; to be scored?
+    uint32_t seen = 0;                                    // NS: the word of the exact visited set that holds v
+    float *ema_s = reinterpret_cast<float *>(adj_id + 3);
 
     // neighbour `grp` of node nd: duplicates within the row and ids the cache knows are dropped,
     // the row of a remaining one is requested
@@ -365,6 +367,11 @@ __global__ __launch_bounds__(GRAPH_THREADS, 2) void graph_search_kernel(
         if ((unsigned)v < (unsigned)N && sub == 0)
             first_time = atomicExch(&cache[((uint32_t)v * 2654435761u) >> cache_shift], v) != v;
         fresh = (int)((__builtin_amdgcn_ballot_w64(first_time) >> gbase) & 1u);
+        // NS: the exact visited bit is read with the row (one round trip for both; the read
+        // bypasses the vector L1, the atomics of earlier expansions completed before the barrier
+        // after their scoring) and set after scoring by an atomic that returns nothing
+        if (NS && fresh && sub == 0)
+            seen = __hip_atomic_load(&seen_bits[v >> 5], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         if (fresh) row_issue(v, x);
     };
     request(node);
@@ -410,8 +417,14 @@ __global__ __launch_bounds__(GRAPH_THREADS, 2) void graph_search_kernel(
         if (!have2 && tid < R) ahead = graph[(size_t)node2 * R + tid];
 
         // products and list positions of the neighbours of `node`
+        ++n_expand;
         float s = 0.f;
         if (fresh) s = row_dots(v, x);
+        if (NS) {                                         // the cache may have forgotten v: the bitset has not
+            const bool was_seen = sub == 0 && fresh && ((seen >> (v & 31)) & 1u);
+            if ((__builtin_amdgcn_ballot_w64(was_seen) >> gbase) & 1u) fresh = 0;
+            if (fresh && sub == 0) atomicOr(&seen_bits[v >> 5], 1u << (v & 31));
+        }
         int pos = -1;
         if (fresh && s == s) {                             // a NaN score is never listed
             if (len <= 512) {
@@ -434,6 +447,23 @@ __global__ __launch_bounds__(GRAPH_THREADS, 2) void graph_search_kernel(
             if (into == 0) aid0 = node2; else aid1 = node2;
         }
         __syncthreads();
+
+        // NS: the relative quality of every newly scored node against the best and worst entries of
+        // the list as it stands before they go in, into the moving average in slot order (a slot
+        // holds a sample exactly when it scored a node: later slots that name the same id were
+        // dropped with the row).  Kept by the last wave, handed to the others through LDS.
+        if (NS && wave == GRAPH_WAVES - 1) {
+            const float s_best = ls(cur)[0], s_worst = ls(cur)[len - 1];
+            float r = NAN;                                // NaN: no sample; -inf: one, but best == worst
+            if (lane < 32 && ci[lane] >= 0) r = s_best != s_worst ? (s_best - cs[lane]) / (s_best - s_worst) : -INFINITY;
+            const uint32_t mag = __float_as_uint(r) & 0x7fffffffu;
+            n_dist += __builtin_popcountll(__builtin_amdgcn_ballot_w64(mag <= 0x7f800000u));
+            for (uint64_t defined = __builtin_amdgcn_ballot_w64(mag < 0x7f800000u); defined != 0; defined &= defined - 1) {
+                const float ri = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(r), __builtin_ctzll(defined)));
+                ema = fmaf(ns.alpha, ri - ema, ema);
+            }
+            if (lane == 0) ema_s[0] = ema;
+        }
 
         // what is inserted (lane i < 32 of every wave looks at neighbour i) and which node is next
         const int cl = lane & 31;
@@ -465,7 +495,8 @@ __global__ __launch_bounds__(GRAPH_THREADS, 2) void graph_search_kernel(
             const float lsc = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(c_s), l));
             if (node2 < 0 || precedes(lsc, lv, s2, node2)) { best_l = l; best_v = lv; }
         }
-        if (best_v < 0) break;                            // nothing left to expand: natural stop
+        const bool last = best_v < 0;                     // nothing left to expand: natural stop
+        if (!NS && last) break;                           // (NS: after the maturity test below)
 
         // New entries at or before list position j.  A few insertions (the rule once the list has
         // settled): their positions are read out of lanes one by one; many: the 32 positions are
@@ -497,7 +528,7 @@ __global__ __launch_bounds__(GRAPH_THREADS, 2) void graph_search_kernel(
         // (when an old entry stays the best, every new entry comes after it)
         const int next_p = best_l >= 0 ? __builtin_amdgcn_readlane(c_p, best_l) : p2;
 
-        request(best_v);
+        if (!last) request(best_v);
 
         // merge, as in the plain loop; the entry of the next node is marked as expanded on its way
         if (n_new != 0) {
@@ -554,10 +585,23 @@ __global__ __launch_bounds__(GRAPH_THREADS, 2) void graph_search_kernel(
                 if (new_at >= 0) { ls(cur)[new_at] = new_s; li(cur)[new_at] = new_e; }
             }
             len = min(ef, len + n_new);
-        } else if (tid == 0) {
+        } else if (tid == 0 && !last) {
             li(cur)[p2] |= EXPANDED;                      // the list stays as it is
         }
         lds_barrier();
+        if (NS) {
+            ema = ema_s[0];
+            if (ema > ns.tau) {                           // mature: leave as soon as the engine is ready
+                int ready = 1;
+                if (ns.ready) {
+                    if (tid == 0) adj_id[2] = __hip_atomic_load(ns.ready, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+                    __syncthreads();
+                    ready = adj_id[2];
+                }
+                if (ready) { early = 1; break; }
+            }
+            if (last) break;
+        }
         node = best_v;
         p = next_p;
     }
