@@ -203,7 +203,6 @@ __global__ __launch_bounds__(GRAPH_THREADS, 2) void graph_search_kernel(
     const int nch = d * T::bytes / 16;                    // 16-byte chunks per row
     const int RP = RPT ? RPT : (int)L.rp;
     constexpr bool PIPELINED = RPT == 32;                 // R <= 32: the software-pipelined loop
-    constexpr bool ROWDUP = false;                        // (plain loop) duplicate ids of a row settled while scoring
     const uint32_t cache_shift = 32u - L.cache_bits;
     uint32_t *seen_bits = NS ? ns.visited + (size_t)b * ns.words : nullptr;   // zero on entry
 
@@ -606,6 +605,8 @@ __global__ __launch_bounds__(GRAPH_THREADS, 2) void graph_search_kernel(
         p = next_p;
     }
     } else {
+    // ---- R > 32: the plain loop, 32 graph slots per scoring pass -----------------------------------
+    // read the list top, score, barrier, sort out ids named twice, barrier, merge, barrier, scan
     int p = 0, p2 = -1;                                   // best and second-best unexpanded entries
     float *ema_s = reinterpret_cast<float *>(adj_id + 3);
     for (;;) {
@@ -628,32 +629,11 @@ __global__ __launch_bounds__(GRAPH_THREADS, 2) void graph_search_kernel(
         // score the unseen neighbours of `node`, 32 graph slots per pass
         for (int base = 0; base < RP; base += ROWS_PER_PASS) {
             const int slot = base + grp;
-            // The row comes from LDS if it was read ahead, else from the graph; the two cases are
-            // kept apart (one address space each, plain LDS and global loads) and every read is
-            // unconditional, with a clamped index, so that all of them are in flight together.
-            int v, o4[4];
-            const int vslot = min(slot, R - 1);
-            if (have_u >= 0) {
-                const int *row = adj + have_u * RMAX_LDS;
-                v = row[vslot];
-#pragma unroll
-                for (int t = 0; t < 4; ++t) o4[t] = row[min(sub * 4 + t, R - 1)];
-            } else {
-                const int32_t *row = graph + (size_t)node * R;
-                v = row[vslot];
-#pragma unroll
-                for (int t = 0; t < 4; ++t) o4[t] = row[min(sub * 4 + t, R - 1)];
-            }
-            if (slot >= R) v = -1;
-            if constexpr (ROWDUP) {
-                // An id that an earlier slot of the row names as well is left to that slot.  The 8
-                // lanes of the group look at 4 slots each (read together with v: no extra round
-                // trip), which settles duplicates here and saves a pass and a barrier after scoring.
-                int dup = 0;
-#pragma unroll
-                for (int t = 0; t < 4; ++t) dup |= (int)(sub * 4 + t < min(slot, R)) & (int)(o4[t] == v);
-                const unsigned grp_bits = (unsigned)(__builtin_amdgcn_ballot_w64(dup != 0) >> (lane & ~(LANES_PER_ROW - 1))) & 0xffu;
-                if (grp_bits != 0) v = -1;
+            // the row comes from LDS if it was read ahead, else from the graph
+            int v = -1;
+            if (slot < R) {
+                if (have_u >= 0) v = adj[have_u * RMAX_LDS + slot];
+                else v = graph[(size_t)node * R + slot];
             }
             // the group's first lane asks the cache; its answer reaches the others as a lane mask
             bool first_time = false;
@@ -706,7 +686,6 @@ __global__ __launch_bounds__(GRAPH_THREADS, 2) void graph_search_kernel(
         // (the loops over the scored neighbours read them with wide, unconditional LDS loads and
         // use branch-free arithmetic: a short-circuit "j < i && ci[j] == v" compiles into one
         // predicated load-and-wait per j, i.e. 32 LDS round trips in a row)
-        if constexpr (!ROWDUP)
         for (int i = tid; i < RP; i += GRAPH_THREADS) {
             const int v = ci[i];
             if (v >= 0) {
@@ -801,7 +780,7 @@ __global__ __launch_bounds__(GRAPH_THREADS, 2) void graph_search_kernel(
             }
             if (lane == 0) ema_s[0] = ema;
         }
-        if constexpr (!ROWDUP) __syncthreads();
+        __syncthreads();
 
         // merge: new entries go to pos + (rank among the new entries), old entry j moves up by the
         // number of new entries that precede it.  Lists of up to 2048 entries are double-buffered

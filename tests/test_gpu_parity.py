@@ -289,6 +289,35 @@ def test_graph_long_lists(ef, R, dtype):
     assert np.abs(st[:, 1] - nd).max() <= max(8, nd.max() // 100) and np.abs(st[:, 2] - ne).max() <= max(4, ne.max() // 100)
 
 
+@pytest.mark.parametrize("ef,R,k", [(16, 8, 5), (200, 32, 10), (700, 32, 16), (48, 40, 7)])
+def test_graph_ties_go_to_lower_id(ef, R, k):
+    """Every vector occurs four times under scattered ids, so a query scores the copies exactly alike (in fp32
+    on the GPU as in fp64 in the oracle) and the order (score descending, id ascending) decides every one of
+    those ties: in the list positions, among the neighbours of one expansion, in the choice of the next node,
+    at the k-th place.  Ids must match the oracle's exactly."""
+    say(f"graph with tied scores: ef={ef} R={R} k={k}")
+    N, d = 4000, 64
+    base = synth.make_corpus(N // 4, d, 8, seed=ef + R, dtype=torch.float16, zipf_a=None, sigma=0.4)
+    gen = torch.Generator().manual_seed(ef)
+    where = torch.randperm(N, generator=gen)                      # copy j of vector i sits at row where[4 i + j]
+    x = torch.empty(N, d, dtype=torch.float16)
+    x[where] = base.x.repeat_interleave(4, 0)
+    q = synth.make_queries(base, 24)
+    g = synth.ring_union(synth.knn_graph(x, R - 2)).contiguous()
+    ids, sc = ann.ann_graph_search_typed(x.to(DEV), g.to(DEV), 5, q.to(DEV), k, ef)
+    torch.cuda.synchronize()
+    o_ids, o_sc, o_sc64, nd, ne = oracle.graph_search(x.numpy(), g.numpy(), 5, q.numpy(), k, ef)
+    assert (o_sc[:, 0] == o_sc[:, 1]).any(), "the workload is meant to have ties at the top"
+    assert np.array_equal(ids.cpu().numpy(), o_ids)
+    assert np.abs(sc.cpu().numpy() - o_sc64).max() < 1e-4
+    # the same through the maturity-exit entry point with the exit switched off, counters included
+    n_ids, n_sc, stats, _ = ann.ann_graph_search_nonstall_typed(x.to(DEV), g.to(DEV), 5, q.to(DEV), k, ef, tau=float("inf"))
+    torch.cuda.synchronize()
+    assert np.array_equal(n_ids.cpu().numpy(), o_ids)
+    st = stats.cpu().numpy()
+    assert np.array_equal(st[:, 1], nd) and np.array_equal(st[:, 2], ne)
+
+
 def test_graph_padding_when_few_nodes_are_reachable():
     c = synth.make_corpus(200, 64, 4, seed=2, dtype=torch.float16, zipf_a=None, sigma=0.3)
     q = synth.make_queries(c, 4)
