@@ -377,16 +377,33 @@ __global__ __launch_bounds__(GRAPH_THREADS, 2) void graph_search_kernel(
 
     for (;;) {
         // the runner-up: first unexpanded entry other than p (everything before p is expanded)
-        int p2 = -1;
+        int p2 = -1, node2 = -1;
+        float s2 = 0.f;
         if (len <= GRAPH_THREADS) {
+            // every wave looks at the whole list itself: ids and scores in one round trip, the
+            // runner-up's own pair then comes out of a lane
             uint32_t e4[GRAPH_WAVES];
+            float s4[GRAPH_WAVES];
 #pragma unroll
-            for (int w = 0; w < GRAPH_WAVES; ++w) e4[w] = w * 64 < len ? li(cur)[min(w * 64 + lane, len - 1)] : EXPANDED;
+            for (int w = 0; w < GRAPH_WAVES; ++w) {
+                e4[w] = EXPANDED;
+                s4[w] = 0.f;
+                if (w * 64 < len) {
+                    const int j = min(w * 64 + lane, len - 1);
+                    e4[w] = li(cur)[j];
+                    s4[w] = ls(cur)[j];
+                }
+            }
 #pragma unroll
             for (int w = 0; w < GRAPH_WAVES; ++w) {
                 const int j = w * 64 + lane;
                 const uint64_t mw = __builtin_amdgcn_ballot_w64(j < len && j != p && !(e4[w] & EXPANDED));
-                if (mw != 0 && p2 < 0) p2 = w * 64 + __builtin_ctzll(mw);
+                if (mw != 0 && p2 < 0) {
+                    const int l = __builtin_ctzll(mw);
+                    p2 = w * 64 + l;
+                    node2 = __builtin_amdgcn_readlane((int)e4[w], l);
+                    s2 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(s4[w]), l));
+                }
             }
         } else {
             for (int base = (p + 1) & ~(GRAPH_THREADS - 1); base < len; base += GRAPH_THREADS) {
@@ -402,12 +419,10 @@ __global__ __launch_bounds__(GRAPH_THREADS, 2) void graph_search_kernel(
                 if (p2 >= 0) break;
                 lds_barrier();                            // um is rewritten in the next round
             }
-        }
-        int node2 = -1;
-        float s2 = 0.f;
-        if (p2 >= 0) {
-            node2 = __builtin_amdgcn_readfirstlane((int)(li(cur)[p2] & ~EXPANDED));
-            s2 = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(ls(cur)[p2])));
+            if (p2 >= 0) {
+                node2 = __builtin_amdgcn_readfirstlane((int)(li(cur)[p2] & ~EXPANDED));
+                s2 = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(ls(cur)[p2])));
+            }
         }
         // Read-ahead: the runner-up is the most likely next expansion, so its adjacency row is
         // fetched now, behind the rows already requested; it is stored once those are used.
@@ -468,6 +483,7 @@ __global__ __launch_bounds__(GRAPH_THREADS, 2) void graph_search_kernel(
         const int cl = lane & 31;
         const float c_s = cs[cl];
         const int c_v = ci[cl], c_p = cpos[cl];
+        asm volatile("" ::"v"(c_s), "v"(c_v));            // all three reads now, in one round trip
         const bool c_ok = lane < 32 && c_p >= 0;
         const uint32_t new_mask = (uint32_t)__builtin_amdgcn_ballot_w64(c_ok);
         const int n_new = __builtin_popcount(new_mask);
