@@ -255,7 +255,10 @@ __global__ __launch_bounds__(GRAPH_THREADS, 2) void graph_search_kernel(
         asm volatile("" : "+v"(lim));
 #pragma unroll
         for (int g = 0; g < 4; ++g)
-            if (g * 4 * LANES_PER_ROW < nch) {
+            if ((g + 1) * 4 * LANES_PER_ROW <= nch) {      // the whole run is inside the row
+#pragma unroll
+                for (int u = 4 * g; u < 4 * g + 4; ++u) acc = dot_chunk<T>(x[u], qr[u], acc);
+            } else if (g * 4 * LANES_PER_ROW < nch) {
 #pragma unroll
                 for (int u = 4 * g; u < 4 * g + 4; ++u) {
                     const float t = dot_chunk<T>(x[u], qr[u], acc);
