@@ -159,9 +159,9 @@ __device__ __forceinline__ int group_lower_bound_fast(const float *s, const uint
     return 64 * blk + group_sum(gt);
 }
 
-// RPT: number of graph slots rounded up to 32 when it is known at compile time (32 for
-// R <= 32: the short loops over the scored neighbours are then fully unrolled and their
-// LDS reads issued together), 0 = taken from the layout at run time.
+// RPT: 32 for graphs with R <= 32 slots per node (one scoring pass per expansion, loops over the
+// scored neighbours fully unrolled: the software-pipelined loop), 0 for wider graphs (the number
+// of slots, rounded up to 32, comes from the layout at run time: the plain loop).
 // NS: with the maturity exit (parameters in `ns`, ignored otherwise).
 template <class T, int RPT, bool NS>
 __global__ __launch_bounds__(GRAPH_THREADS, 2) void graph_search_kernel(
@@ -702,27 +702,11 @@ __global__ __launch_bounds__(GRAPH_THREADS, 2) void graph_search_kernel(
         __syncthreads();
 
         // an id named by an earlier slot as well is taken once: cpos = -1 for the later slot
-        // (the loops over the scored neighbours read them with wide, unconditional LDS loads and
-        // use branch-free arithmetic: a short-circuit "j < i && ci[j] == v" compiles into one
-        // predicated load-and-wait per j, i.e. 32 LDS round trips in a row)
         for (int i = tid; i < RP; i += GRAPH_THREADS) {
             const int v = ci[i];
             if (v >= 0) {
                 int dup = 0;
-                if constexpr (RPT == 32) {
-                    int4 c4[8];
-#pragma unroll
-                    for (int u = 0; u < 8; ++u) c4[u] = reinterpret_cast<const int4 *>(ci)[u];
-#pragma unroll
-                    for (int u = 0; u < 8; ++u) {
-                        dup |= (int)(c4[u].x == v) & (int)(4 * u + 0 < i);
-                        dup |= (int)(c4[u].y == v) & (int)(4 * u + 1 < i);
-                        dup |= (int)(c4[u].z == v) & (int)(4 * u + 2 < i);
-                        dup |= (int)(c4[u].w == v) & (int)(4 * u + 3 < i);
-                    }
-                } else {
-                    for (int j = 0; j < i; ++j) dup |= (int)(ci[j] == v);
-                }
+                for (int j = 0; j < i; ++j) dup |= (int)(ci[j] == v);
                 if (dup) cpos[i] = -1;
             }
         }
@@ -745,58 +729,18 @@ __global__ __launch_bounds__(GRAPH_THREADS, 2) void graph_search_kernel(
                     if (r != -INFINITY) ema = fmaf(ns.alpha, r - ema, ema);
                 }
             };
-            if constexpr (RPT == 32) {
-                // lane i < 32 handles slot i: the row in 24 wide LDS reads, samples passed on in
-                // slot order through scalar registers
-                float r = NAN;
-                if (lane < 32) {
-                    int4 o4[8], i4[8];
-                    f4 s4[8];
-#pragma unroll
-                    for (int u = 0; u < 8; ++u) {
-                        o4[u] = reinterpret_cast<const int4 *>(co)[u];
-                        i4[u] = reinterpret_cast<const int4 *>(ci)[u];
-                        s4[u] = reinterpret_cast<const f4 *>(cs)[u];
-                    }
-                    const int me = co[lane];
-                    bool first = me >= 0, scored = false;
-                    float sv = 0.f;
-#pragma unroll
-                    for (int j = 0; j < 32; ++j) {
-                        const int4 oq = o4[j >> 2], iq = i4[j >> 2];
-                        const int oj = (j & 3) == 0 ? oq.x : (j & 3) == 1 ? oq.y : (j & 3) == 2 ? oq.z : oq.w;
-                        const int ij = (j & 3) == 0 ? iq.x : (j & 3) == 1 ? iq.y : (j & 3) == 2 ? iq.z : iq.w;
-                        first &= !((j < lane) & (oj == me));
-                        scored |= (ij == me);
-                        sv = (ij == me) ? s4[j >> 2][j & 3] : sv;
-                    }
-                    r = rq_of(lane, me, first, scored, sv);
+            for (int i = lane; i < RP; i += WAVE) {
+                const int me = co[i];
+                bool first = me >= 0, scored = false;
+                float sv = 0.f;
+                for (int j = 0; j < RP; ++j) {
+                    if (j < i && co[j] == me) first = false;
+                    if (ci[j] == me) { scored = true; sv = cs[j]; }
                 }
-                // only the slots that hold a sample are visited (about a third of them), in slot order
-                // (tests on the bit pattern: not NaN = a newly scored node, finite = with a defined RQ)
-                const uint32_t mag = __float_as_uint(r) & 0x7fffffffu;
-                n_dist += __builtin_popcountll(__builtin_amdgcn_ballot_w64(mag <= 0x7f800000u));
-                uint64_t defined = __builtin_amdgcn_ballot_w64(mag < 0x7f800000u);
-                while (defined != 0) {
-                    const int i = __builtin_ctzll(defined);
-                    defined &= defined - 1;
-                    const float ri = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(r), i));
-                    ema = fmaf(ns.alpha, ri - ema, ema);
-                }
-            } else {
-                for (int i = lane; i < RP; i += WAVE) {
-                    const int me = co[i];
-                    bool first = me >= 0, scored = false;
-                    float sv = 0.f;
-                    for (int j = 0; j < RP; ++j) {
-                        if (j < i && co[j] == me) first = false;
-                        if (ci[j] == me) { scored = true; sv = cs[j]; }
-                    }
-                    rq[i] = rq_of(i, me, first, scored, sv);
-                }
-                // rq[] is written and read by this wave only, in program order
-                for (int i = 0; i < RP; ++i) take(rq[i]);
+                rq[i] = rq_of(i, me, first, scored, sv);
             }
+            // rq[] is written and read by this wave only, in program order
+            for (int i = 0; i < RP; ++i) take(rq[i]);
             if (lane == 0) ema_s[0] = ema;
         }
         __syncthreads();
@@ -807,25 +751,9 @@ __global__ __launch_bounds__(GRAPH_THREADS, 2) void graph_search_kernel(
         const bool inplace = L.ls1 == L.ls0;
         int n_new = 0;
         unsigned jmin = 0xffffffffu;                      // lowest position a new entry takes
-        int4 p4[RPT == 32 ? 8 : 1];                       // R <= 32: every thread holds the 32 positions
-        if constexpr (RPT == 32) {
-            // how many: one position per lane and a lane mask; the 32 positions themselves are
-            // only fetched when something is inserted, their minimum only where it is used
-            n_new = __builtin_popcount((uint32_t)__builtin_amdgcn_ballot_w64(cpos[lane & 31] >= 0));
-            if (n_new != 0) {
-#pragma unroll
-                for (int u = 0; u < 8; ++u) p4[u] = reinterpret_cast<const int4 *>(cpos)[u];
-                if (inplace || len > GRAPH_THREADS) {
-#pragma unroll
-                    for (int u = 0; u < 8; ++u)
-                        jmin = min(min(jmin, (unsigned)p4[u].x), min((unsigned)p4[u].y, min((unsigned)p4[u].z, (unsigned)p4[u].w)));
-                }
-            }
-        } else {
-            for (int i = 0; i < RP; ++i) {
-                n_new += (cpos[i] >= 0);
-                jmin = min(jmin, (unsigned)cpos[i]);
-            }
+        for (int i = 0; i < RP; ++i) {
+            n_new += (cpos[i] >= 0);
+            jmin = min(jmin, (unsigned)cpos[i]);
         }
         // nothing to insert (most expansions once the list has settled): the list stays where it is
         const int nxt = inplace || n_new == 0 ? cur : cur ^ 1;
@@ -833,41 +761,14 @@ __global__ __launch_bounds__(GRAPH_THREADS, 2) void graph_search_kernel(
         // when, as an unsigned number, it is <= j; -1 is not)
         auto shift_of = [&](int j) {
             int shift = 0;
-            if constexpr (RPT == 32) {
-#pragma unroll
-                for (int u = 0; u < 8; ++u)
-                    shift += (int)((unsigned)p4[u].x <= (unsigned)j) + (int)((unsigned)p4[u].y <= (unsigned)j) +
-                             (int)((unsigned)p4[u].z <= (unsigned)j) + (int)((unsigned)p4[u].w <= (unsigned)j);
-            } else {
-                for (int i = 0; i < RP; ++i) shift += (int)((unsigned)cpos[i] <= (unsigned)j);
-            }
+            for (int i = 0; i < RP; ++i) shift += (int)((unsigned)cpos[i] <= (unsigned)j);
             return shift;
         };
         // the new entry of this thread: final position or -1
         int new_at = -1;
         float new_s = 0.f;
         int new_v = 0;
-        if constexpr (RPT == 32) {
-            // row group g places scored neighbour g: each of its 8 lanes compares it with 4 of the
-            // 32 neighbours (one wide read each of scores, ids, positions), the counts are added
-            // up by shuffles, the group's first lane writes the entry
-            if (n_new != 0) {
-                const int pos = cpos[grp];
-                if (pos >= 0) {                            // the same for the 8 lanes of the group
-                    new_s = cs[grp];
-                    new_v = ci[grp];
-                    const f4 sq = reinterpret_cast<const f4 *>(cs)[sub];
-                    const int4 cq = reinterpret_cast<const int4 *>(ci)[sub];
-                    const int4 pq = reinterpret_cast<const int4 *>(cpos)[sub];
-                    int r = ((int)(pq.x >= 0) & precedes01(sq[0], cq.x, new_s, new_v)) +
-                            ((int)(pq.y >= 0) & precedes01(sq[1], cq.y, new_s, new_v)) +
-                            ((int)(pq.z >= 0) & precedes01(sq[2], cq.z, new_s, new_v)) +
-                            ((int)(pq.w >= 0) & precedes01(sq[3], cq.w, new_s, new_v));
-                    r = group_sum(r);
-                    if (sub == 0 && pos + r < ef) new_at = pos + r;
-                }
-            }
-        } else if (n_new != 0 && tid < RP) {              // slot tid, RP <= GRAPH_THREADS
+        if (n_new != 0 && tid < RP) {                     // slot tid, RP <= GRAPH_THREADS
             const int pos = cpos[tid];
             if (pos >= 0) {
                 new_s = cs[tid];
