@@ -318,6 +318,54 @@ def test_graph_ties_go_to_lower_id(ef, R, k):
     assert np.array_equal(st[:, 1], nd) and np.array_equal(st[:, 2], ne)
 
 
+def test_graph_random_configurations():
+    """Thirty seeded draws of (N, d, R, ef, k, dtype, B) with junk ids, repeated ids and repeated vectors in
+    the inputs: every list length regime (up to 64, up to 256, up to 512, beyond), both loops (R <= 32 and
+    R > 32) and both entry points against the oracle, counters of the maturity variant included."""
+    rng = np.random.default_rng(2024)
+    total = strict_total = 0
+    for case in range(30):
+        N = int(rng.integers(40, 4000))
+        d = int(rng.choice([8, 16, 24, 64, 72, 136, 256, 520]))
+        R = int(rng.choice([1, 2, 5, 8, 16, 31, 32, 33, 48]))
+        ef = int(rng.choice([1, 3, 17, 64, 65, 200, 256, 257, 400, 512, 513, 900]))
+        k = int(rng.integers(1, min(ef, 20) + 1))
+        B = int(rng.integers(1, 12))
+        dtype = [torch.float16, torch.bfloat16, torch.float32][int(rng.integers(0, 3))]
+        say(f"graph random case {case}: N={N} d={d} R={R} ef={ef} k={k} B={B} {dtype}")
+        c = synth.make_corpus(N, d, max(2, N // 300), seed=1000 + case, dtype=dtype, zipf_a=None, sigma=0.4)
+        x = c.x.clone()
+        gen = torch.Generator().manual_seed(case)
+        copies = torch.randint(0, N, (N // 10,), generator=gen)
+        x[copies] = x[torch.randint(0, N, (N // 10,), generator=gen)].clone()        # repeated vectors: tied scores
+        q = synth.make_queries(c, B)
+        nn_ = max(1, min(R, N - 1) // 2)
+        g = synth.knn_graph(x, nn_)
+        junk = torch.randint(-1, N + 2, (N, R - g.shape[1]), generator=gen, dtype=torch.int32)
+        g = torch.cat([g, junk], 1)[:, :R].contiguous()
+        g[:, -1] = (torch.arange(N, dtype=torch.int32) + 1) % N                       # a ring keeps it connected
+        if R >= 2:
+            g[::7, 0] = g[::7, R - 1]                                                 # an id named twice in a row
+        entry = int(rng.integers(0, N))
+        name = np_dtype_name(x)
+        xn, qn, gn = to_np(x), to_np(q), g.numpy()
+        ids, sc = ann.ann_graph_search_typed(x.to(DEV), g.to(DEV), entry, q.to(DEV), k, ef)
+        n_ids, n_sc, stats, _ = ann.ann_graph_search_nonstall_typed(x.to(DEV), g.to(DEV), entry, q.to(DEV), k, ef,
+                                                                    tau=float("inf"))
+        torch.cuda.synchronize()
+        o_ids, _, o_sc64, nd, ne = oracle.graph_search(xn, gn, entry, qn, k, ef, dtype=name)
+        st, _, n = compare_topk(ids.cpu().numpy(), sc.cpu().numpy(), o_ids, o_sc64, xn, qn, dtype=name)
+        compare_topk(n_ids.cpu().numpy(), n_sc.cpu().numpy(), o_ids, o_sc64, xn, qn, dtype=name)
+        assert np.array_equal(ids.cpu().numpy(), n_ids.cpu().numpy()), "the two entry points disagree"
+        same = np.all(ids.cpu().numpy() == o_ids, axis=1)
+        stn = stats.cpu().numpy()
+        assert np.array_equal(stn[same, 1], nd[same]) and np.array_equal(stn[same, 2], ne[same]), (stn, nd, ne)
+        total += n
+        strict_total += st
+    say(f"  {strict_total}/{total} queries with ids identical to the oracle's")
+    assert strict_total >= total - max(2, total // 50)
+
+
 def test_graph_padding_when_few_nodes_are_reachable():
     c = synth.make_corpus(200, 64, 4, seed=2, dtype=torch.float16, zipf_a=None, sigma=0.3)
     q = synth.make_queries(c, 4)
