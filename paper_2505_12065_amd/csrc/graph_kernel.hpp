@@ -382,49 +382,54 @@ __global__ __launch_bounds__(GRAPH_THREADS, 2) void graph_search_kernel(
         // the runner-up: first unexpanded entry other than p (everything before p is expanded)
         int p2 = -1, node2 = -1;
         float s2 = 0.f;
-        if (len <= GRAPH_THREADS) {
-            // every wave looks at the whole list itself: ids and scores in one round trip, the
-            // runner-up's own pair then comes out of a lane
+        {
+            // Every wave looks itself at the 256 entries from the block of 64 that holds p + 1 on:
+            // ids and scores in one round trip, the runner-up's own pair then comes out of a lane.
+            // No exchange between the waves and no barrier, whatever the length of the list.
+            const int base0 = (p + 1) & ~63;
             uint32_t e4[GRAPH_WAVES];
             float s4[GRAPH_WAVES];
 #pragma unroll
             for (int w = 0; w < GRAPH_WAVES; ++w) {
                 e4[w] = EXPANDED;
                 s4[w] = 0.f;
-                if (w * 64 < len) {
-                    const int j = min(w * 64 + lane, len - 1);
+                if (base0 + w * 64 < len) {
+                    const int j = min(base0 + w * 64 + lane, len - 1);
                     e4[w] = li(cur)[j];
                     s4[w] = ls(cur)[j];
                 }
             }
 #pragma unroll
             for (int w = 0; w < GRAPH_WAVES; ++w) {
-                const int j = w * 64 + lane;
+                const int j = base0 + w * 64 + lane;
                 const uint64_t mw = __builtin_amdgcn_ballot_w64(j < len && j != p && !(e4[w] & EXPANDED));
                 if (mw != 0 && p2 < 0) {
                     const int l = __builtin_ctzll(mw);
-                    p2 = w * 64 + l;
+                    p2 = base0 + w * 64 + l;
                     node2 = __builtin_amdgcn_readlane((int)e4[w], l);
                     s2 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(s4[w]), l));
                 }
             }
-        } else {
-            for (int base = (p + 1) & ~(GRAPH_THREADS - 1); base < len; base += GRAPH_THREADS) {
-                const int j = base + tid;
-                const uint64_t m = __builtin_amdgcn_ballot_w64(j < len && j != p && !(li(cur)[j] & EXPANDED));
-                if (lane == 0) um[wave] = m;
-                lds_barrier();
+            // nothing unexpanded among those 256 (rare): the rest, 256 entries per round, one ballot per
+            // wave handed round through LDS
+            if (p2 < 0 && base0 + GRAPH_THREADS < len) {
+                for (int base = base0 + GRAPH_THREADS; base < len; base += GRAPH_THREADS) {
+                    const int j = base + tid;
+                    const uint64_t m = __builtin_amdgcn_ballot_w64(j < len && !(li(cur)[j] & EXPANDED));
+                    if (lane == 0) um[wave] = m;
+                    lds_barrier();
 #pragma unroll
-                for (int w = 0; w < GRAPH_WAVES; ++w) {
-                    const uint64_t mw = um[w];
-                    if (mw != 0 && p2 < 0) p2 = base + w * 64 + __builtin_ctzll(mw);
+                    for (int w = 0; w < GRAPH_WAVES; ++w) {
+                        const uint64_t mw = um[w];
+                        if (mw != 0 && p2 < 0) p2 = base + w * 64 + __builtin_ctzll(mw);
+                    }
+                    if (p2 >= 0) break;
+                    lds_barrier();                        // um is rewritten in the next round
                 }
-                if (p2 >= 0) break;
-                lds_barrier();                            // um is rewritten in the next round
-            }
-            if (p2 >= 0) {
-                node2 = __builtin_amdgcn_readfirstlane((int)(li(cur)[p2] & ~EXPANDED));
-                s2 = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(ls(cur)[p2])));
+                if (p2 >= 0) {
+                    node2 = __builtin_amdgcn_readfirstlane((int)(li(cur)[p2] & ~EXPANDED));
+                    s2 = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(ls(cur)[p2])));
+                }
             }
         }
         // Read-ahead: the runner-up is the most likely next expansion, so its adjacency row is
