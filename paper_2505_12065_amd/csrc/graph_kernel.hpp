@@ -338,10 +338,11 @@ __global__ __launch_bounds__(GRAPH_THREADS, 2) void graph_search_kernel(
 
     // neighbour `grp` of node nd: duplicates within the row and ids the cache knows are dropped,
     // the row of a remaining one is requested
-    auto request = [&](int nd) {
+    // (in two steps, so that the merge can be put between them when the row has to come from the graph)
+    int o4[4];                                            // 4 of the row's ids per lane, for the duplicate test
+    auto request_row = [&](int nd) {
         const int have = aid0 == nd ? 0 : (aid1 == nd ? 1 : -1);
         const int slot = grp;
-        int o4[4];
         const int vslot = min(slot, R - 1);
         if (have >= 0) {
             // (through a pointer that names the LDS address space: with plain pointers the compiler
@@ -360,6 +361,9 @@ __global__ __launch_bounds__(GRAPH_THREADS, 2) void graph_search_kernel(
 #pragma unroll
             for (int t = 0; t < 4; ++t) o4[t] = row[min(sub * 4 + t, R - 1)];
         }
+    };
+    auto request_rest = [&] {
+        const int slot = grp;
         if (slot >= R) v = -1;
         int dup = 0;
 #pragma unroll
@@ -376,7 +380,8 @@ __global__ __launch_bounds__(GRAPH_THREADS, 2) void graph_search_kernel(
             seen = __hip_atomic_load(&seen_bits[v >> 5], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         if (fresh) row_issue(v, x);
     };
-    request(node);
+    request_row(node);
+    request_rest();
 
     for (;;) {
         // the runner-up: first unexpanded entry other than p (everything before p is expanded)
@@ -551,7 +556,13 @@ __global__ __launch_bounds__(GRAPH_THREADS, 2) void graph_search_kernel(
         // (when an old entry stays the best, every new entry comes after it)
         const int next_p = best_l >= 0 ? __builtin_amdgcn_readlane(c_p, best_l) : p2;
 
-        if (!last) request(best_v);
+        // Its adjacency row is held in LDS when it was the runner-up; a new entry's row has to come
+        // from the graph, a global round trip, and then the merge goes first, under that load.
+        const bool held = aid0 == best_v || aid1 == best_v;
+        if (!last) {
+            request_row(best_v);
+            if (held) request_rest();
+        }
 
         // merge, as in the plain loop; the entry of the next node is marked as expanded on its way
         if (n_new != 0) {
@@ -611,6 +622,7 @@ __global__ __launch_bounds__(GRAPH_THREADS, 2) void graph_search_kernel(
         } else if (tid == 0 && !last) {
             li(cur)[p2] |= EXPANDED;                      // the list stays as it is
         }
+        if (!last && !held) request_rest();
         lds_barrier();
         if (NS) {
             ema = ema_s[0];
