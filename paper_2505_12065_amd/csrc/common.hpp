@@ -167,6 +167,34 @@ __device__ __forceinline__ float dot_chunk<F32>(u4 x, u4 q, float acc) {
     return acc;
 }
 
+// The same with four accumulators, one per 4 bytes of the chunk: four independent chains, for
+// callers whose lanes add up many chunks one after the other (a dependent chain of dot
+// instructions issues several times slower than independent ones).  The caller adds the four.
+template <class T>
+__device__ __forceinline__ void dot_chunk4(u4 x, u4 q, f4 &acc);
+
+template <>
+__device__ __forceinline__ void dot_chunk4<F16>(u4 x, u4 q, f4 &acc) {
+    const h8 a = __builtin_bit_cast(h8, x), b = __builtin_bit_cast(h8, q);
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+        acc[i] = __builtin_amdgcn_fdot2(h2{a[2 * i], a[2 * i + 1]}, h2{b[2 * i], b[2 * i + 1]}, acc[i], false);
+}
+
+template <>
+__device__ __forceinline__ void dot_chunk4<BF16>(u4 x, u4 q, f4 &acc) {
+    const b8 a = __builtin_bit_cast(b8, x), b = __builtin_bit_cast(b8, q);
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+        acc[i] = __builtin_amdgcn_fdot2_f32_bf16(bf2{a[2 * i], a[2 * i + 1]}, bf2{b[2 * i], b[2 * i + 1]}, acc[i], false);
+}
+
+template <>
+__device__ __forceinline__ void dot_chunk4<F32>(u4 x, u4 q, f4 &acc) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) acc[i] = fmaf(__uint_as_float(x[i]), __uint_as_float(q[i]), acc[i]);
+}
+
 // ---- MFMA ---------------------------------------------------------------------------------
 // D[16x16] += A[16x32] * B[32x16].  Lane l supplies A[l % 16][8*(l/16) .. +8) and
 // B[8*(l/16) .. +8)[l % 16]; it receives D[4*(l/16) + i][l % 16], i = 0..3.

@@ -250,18 +250,19 @@ __global__ __launch_bounds__(GRAPH_THREADS, 2) void graph_search_kernel(
     };
     auto row_dots = [&](int v, u4 (&x)[16]) -> float {
         const char *rp = static_cast<const char *>(X) + (size_t)v * nch * 16;
-        float acc = 0.f;
+        f4 acc = {0.f, 0.f, 0.f, 0.f};                    // four independent chains, added at the end
         int lim = nch - sub;
         asm volatile("" : "+v"(lim));
 #pragma unroll
         for (int g = 0; g < 4; ++g)
             if ((g + 1) * 4 * LANES_PER_ROW <= nch) {      // the whole run is inside the row
 #pragma unroll
-                for (int u = 4 * g; u < 4 * g + 4; ++u) acc = dot_chunk<T>(x[u], qr[u], acc);
+                for (int u = 4 * g; u < 4 * g + 4; ++u) dot_chunk4<T>(x[u], qr[u], acc);
             } else if (g * 4 * LANES_PER_ROW < nch) {
 #pragma unroll
                 for (int u = 4 * g; u < 4 * g + 4; ++u) {
-                    const float t = dot_chunk<T>(x[u], qr[u], acc);
+                    f4 t = acc;
+                    dot_chunk4<T>(x[u], qr[u], t);
                     acc = u * LANES_PER_ROW < lim ? t : acc;
                 }
             }
@@ -283,12 +284,13 @@ __global__ __launch_bounds__(GRAPH_THREADS, 2) void graph_search_kernel(
                 if (cb + g * 4 * LANES_PER_ROW < nch) {
 #pragma unroll
                     for (int u = 4 * g; u < 4 * g + 4; ++u) {
-                        const float t = dot_chunk<T>(x[u], qv[u], acc);
+                        f4 t = acc;
+                        dot_chunk4<T>(x[u], qv[u], t);
                         acc = u * LANES_PER_ROW < lim ? t : acc;
                     }
                 }
         }
-        return group_sum(acc);
+        return group_sum((acc[0] + acc[1]) + (acc[2] + acc[3]));
     };
     auto score_row = [&](int v) -> float {
         u4 x[16];
