@@ -101,6 +101,23 @@ int ann_flat_search(const void *corpus, int64_t N, int32_t d,
                     const void *queries, int32_t B, int32_t k,
                     int32_t *ids, float *scores, void *stream);
 
+/* ann_flat_search_typed for callers that cannot allocate device memory: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same kernels,
+ * same results, but the workspace is a fixed array of ANN_STATIC_WORKSPACE_BYTES that is part of
+ * the library's code object (every device the library runs on holds it until the process ends),
+ * and the call never allocates, frees or grows anything and records no timing events.
+ *   - A search whose workspace (ann_flat_workspace_bytes) exceeds ANN_STATIC_WORKSPACE_BYTES is
+ *     rejected with ANN_ERR_INVALID; nothing is enqueued.  8 MiB covers k <= 4 at any of the
+ *     batch sizes used here (1 M x 768 fp16, B = 512, k = 3 needs 4.2 MB).
+ *   - All calls on one device share that device's array: they are safe one after the other on
+ *     one stream (or ordered by the caller across streams); calls that overlap on one device
+ *     race.  It does not share anything with the workspace of the other entry points.
+ *   - Nothing in the array has to survive between calls; each call writes what it reads. */
+#define ANN_STATIC_WORKSPACE_BYTES (8 * 1024 * 1024)
+int ann_flat_search_static(const void *corpus, int64_t N, int32_t d, int32_t dtype,
+                           const void *queries, int32_t B, int32_t k,
+                           int32_t *ids, float *scores, void *stream);
+
 /*
  * Approximate retrieval by best-first search over a proximity graph (Section
  * 2.1: graph-based ANN; Section 3.3: a candidate list with a best and a worst

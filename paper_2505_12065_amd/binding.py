@@ -24,7 +24,7 @@ EXPORTS = ("ann_version", "ann_last_error", "ann_flat_search_typed", "ann_flat_s
            "ann_set_default_dtype", "ann_flat_workspace_bytes", "ann_release_workspace",
            "ann_graph_search_nonstall_typed", "ann_graph_nonstall_workspace_bytes",
            "ann_graph_search_entries_typed", "ann_gather_ids", "ann_timing_enable", "ann_timing_read",
-           "ann_measure_mfma_rate", "ann_priority_order")
+           "ann_measure_mfma_rate", "ann_priority_order", "ann_flat_search_static")
 
 
 class AnnError(RuntimeError):
@@ -51,6 +51,7 @@ def lib() -> ctypes.CDLL:
         L.ann_last_error.restype = c.c_char_p
         L.ann_flat_search_typed.argtypes = [vp, i64, i32, i32, vp, i32, i32, vp, vp, vp]
         L.ann_flat_search.argtypes = [vp, i64, i32, vp, i32, i32, vp, vp, vp]
+        L.ann_flat_search_static.argtypes = [vp, i64, i32, i32, vp, i32, i32, vp, vp, vp]
         L.ann_graph_search_typed.argtypes = [vp, i64, i32, i32, vp, i32, i32, vp, i32, i32, i32, vp, vp, vp]
         L.ann_graph_search.argtypes = [vp, vp, i32, i32, vp, i32, i32, i32, vp, vp, vp]
         L.ann_register_corpus.argtypes = [vp, i64, i32, i32]
@@ -123,6 +124,24 @@ def ann_flat_search_typed(corpus: torch.Tensor, queries: torch.Tensor, k: int, *
     with torch.cuda.device(corpus.device):
         _check(lib().ann_flat_search_typed(corpus.data_ptr(), N, d, _DTYPES[corpus.dtype], queries.data_ptr(), B, k,
                                            ids.data_ptr(), scores.data_ptr(), _stream(stream)))
+    return ids, scores
+
+
+ANN_STATIC_WORKSPACE_BYTES = 8 * 1024 * 1024
+
+
+def ann_flat_search_static(corpus: torch.Tensor, queries: torch.Tensor, k: int, *, ids: torch.Tensor,
+                           scores: torch.Tensor, stream=None) -> Tuple[torch.Tensor, torch.Tensor]:
+    """Exact top-k through the entry point that allocates nothing: the caller brings ids and
+    scores, the workspace is the library's static array."""
+    _matrix(corpus, "corpus"), _matrix(queries, "queries")
+    if queries.dtype != corpus.dtype or queries.shape[1] != corpus.shape[1]:
+        raise ValueError("queries must have the corpus' element type and dimension")
+    (N, d), B = corpus.shape, queries.shape[0]
+    ids, scores = _outputs(B, k, corpus.device, ids, scores)
+    with torch.cuda.device(corpus.device):
+        _check(lib().ann_flat_search_static(corpus.data_ptr(), N, d, _DTYPES[corpus.dtype], queries.data_ptr(), B, k,
+                                            ids.data_ptr(), scores.data_ptr(), _stream(stream)))
     return ids, scores
 
 

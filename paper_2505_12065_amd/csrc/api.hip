@@ -32,12 +32,23 @@ int fail(int code, const char *fmt, ...) {
 
 constexpr int P_MAX = 2048;
 
+}  // namespace
+
+// Workspace of ann_flat_search_static: lives in the code object, so every device the library
+// runs on holds one copy until the process ends.  In host code this name is only a handle for
+// hipGetSymbolAddress; the device address is looked up once per device (device_state) and is
+// what every launch and every offset computation uses.
+static __device__ __align__(256) unsigned char scratch[ANN_STATIC_WORKSPACE_BYTES];
+
+namespace {
+
 struct DeviceState {
     int cus = 0;
     void *ws = nullptr;
     size_t ws_bytes = 0;
     void *vis = nullptr;          // visited bitsets of the non-stall graph search
     size_t vis_bytes = 0;
+    void *scratch_ptr = nullptr;  // this device's address of `scratch`
 };
 
 std::mutex g_mu;
@@ -53,6 +64,15 @@ int device_state(DeviceState **out) {
     if (st.cus == 0) {
         if (hipDeviceGetAttribute(&st.cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || st.cus <= 0)
             return fail(ANN_ERR_LAUNCH, "cannot query the compute-unit count of device %d", dev);
+    }
+    if (!st.scratch_ptr) {                       // device `dev` is current here
+        void *p = nullptr;
+        hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !p) {
+            (void)hipGetLastError();
+            return fail(ANN_ERR_LAUNCH, "cannot resolve the static workspace on device %d: %s", dev, hipGetErrorString(e));
+        }
+        st.scratch_ptr = p;
     }
     *out = &st;
     return ANN_OK;
@@ -80,6 +100,7 @@ int64_t visited_words(int64_t N) { return (N + 511) / 512 * 16; }
 // ---- optional event timing of the main kernels -----------------------------------------------
 struct TimedLaunch { hipEvent_t a, b; int kernel; };
 bool g_timing = false;
+bool g_timing_off = false;                 // set while an entry point that may not create events runs
 std::vector<TimedLaunch> g_timed;          // records of the current session
 std::vector<hipEvent_t> g_event_pool;      // events of earlier sessions, reused
 
@@ -99,7 +120,7 @@ struct TimedScope {
     hipStream_t stream;
     int index = -1;
     TimedScope(int kernel, hipStream_t s) : stream(s) {     // kernel < 0: not recorded
-        if (!g_timing || kernel < 0) return;
+        if (!g_timing || g_timing_off || kernel < 0) return;
         TimedLaunch t{pooled_event(), pooled_event(), kernel};
         if (!t.a || !t.b) return;
         if (hipEventRecord(t.a, stream) != hipSuccess) { (void)hipGetLastError(); return; }
@@ -494,7 +515,32 @@ int ann_flat_search_typed(const void *corpus, int64_t N, int32_t d, int32_t dtyp
 
 int ann_flat_search(const void *corpus, int64_t N, int32_t d, const void *queries, int32_t B, int32_t k,
                     int32_t *ids, float *scores, void *stream) {
-    return ann_flat_search_typed(corpus, N, d, g_default_dtype, queries, B, k, ids, scores, stream);
+    int dtype;
+    {
+        std::lock_guard<std::mutex> lock(g_mu);
+        dtype = g_default_dtype;
+    }
+    return ann_flat_search_typed(corpus, N, d, dtype, queries, B, k, ids, scores, stream);
+}
+
+int ann_flat_search_static(const void *corpus, int64_t N, int32_t d, int32_t dtype, const void *queries,
+                           int32_t B, int32_t k, int32_t *ids, float *scores, void *stream) {
+    if (B == 0) return ANN_OK;
+    if (int rc = check_common(corpus, N, d, dtype, queries, B, k, ids, scores)) return rc;
+    if (k > ANN_K_MAX) return fail(ANN_ERR_INVALID, "k = %d exceeds ANN_K_MAX = %d", k, ANN_K_MAX);
+    std::lock_guard<std::mutex> lock(g_mu);
+    DeviceState *st = nullptr;
+    if (int rc = device_state(&st)) return rc;
+    const FlatPlan pl = flat_plan(st->cus, N, d, dtype, B, k);
+    if (dtype != ANN_F32 && pl.nqg_max < 1) return fail(ANN_ERR_INVALID, "d = %d too large for LDS", d);
+    if (pl.ws_bytes > (size_t)ANN_STATIC_WORKSPACE_BYTES)
+        return fail(ANN_ERR_INVALID, "this search needs %zu bytes of workspace, the static one holds %d",
+                    pl.ws_bytes, ANN_STATIC_WORKSPACE_BYTES);
+    g_timing_off = true;                                  // event pairs would have to be created
+    const int rc = flat_search_run(pl, corpus, N, d, dtype, queries, B, k, ids, scores,
+                                   static_cast<Cand *>(st->scratch_ptr), static_cast<hipStream_t>(stream));
+    g_timing_off = false;
+    return rc;
 }
 
 static int check_graph(const void *corpus, int64_t N, int32_t d, int32_t dtype, const int32_t *graph, int32_t R,
