@@ -54,12 +54,12 @@ def _load():
                                            c.c_int32, c.c_int32, c.c_void_p, c.c_void_p, c.c_void_p, c.c_int]
         lib.oracle_graph_search.restype = c.c_int
         lib.oracle_graph_search.argtypes = [c.c_void_p, c.c_int64, c.c_int32, c.c_int, c.c_void_p, c.c_int32,
-                                            c.c_int32, c.c_void_p, c.c_int32, c.c_int32, c.c_int32,
+                                            c.c_int32, c.c_void_p, c.c_int32, c.c_void_p, c.c_int32, c.c_int32, c.c_int32,
                                             c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_int]
         lib.oracle_graph_search_nonstall.restype = c.c_int
         lib.oracle_graph_search_nonstall.argtypes = [c.c_void_p, c.c_int64, c.c_int32, c.c_int, c.c_void_p, c.c_int32,
-                                                     c.c_int32, c.c_void_p, c.c_int32, c.c_int32, c.c_int32,
-                                                     c.c_float, c.c_int32, c.c_int64, c.c_int64,
+                                                     c.c_int32, c.c_void_p, c.c_int32, c.c_void_p, c.c_int32, c.c_int32, c.c_int32,
+                                                     c.c_float, c.c_int32, c.c_int, c.c_int64, c.c_int64,
                                                      c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_int]
         lib.oracle_priority_order.restype = c.c_int
         lib.oracle_priority_order.argtypes = [c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_int32, c.c_int32,
@@ -113,9 +113,25 @@ def flat_search(corpus, queries, k: int, *, dtype: Optional[str] = None,
     return ids, sc, sc64
 
 
-def graph_search(corpus, graph, entry: int, queries, k: int, ef: int, *, dtype: Optional[str] = None,
-                 n_threads: int = 0):
-    """Best-first graph search.  Returns (ids, scores fp32, scores fp64, n_dist, n_expand)."""
+def _entries(entries, B: int):
+    """None, or the per-query entry nodes as a contiguous int32 [B, E] array."""
+    if entries is None:
+        return None, 0, 0
+    e = np.ascontiguousarray(entries, dtype=np.int32)
+    if e.ndim == 1:
+        e = e.reshape(B, 1)
+    if e.ndim != 2 or e.shape[0] != B or e.shape[1] < 1:
+        raise ValueError("entries [B] or [B, E] expected")
+    return e, e.ctypes.data, e.shape[1]
+
+
+RQ_FORMS = {"node": 0, "expansion": 1}
+
+
+def graph_search(corpus, graph, entry: int, queries, k: int, ef: int, *, entries=None,
+                 dtype: Optional[str] = None, n_threads: int = 0):
+    """Best-first graph search from the node `entry`, or, with `entries` ([B] or [B, E]), from
+    each query's own entry nodes.  Returns (ids, scores fp32, scores fp64, n_dist, n_expand)."""
     corpus, queries, code = _prep(corpus, queries, dtype)
     graph = np.ascontiguousarray(graph, dtype=np.int32)
     N, d = corpus.shape
@@ -127,8 +143,9 @@ def graph_search(corpus, graph, entry: int, queries, k: int, ef: int, *, dtype: 
     sc64 = np.empty((B, k), np.float64)
     nd = np.empty(B, np.int64)
     ne = np.empty(B, np.int64)
+    keep, e_ptr, E = _entries(entries, B)
     rc = _load().oracle_graph_search(corpus.ctypes.data, N, d, code, graph.ctypes.data, graph.shape[1],
-                                     entry, queries.ctypes.data, B, k, ef, ids.ctypes.data,
+                                     entry, e_ptr, E, queries.ctypes.data, B, k, ef, ids.ctypes.data,
                                      sc.ctypes.data, sc64.ctypes.data, nd.ctypes.data, ne.ctypes.data,
                                      n_threads)
     if rc != 0:
@@ -137,9 +154,12 @@ def graph_search(corpus, graph, entry: int, queries, k: int, ef: int, *, dtype: 
 
 
 def graph_search_nonstall(corpus, graph, entry: int, queries, k: int, ef: int, *, tau: float = 0.9,
-                          window: int = 500, ready_from: int = 0, max_expand: int = 0,
-                          dtype: Optional[str] = None, n_threads: int = 0):
+                          window: int = 500, form: str = "expansion", ready_from: int = 0, max_expand: int = 0,
+                          entries=None, dtype: Optional[str] = None, n_threads: int = 0):
     """Best-first graph search with the maturity (non-stall) exit of Section 3.3.
+    form "node": best / worst of the candidate list as it stands when each node is scored (binary64);
+    form "expansion": as it stands when the expansion starts, binary32 decision (the form a search that
+    scores a node's neighbours together computes; the GPU library is compared with this one).
     Returns (ids, scores fp32, scores fp64, stats int32 [B,3] = (early, n_dist, n_expand), ema fp32 [B])."""
     corpus, queries, code = _prep(corpus, queries, dtype)
     graph = np.ascontiguousarray(graph, dtype=np.int32)
@@ -152,8 +172,10 @@ def graph_search_nonstall(corpus, graph, entry: int, queries, k: int, ef: int, *
     sc64 = np.empty((B, k), np.float64)
     stats = np.empty((B, 3), np.int32)
     ema = np.empty(B, np.float32)
+    keep, e_ptr, E = _entries(entries, B)
     rc = _load().oracle_graph_search_nonstall(corpus.ctypes.data, N, d, code, graph.ctypes.data, graph.shape[1], entry,
-                                              queries.ctypes.data, B, k, ef, tau, window, ready_from, max_expand,
+                                              e_ptr, E, queries.ctypes.data, B, k, ef, tau, window, RQ_FORMS[form],
+                                              ready_from, max_expand,
                                               ids.ctypes.data, sc.ctypes.data, sc64.ctypes.data, stats.ctypes.data,
                                               ema.ctypes.data, n_threads)
     if rc != 0:

@@ -173,7 +173,9 @@ int oracle_flat_search(const void *corpus, int64_t N, int32_t d, int dtype,
  * Graph retrieval: deterministic best-first search with a candidate list of at
  * most ef entries.
  *
- *   visited = {entry};  L = [(score(entry), entry, unexpanded)]
+ *   visited = {};  L = []
+ *   for each entry node in the order given: skip ids outside [0, N) and ids already
+ *           visited; otherwise mark visited, score it and put it into L by the rule below
  *   repeat: p = first unexpanded element of L (L is kept in order, so this is
  *           the best unexpanded candidate, ties to the lower id); stop if none
  *           mark p expanded
@@ -183,69 +185,93 @@ int oracle_flat_search(const void *corpus, int64_t N, int32_t d, int dtype,
  *           L is cut back to ef entries
  *   result: the first k elements of L, padded with (id -1, score -inf).
  *
+ * Entry nodes: `entries` == NULL means every query starts from the one node `entry`
+ * (E is ignored); otherwise query b starts from entries[b*E .. b*E + E), E >= 1 (a coarse
+ * index in front of the graph, such as HNSW's upper layers named in Section 2.1, hands the
+ * search one or several starting points; the paper does not say how many).
  * A node is marked visited when it is first scored, not when it is expanded.
+ * A node whose score is NaN is scored, counted and marked visited like any other but never
+ * enters L (no order relation holds for it).
  * n_dist[b] / n_expand[b] (optional) count scored nodes and expansions.
  * Returns 0, or -1 on bad arguments / allocation failure.
  */
+typedef struct {
+    scored_t *L;
+    uint8_t *expanded;
+    int32_t len, ef;
+} list_t;
+
+/* Put (s, v) into the ordered list unless it is NaN, or the list is full and (s, v) does not
+ * precede its last element.  Returns 1 if it went in. */
+static int list_offer(list_t *l, double s, int32_t v)
+{
+    if (s != s) return 0;
+    if (l->len == l->ef && !precedes(s, v, l->L[l->len - 1].s, l->L[l->len - 1].id)) return 0;
+    int32_t pos = l->len;               /* insertion point that keeps L in order */
+    while (pos > 0 && precedes(s, v, l->L[pos - 1].s, l->L[pos - 1].id)) --pos;
+    for (int32_t i = l->len; i > pos; --i) { l->L[i] = l->L[i - 1]; l->expanded[i] = l->expanded[i - 1]; }
+    l->L[pos].s = s; l->L[pos].id = v; l->expanded[pos] = 0;
+    if (l->len < l->ef) ++l->len;       /* otherwise the old worst fell off the end */
+    return 1;
+}
+
 int oracle_graph_search(const void *corpus, int64_t N, int32_t d, int dtype,
                         const int32_t *graph, int32_t R, int32_t entry,
+                        const int32_t *entries, int32_t E,
                         const void *queries, int32_t B, int32_t k, int32_t ef,
                         int32_t *ids, float *scores, double *scores64,
                         int64_t *n_dist, int64_t *n_expand, int threads)
 {
     if (!corpus || !graph || !queries || !ids || !scores || N < 1 || d < 1 || R < 1 ||
-        B < 1 || k < 1 || ef < k || entry < 0 || entry >= N)
+        B < 1 || k < 1 || ef < k)
         return -1;
+    if (entries ? E < 1 : (entry < 0 || entry >= N)) return -1;
     prepare_tables();
     int failed = 0;
 #pragma omp parallel for schedule(dynamic, 1) num_threads(use_threads(threads))
     for (int32_t b = 0; b < B; ++b) {
         double *q = malloc(sizeof(double) * (size_t)d);
         uint8_t *visited = calloc((size_t)N, 1);
-        scored_t *L = malloc(sizeof(scored_t) * (size_t)(ef + 1));
-        uint8_t *expanded = malloc((size_t)(ef + 1));
-        if (!q || !visited || !L || !expanded) {
-            failed = 1; free(q); free(visited); free(L); free(expanded); continue;
+        list_t l = { malloc(sizeof(scored_t) * (size_t)(ef + 1)), malloc((size_t)(ef + 1)), 0, ef };
+        if (!q || !visited || !l.L || !l.expanded) {
+            failed = 1; free(q); free(visited); free(l.L); free(l.expanded); continue;
         }
         for (int32_t j = 0; j < d; ++j) q[j] = load_value(queries, (int64_t)b * d + j, dtype);
 
-        int32_t len = 1;
-        int64_t dist_count = 1, expand_count = 0;
-        visited[entry] = 1;
-        L[0].s = score_row(corpus, entry, d, dtype, q);
-        L[0].id = entry;
-        expanded[0] = 0;
+        int64_t dist_count = 0, expand_count = 0;
+        const int32_t n_entries = entries ? E : 1;
+        for (int32_t e = 0; e < n_entries; ++e) {
+            const int32_t v = entries ? entries[(int64_t)b * E + e] : entry;
+            if (v < 0 || v >= N || visited[v]) continue;
+            visited[v] = 1;
+            ++dist_count;
+            list_offer(&l, score_row(corpus, v, d, dtype, q), v);
+        }
 
         for (;;) {
             int32_t p = 0;
-            while (p < len && expanded[p]) ++p;
-            if (p == len) break;
-            expanded[p] = 1;
+            while (p < l.len && l.expanded[p]) ++p;
+            if (p == l.len) break;
+            l.expanded[p] = 1;
             ++expand_count;
-            int32_t node = L[p].id;     /* copy: L may shift below */
+            int32_t node = l.L[p].id;     /* copy: L may shift below */
             for (int32_t slot = 0; slot < R; ++slot) {
                 int32_t v = graph[(int64_t)node * R + slot];
                 if (v < 0 || v >= N || visited[v]) continue;
                 visited[v] = 1;
                 ++dist_count;
-                double s = score_row(corpus, v, d, dtype, q);
-                if (len == ef && !precedes(s, v, L[len - 1].s, L[len - 1].id)) continue;
-                int32_t pos = len;      /* insertion point that keeps L in order */
-                while (pos > 0 && precedes(s, v, L[pos - 1].s, L[pos - 1].id)) --pos;
-                for (int32_t i = len; i > pos; --i) { L[i] = L[i - 1]; expanded[i] = expanded[i - 1]; }
-                L[pos].s = s; L[pos].id = v; expanded[pos] = 0;
-                if (len < ef) ++len;    /* otherwise the old worst fell off the end */
+                list_offer(&l, score_row(corpus, v, d, dtype, q), v);
             }
         }
         for (int32_t i = 0; i < k; ++i) {
-            int has = i < len;
-            ids[(int64_t)b * k + i] = has ? L[i].id : -1;
-            scores[(int64_t)b * k + i] = has ? (float)L[i].s : -INFINITY;
-            if (scores64) scores64[(int64_t)b * k + i] = has ? L[i].s : -INFINITY;
+            int has = i < l.len;
+            ids[(int64_t)b * k + i] = has ? l.L[i].id : -1;
+            scores[(int64_t)b * k + i] = has ? (float)l.L[i].s : -INFINITY;
+            if (scores64) scores64[(int64_t)b * k + i] = has ? l.L[i].s : -INFINITY;
         }
         if (n_dist) n_dist[b] = dist_count;
         if (n_expand) n_expand[b] = expand_count;
-        free(q); free(visited); free(L); free(expanded);
+        free(q); free(visited); free(l.L); free(l.expanded);
     }
     return failed ? -1 : 0;
 }
@@ -253,102 +279,133 @@ int oracle_graph_search(const void *corpus, int64_t N, int32_t d, int dtype,
 /*
  * Graph retrieval with the non-stall (maturity) exit of Section 3.3 / Appendix B.2.
  *
- * The search is the one above.  In addition every newly scored node t yields
+ * The search is the one above.  In addition every node t scored during an expansion yields
  *     RQ_t = (d_t - d_best) / (d_worst - d_best),     d = -score (a distance),
  * where d_best / d_worst belong to the best and worst entries of the candidate list.
  * RQ is smoothed by an exponential moving average with window W ("window size of
- * 500"; read as alpha = 2 / (W + 1), EMA_0 = 0), and the search stops as soon as
- * EMA > tau (0.9 in the paper) AND the engine is ready; otherwise it stops naturally.
+ * 500"; read as alpha = 2 / (W + 1), EMA_0 = 0, EMA <- EMA + alpha (RQ - EMA)), and the
+ * search stops as soon as EMA > tau (0.9 in the paper) AND the engine is ready; otherwise it
+ * stops naturally.  A node whose RQ is undefined (fewer than two list entries, or
+ * best == worst, or a NaN score) gives no sample; the entry nodes give none either (they are
+ * handed to the search, not discovered by it); the exit test is made after each expansion.
  *
- * Readings: the neighbours of one expansion are handled as a batch, so best and worst
- * are those of the list as it stood when the expansion started; neighbours enter the
- * average in slot order; a node whose RQ is undefined (fewer than two list entries, or
- * best == worst) is skipped; the exit test is made after each expansion.
+ * Section 3.3 takes best and worst from the list as it stands "currently", i.e. when node t
+ * is scored.  Two forms of that are stated here, selected by `form`:
+ *
+ *   ORACLE_RQ_PER_NODE (0): the wording taken literally for a search that scores one node
+ *     after the other: best / worst are those of the list at the moment t is scored, after
+ *     the earlier neighbours of the same expansion have gone in.  All in binary64.
+ *   ORACLE_RQ_PER_EXPANSION (1): the neighbours of one expansion are discovered together (one
+ *     step of the search); "currently" is then the list as that step starts, the same for all
+ *     of them, and the samples enter the average in slot order.  This is the form a search
+ *     that scores all neighbours of a node at once can compute, and the one the GPU library
+ *     is compared with.  Because the average decides an integer (the expansion at which the
+ *     search leaves), this form takes the decision in the precision of the implementation
+ *     under test, binary32: the score is rounded to binary32, RQ is one binary32 division,
+ *     the update one fused multiply-add.
+ *
+ * The two forms differ only inside an expansion that changes the list's best or worst entry
+ * while it is still being scored; tests/test_oracle_pins.py pins each by a hand trace and
+ * measures how often they leave at different expansions.
+ *
  * `ready_from` models the engine: it is ready from expansion count `ready_from` on
  * (0 = always, a huge value = never).  `max_expand` > 0 additionally stops the search
  * after that many expansions (used to check that an early exit returns exactly the
  * state the full search had at that point).
- *
- * Decision precision: RQ and the EMA are computed in binary32 with one fused
- * multiply-add per update, the same operations the GPU kernel uses, from the score
- * rounded to binary32.  stats[b] = {early exit (0/1), scored nodes, expansions}.
+ * stats[b] = {early exit (0/1), scored nodes, expansions}.
  */
+enum { ORACLE_RQ_PER_NODE = 0, ORACLE_RQ_PER_EXPANSION = 1 };
+
 int oracle_graph_search_nonstall(const void *corpus, int64_t N, int32_t d, int dtype,
                                  const int32_t *graph, int32_t R, int32_t entry,
+                                 const int32_t *entries, int32_t E,
                                  const void *queries, int32_t B, int32_t k, int32_t ef,
-                                 float tau, int32_t window, int64_t ready_from, int64_t max_expand,
+                                 float tau, int32_t window, int form, int64_t ready_from, int64_t max_expand,
                                  int32_t *ids, float *scores, double *scores64,
                                  int32_t *stats, float *ema_out, int threads)
 {
     if (!corpus || !graph || !queries || !ids || !scores || N < 1 || d < 1 || R < 1 ||
-        B < 1 || k < 1 || ef < k || entry < 0 || entry >= N || window < 1)
+        B < 1 || k < 1 || ef < k || window < 1)
         return -1;
+    if (entries ? E < 1 : (entry < 0 || entry >= N)) return -1;
+    if (form != ORACLE_RQ_PER_NODE && form != ORACLE_RQ_PER_EXPANSION) return -1;
     prepare_tables();
-    const float alpha = 2.0f / ((float)window + 1.0f);
+    const float alpha32 = 2.0f / ((float)window + 1.0f);
+    const double alpha64 = 2.0 / ((double)window + 1.0);
     int failed = 0;
 #pragma omp parallel for schedule(dynamic, 1) num_threads(use_threads(threads))
     for (int32_t b = 0; b < B; ++b) {
         double *q = malloc(sizeof(double) * (size_t)d);
         uint8_t *visited = calloc((size_t)N, 1);
-        scored_t *L = malloc(sizeof(scored_t) * (size_t)(ef + 1));
-        uint8_t *expanded = malloc((size_t)(ef + 1));
-        if (!q || !visited || !L || !expanded) {
-            failed = 1; free(q); free(visited); free(L); free(expanded); continue;
+        list_t l = { malloc(sizeof(scored_t) * (size_t)(ef + 1)), malloc((size_t)(ef + 1)), 0, ef };
+        if (!q || !visited || !l.L || !l.expanded) {
+            failed = 1; free(q); free(visited); free(l.L); free(l.expanded); continue;
         }
         for (int32_t j = 0; j < d; ++j) q[j] = load_value(queries, (int64_t)b * d + j, dtype);
 
-        int32_t len = 1, early = 0;
-        int64_t dist_count = 1, expand_count = 0;
-        float ema = 0.0f;
-        visited[entry] = 1;
-        L[0].s = score_row(corpus, entry, d, dtype, q);
-        L[0].id = entry;
-        expanded[0] = 0;
+        int32_t early = 0;
+        int64_t dist_count = 0, expand_count = 0;
+        float ema32 = 0.0f;             /* per-expansion form */
+        double ema64 = 0.0;             /* per-node form */
+        const int32_t n_entries = entries ? E : 1;
+        for (int32_t e = 0; e < n_entries; ++e) {
+            const int32_t v = entries ? entries[(int64_t)b * E + e] : entry;
+            if (v < 0 || v >= N || visited[v]) continue;
+            visited[v] = 1;
+            ++dist_count;
+            list_offer(&l, score_row(corpus, v, d, dtype, q), v);
+        }
 
         for (;;) {
             int32_t p = 0;
-            while (p < len && expanded[p]) ++p;
-            if (p == len) break;
+            while (p < l.len && l.expanded[p]) ++p;
+            if (p == l.len) break;
             if (max_expand > 0 && expand_count >= max_expand) break;
-            expanded[p] = 1;
+            l.expanded[p] = 1;
             ++expand_count;
-            int32_t node = L[p].id;
-            /* best and worst of the list as this expansion starts */
-            const int have_range = len >= 2;
-            const float s_best = (float)L[0].s, s_worst = (float)L[len - 1].s;
+            int32_t node = l.L[p].id;
+            /* per-expansion form: best and worst of the list as this expansion starts */
+            const int start_range = l.len >= 2;
+            const float start_best = (float)l.L[0].s, start_worst = (float)l.L[l.len - 1].s;
             for (int32_t slot = 0; slot < R; ++slot) {
                 int32_t v = graph[(int64_t)node * R + slot];
                 if (v < 0 || v >= N || visited[v]) continue;
                 visited[v] = 1;
                 ++dist_count;
                 double s = score_row(corpus, v, d, dtype, q);
-                if (have_range && s_best != s_worst) {
-                    /* (d_t - d_best) / (d_worst - d_best) with d = -score */
-                    const float rq = (s_best - (float)s) / (s_best - s_worst);
-                    ema = fmaf(alpha, rq - ema, ema);
+                if (s == s) {
+                    if (form == ORACLE_RQ_PER_EXPANSION) {
+                        if (start_range && start_best != start_worst) {
+                            /* (d_t - d_best) / (d_worst - d_best) with d = -score */
+                            const float rq = (start_best - (float)s) / (start_best - start_worst);
+                            ema32 = fmaf(alpha32, rq - ema32, ema32);
+                        }
+                    } else {
+                        const double d_t = -s, d_best = -l.L[0].s, d_worst = -l.L[l.len - 1].s;
+                        if (l.len >= 2 && d_worst != d_best) {
+                            const double rq = (d_t - d_best) / (d_worst - d_best);
+                            ema64 = ema64 + alpha64 * (rq - ema64);
+                        }
+                    }
                 }
-                if (len == ef && !precedes(s, v, L[len - 1].s, L[len - 1].id)) continue;
-                int32_t pos = len;
-                while (pos > 0 && precedes(s, v, L[pos - 1].s, L[pos - 1].id)) --pos;
-                for (int32_t i = len; i > pos; --i) { L[i] = L[i - 1]; expanded[i] = expanded[i - 1]; }
-                L[pos].s = s; L[pos].id = v; expanded[pos] = 0;
-                if (len < ef) ++len;
+                list_offer(&l, s, v);
             }
-            if (ema > tau && expand_count >= ready_from) { early = 1; break; }
+            const int mature = form == ORACLE_RQ_PER_EXPANSION ? ema32 > tau : ema64 > (double)tau;
+            if (mature && expand_count >= ready_from) { early = 1; break; }
         }
         for (int32_t i = 0; i < k; ++i) {
-            int has = i < len;
-            ids[(int64_t)b * k + i] = has ? L[i].id : -1;
-            scores[(int64_t)b * k + i] = has ? (float)L[i].s : -INFINITY;
-            if (scores64) scores64[(int64_t)b * k + i] = has ? L[i].s : -INFINITY;
+            int has = i < l.len;
+            ids[(int64_t)b * k + i] = has ? l.L[i].id : -1;
+            scores[(int64_t)b * k + i] = has ? (float)l.L[i].s : -INFINITY;
+            if (scores64) scores64[(int64_t)b * k + i] = has ? l.L[i].s : -INFINITY;
         }
         if (stats) {
             stats[(int64_t)b * 3 + 0] = early;
             stats[(int64_t)b * 3 + 1] = (int32_t)dist_count;
             stats[(int64_t)b * 3 + 2] = (int32_t)expand_count;
         }
-        if (ema_out) ema_out[b] = ema;
-        free(q); free(visited); free(L); free(expanded);
+        if (ema_out) ema_out[b] = form == ORACLE_RQ_PER_EXPANSION ? ema32 : (float)ema64;
+        free(q); free(visited); free(l.L); free(l.expanded);
     }
     return failed ? -1 : 0;
 }

@@ -61,6 +61,81 @@ def compare_topk(g_ids, g_sc, o_ids, o_sc64, corpus_np, queries_np, dtype=None, 
     return strict, B - strict, B
 
 
+NEAR_TIE = 1e-6   # two fp64 oracle scores closer than this may be ordered the other way round in fp32
+
+
+def walk(score_of, graph_row, N, entries, k, ef, max_expand=0):
+    """The best-first search written once more, in Python, over a score function (used only to
+    explain a trajectory that differs from the oracle's, never as the expected value of a test).
+    Returns (top-k ids, n_dist, n_expand, {node: score})."""
+    import bisect
+    scored, L, expanded = {}, [], set()          # L: sorted list of (-score, id)
+    n_expand = 0
+
+    def offer(v):
+        s = scored[v] = score_of(v)
+        if s != s:
+            return
+        key = (-s, v)
+        if len(L) == ef and not key < L[-1]:
+            return
+        bisect.insort(L, key)
+        if len(L) > ef:
+            L.pop()
+
+    for e in entries:
+        if 0 <= e < N and e not in scored:
+            offer(int(e))
+    while True:
+        nxt = next((key for key in L if key[1] not in expanded), None)
+        if nxt is None or (max_expand and n_expand >= max_expand):
+            break
+        expanded.add(nxt[1])
+        n_expand += 1
+        for v in graph_row(nxt[1]):
+            v = int(v)
+            if 0 <= v < N and v not in scored:
+                offer(v)
+    return [key[1] for key in L[:k]], len(scored), n_expand, scored
+
+
+def explain_divergence(xn, gn, qn, b, name, entries, k, ef, o_ids, o_counters, g_ids, g_counters, tie=NEAR_TIE):
+    """A GPU search whose counters (n_dist, n_expand) differ from the oracle's is accepted only if
+    it is the oracle's search with the order of one or two pairs of near-tied nodes (fp64 scores
+    closer than `tie`) reversed: the pairs are looked for among everything the oracle's walk scored,
+    each is tried, and the walk that results must reproduce the GPU's ids and counters exactly.
+    Returns [(node a, node b, |score gap|), ...]; raises AssertionError when no such pair exists."""
+    import itertools
+    N = xn.shape[0]
+    memo = {}
+
+    def base(v):
+        if v not in memo:
+            memo[v] = oracle.score(xn, qn, b, v, name)
+        return memo[v]
+
+    row = lambda v: gn[v]
+    ids0, nd0, ne0, scored = walk(base, row, N, entries, k, ef)
+    assert (ids0, nd0, ne0) == ([i for i in o_ids if i >= 0], o_counters[0], o_counters[1]), \
+        ("the explaining walk must be the oracle's", b, ids0, nd0, ne0, o_ids, o_counters)
+    order = sorted((s, v) for v, s in scored.items() if s == s)
+    near = [(order[i][1], order[i + 1][1], order[i + 1][0] - order[i][0])
+            for i in range(len(order) - 1) if order[i + 1][0] - order[i][0] < tie]
+    want = ([i for i in g_ids if i >= 0], g_counters[0], g_counters[1])
+    for n_swaps in (1, 2):
+        for combo in itertools.combinations(near, n_swaps):
+            swap = {}
+            for a, c, _ in combo:
+                swap[a], swap[c] = c, a
+            if len(swap) != 2 * n_swaps:
+                continue
+            got = walk(lambda v: base(swap.get(v, v)), row, N, entries, k, ef)
+            if (sorted(got[0]), got[1], got[2]) == (sorted(want[0]), want[1], want[2]):
+                return [(a, c, gap) for a, c, gap in combo]
+    raise AssertionError(f"query {b}: GPU counters {g_counters} differ from the oracle's {o_counters} and no "
+                         f"near-tie (< {tie}) among {len(near)} candidate pairs explains it")
+
+
 def compare_nonstall(gpu, o, xn, gn, qn, name, entry, k, ef, tau, window, max_off=None):
     """GPU (ids, scores, stats, ema) against the oracle's non-stall result (ids, sc, sc64, stats, ema).
     Queries with the same (early, scored, expansions) are compared list by list.  A query that
@@ -78,10 +153,14 @@ def compare_nonstall(gpu, o, xn, gn, qn, name, entry, k, ef, tau, window, max_of
         assert np.allclose(ema[same], o_ema[same], rtol=5e-4, atol=5e-4)
     for b in off:
         if stats[b, 0] == 0 and o_stats[b, 0] == 0:
-            # both stopped naturally: a near-tie ordered by fp32 rounding sent the two searches through
-            # slightly different expansions; the lists must still agree under the near-tie rule
+            # both stopped naturally after different walks: accepted only if reversing a near-tie of the
+            # oracle's walk (two scored nodes closer than NEAR_TIE in fp64) gives exactly the GPU's walk
             compare_topk(ids[b:b + 1], sc[b:b + 1], o_ids[b:b + 1], o_sc64[b:b + 1], xn, qn, dtype=name, rows=[b])
-            assert abs(int(stats[b, 1]) - int(o_stats[b, 1])) <= max(64, o_stats[b, 1] // 20), (b, stats[b], o_stats[b])
+            pairs = explain_divergence(xn, gn, qn, b, name, [entry], k, ef, o_ids[b].tolist(),
+                                       (int(o_stats[b, 1]), int(o_stats[b, 2])), ids[b].tolist(),
+                                       (int(stats[b, 1]), int(stats[b, 2])))
+            print(f"  query {b}: walk differs from the oracle's at a near-tie: " +
+                  ", ".join(f"nodes {a}/{c} gap {gap:.2e}" for a, c, gap in pairs), flush=True)
             continue
         cut = oracle.graph_search_nonstall(xn, gn, entry, qn[b:b + 1], k, ef, tau=np.inf, window=window,
                                            max_expand=int(stats[b, 2]), dtype=name)

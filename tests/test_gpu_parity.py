@@ -10,7 +10,7 @@ import torch
 import oracle
 import paper_2505_12065_amd as ann
 from paper_2505_12065_amd import synth
-from parity import TOL, compare_topk, np_dtype_name, recall, to_np
+from parity import TOL, compare_topk, explain_divergence, np_dtype_name, recall, to_np
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
@@ -284,9 +284,16 @@ def test_graph_long_lists(ef, R, dtype):
     say(f"  strict {strict}/{n}, oracle expansions {ne.mean():.0f}, scored {nd.mean():.0f}")
     assert strict >= n - 1
     # the counters of the long-list path through the non-stall entry point are the oracle's
-    _, _, stats, _ = ann.ann_graph_search_nonstall_typed(c.x.to(DEV), g.to(DEV), 7, q.to(DEV), 5, ef, tau=float("inf"))
+    ids_ns, _, stats, _ = ann.ann_graph_search_nonstall_typed(c.x.to(DEV), g.to(DEV), 7, q.to(DEV), 5, ef, tau=float("inf"))
+    ids_ns = ids_ns.cpu().numpy()
     st = stats.cpu().numpy()
-    assert np.abs(st[:, 1] - nd).max() <= max(8, nd.max() // 100) and np.abs(st[:, 2] - ne).max() <= max(4, ne.max() // 100)
+    for b in range(q.shape[0]):
+        if (int(st[b, 1]), int(st[b, 2])) == (int(nd[b]), int(ne[b])):
+            continue
+        # another walk than the oracle's: only the reversal of a near-tie (fp64 gap below 1e-6) may cause it
+        pairs = explain_divergence(to_np(c.x), g.numpy(), to_np(q), b, name, [7], 5, ef, o_ids[b].tolist(),
+                                   (int(nd[b]), int(ne[b])), ids_ns[b].tolist(), (int(st[b, 1]), int(st[b, 2])))
+        say(f"  query {b}: walk differs at a near-tie: " + ", ".join(f"nodes {a}/{c2} gap {gap:.2e}" for a, c2, gap in pairs))
 
 
 @pytest.mark.parametrize("ef,R,k", [(16, 8, 5), (200, 32, 10), (700, 32, 16), (48, 40, 7)])
