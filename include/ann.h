@@ -37,7 +37,9 @@
  *     Row b of ids/scores holds the first k entries in that order.  When fewer
  *     than k entries exist (graph search that reaches fewer than k nodes) the
  *     tail is id = -1, score = -inf.  Same inputs give bitwise-same outputs.
- *   - Scores that are NaN are never returned.
+ *   - Scores that are NaN are never returned: such a row never enters a top-k list or a
+ *     candidate list (in the graph search it is scored and marked visited like any other,
+ *     an entry node included, but is never listed or expanded).
  *   - Return value: ANN_OK, or a negative ANN_ERR_* code, in which case
  *     nothing was enqueued and no output was written.  ann_last_error() gives
  *     a message for the calling thread's last failure.
@@ -66,6 +68,7 @@ extern "C" {
 #define ANN_EF_MAX   16384   /* largest candidate list of the graph search (k <= ef) */
 #define ANN_R_MAX    256     /* largest graph out-degree */
 #define ANN_D_MAX    4096    /* largest embedding dimension */
+#define ANN_ENTRIES_MAX 32   /* most entry nodes per query of the graph search */
 #define ANN_REQUESTS_MAX 65536 /* largest request batch of ann_priority_order */
 
 /* Library version as major*10000 + minor*100 + patch. */
@@ -153,14 +156,25 @@ int ann_graph_search(const void *corpus, const int32_t *graph, int32_t R, int32_
                      const void *queries, int32_t B, int32_t k, int32_t ef,
                      int32_t *ids, float *scores, void *stream);
 
-/* ann_graph_search_typed with one entry node per query (Section 2.1: graph-based
- * approximate retrieval; the entry is where the best-first search starts, so a caller
- * with a coarse index, e.g. one representative per cluster found by ann_flat_search
- * over the representatives, starts each query next to its answer).
+/* ann_graph_search_typed with entry nodes of each query's own (Section 2.1: graph-based
+ * approximate retrieval; the index the paper uses, HNSW, reaches the layer searched here
+ * through coarser ones, i.e. every query starts from nodes chosen for it.  A caller with a
+ * coarse index, e.g. an exact search over one representative per cluster by ann_flat_search
+ * followed by ann_gather_ids, starts each query next to its answer).
  *
- *   entries   device, [B] int32 node ids.  A query whose entry is not in [0, N) gets
- *             k padding results (id -1, score -inf); that is not an error.
+ *   entries    device, [B, n_entries] int32 node ids, 1 <= n_entries <= ANN_ENTRIES_MAX.
+ *              The search starts with visited = the entries and the list = the entries in
+ *              order, cut to ef.  Ids outside [0, N) and ids named earlier in the row are left
+ *              out; a query with no usable entry gets k padding results (id -1, score -inf);
+ *              neither is an error.
  */
+int ann_graph_search_multi_typed(const void *corpus, int64_t N, int32_t d, int32_t dtype,
+                                 const int32_t *graph, int32_t R,
+                                 const int32_t *entries, int32_t n_entries,
+                                 const void *queries, int32_t B, int32_t k, int32_t ef,
+                                 int32_t *ids, float *scores, void *stream);
+
+/* The same with one entry node per query: entries is [B]. */
 int ann_graph_search_entries_typed(const void *corpus, int64_t N, int32_t d, int32_t dtype,
                                    const int32_t *graph, int32_t R, const int32_t *entries,
                                    const void *queries, int32_t B, int32_t k, int32_t ef,
@@ -185,8 +199,9 @@ int ann_gather_ids(const int32_t *table, int64_t M, const int32_t *idx, int64_t 
  * with an undefined RQ (best == worst) are skipped, the test follows the expansion.
  * RQ and the average are binary32.
  *
- *   entries        NULL, or device [B] per-query entry nodes used instead of `entry`
- *                  (as in ann_graph_search_entries_typed)
+ *   entries        NULL, or device [B, n_entries] per-query entry nodes used instead of `entry`
+ *   n_entries      (as in ann_graph_search_multi_typed; ignored when entries is NULL).  Entry
+ *                  nodes are given to the search, not discovered by it: they yield no RQ sample
  *   tau, window    threshold and EMA window (the paper uses 0.9 and 500); window >= 1
  *   engine_ready   device-visible int32 (device memory or pinned host memory) the host
  *                  may change while the call runs; read with system scope each time a
@@ -202,7 +217,7 @@ int ann_gather_ids(const int32_t *table, int64_t M, const int32_t *idx, int64_t 
 int ann_graph_search_nonstall_typed(const void *corpus, int64_t N, int32_t d, int32_t dtype,
                                     const int32_t *graph, int32_t R, int32_t entry,
                                     const void *queries, int32_t B, int32_t k, int32_t ef,
-                                    const int32_t *entries, float tau, int32_t window,
+                                    const int32_t *entries, int32_t n_entries, float tau, int32_t window,
                                     const int32_t *engine_ready,
                                     int32_t *ids, float *scores, int32_t *stats, float *ema,
                                     void *stream);
@@ -251,7 +266,8 @@ int ann_timing_read(int32_t kernel, int32_t *launches, double *total_ms);
  * T_{M,j} = min(M) + j/G (max(M) - min(M)); level[i] = the largest j with R[i] > T_{R,j} or
  * W[i] > T_{W,j} or C[i] > T_{C,j}, 0 if there is none.  order[] lists the requests in execution
  * order: levels from the highest down, inside a level by the current queueing time Wcur[i],
- * longest first (equal times in index order).  Thresholds are evaluated in binary64.
+ * longest first (equal times in index order; a NaN time counts as the shortest wait).  Thresholds are
+ * evaluated in binary64 exactly as written, every operation rounded once.
  *
  *   R, C, level, order   device int32 [n];   W, Wcur   device double [n]
  *   1 <= n <= ANN_REQUESTS_MAX, 1 <= G <= 1024 (the paper uses G = 6)

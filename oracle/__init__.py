@@ -34,7 +34,7 @@ _lib = None
 def build(force: bool = False) -> str:
     """Compile ann_oracle.c with gcc into oracle/libann_oracle.so."""
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
-        subprocess.check_call(["gcc", "-O2", "-fopenmp", "-fPIC", "-shared", "-std=c11",
+        subprocess.check_call(["gcc", "-O2", "-ffp-contract=off", "-fopenmp", "-fPIC", "-shared", "-std=c11",
                                "-Wall", "-Wextra", "-o", _LIB, _SRC, "-lm"])
     return _LIB
 

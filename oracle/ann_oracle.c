@@ -136,8 +136,9 @@ double oracle_score(const void *corpus, int32_t d, int dtype, int64_t row,
 
 /*
  * Exact retrieval.  ids[B,k], scores[B,k] (fp32), scores64[B,k] optional.
- * Fewer than k rows cannot happen (k <= N is required).  Returns 0, or -1 on
- * bad arguments / allocation failure.
+ * A row whose score is NaN has no place in the order and is left out; should fewer than
+ * k rows remain, the tail is (id -1, score -inf).  Returns 0, or -1 on bad arguments /
+ * allocation failure.
  */
 int oracle_flat_search(const void *corpus, int64_t N, int32_t d, int dtype,
                        const void *queries, int32_t B, int32_t k,
@@ -153,15 +154,20 @@ int oracle_flat_search(const void *corpus, int64_t N, int32_t d, int dtype,
         scored_t *all = malloc(sizeof(scored_t) * (size_t)N);
         if (!q || !all) { failed = 1; free(q); free(all); continue; }
         for (int32_t j = 0; j < d; ++j) q[j] = load_value(queries, (int64_t)b * d + j, dtype);
+        int64_t m = 0;                  /* rows with a score that can be ordered (not NaN) */
         for (int64_t n = 0; n < N; ++n) {
-            all[n].s = score_row(corpus, n, d, dtype, q);
-            all[n].id = (int32_t)n;
+            const double s = score_row(corpus, n, d, dtype, q);
+            if (s != s) continue;
+            all[m].s = s;
+            all[m].id = (int32_t)n;
+            ++m;
         }
-        qsort(all, (size_t)N, sizeof(scored_t), by_order);
+        qsort(all, (size_t)m, sizeof(scored_t), by_order);
         for (int32_t i = 0; i < k; ++i) {
-            ids[(int64_t)b * k + i] = all[i].id;
-            scores[(int64_t)b * k + i] = (float)all[i].s;
-            if (scores64) scores64[(int64_t)b * k + i] = all[i].s;
+            const int has = i < m;
+            ids[(int64_t)b * k + i] = has ? all[i].id : -1;
+            scores[(int64_t)b * k + i] = has ? (float)all[i].s : -INFINITY;
+            if (scores64) scores64[(int64_t)b * k + i] = has ? all[i].s : -INFINITY;
         }
         free(q);
         free(all);
@@ -417,9 +423,10 @@ int oracle_graph_search_nonstall(const void *corpus, int64_t N, int32_t d, int d
  * C_i context length.  For each metric M and level j in [0, G): T_{M,j} = min(M) + j/G (max(M) - min(M)).
  * level_i = the largest j with R_i > T_{R,j} or W_i > T_{W,j} or C_i > T_{C,j}; 0 if there is none.
  * Execution order: levels from the highest down; inside a level by the current queueing time
- * Wcur_i, longest first (reading: equal times in index order).
- * Arithmetic in binary64, the threshold as one fused multiply-add fma(j/G, max - min, min): the
- * GPU routine uses the same expression, so the integer decisions are taken in the same precision.
+ * Wcur_i, longest first (readings: equal times in index order; a time that is NaN counts as the
+ * shortest possible wait, -inf, so that every request has exactly one place).
+ * Arithmetic in binary64, the threshold exactly as Eq. 1-2 write it: min + (j/G) * (max - min),
+ * every operation rounded once (this file is compiled without floating-point contraction).
  */
 int oracle_priority_order(const int32_t *R, const double *W, const int32_t *C, const double *Wcur,
                           int32_t n, int32_t G, int32_t *level, int32_t *order)
@@ -436,15 +443,17 @@ int oracle_priority_order(const int32_t *R, const double *W, const int32_t *C, c
         int32_t best = 0;
         for (int32_t j = 0; j < G; ++j)
             for (int m = 0; m < 3; ++m)
-                if (v[m] > fma((double)j / (double)G, mx[m] - mn[m], mn[m])) best = j;
+                if (v[m] > mn[m] + ((double)j / (double)G) * (mx[m] - mn[m])) best = j;
         level[i] = best;
     }
     /* stable selection: position of i = number of requests that go before it */
     for (int32_t i = 0; i < n; ++i) {
         int32_t before = 0;
+        const double wi = Wcur[i] == Wcur[i] ? Wcur[i] : -INFINITY;
         for (int32_t j = 0; j < n; ++j) {
             if (j == i) continue;
-            if (level[j] > level[i] || (level[j] == level[i] && (Wcur[j] > Wcur[i] || (Wcur[j] == Wcur[i] && j < i))))
+            const double wj = Wcur[j] == Wcur[j] ? Wcur[j] : -INFINITY;
+            if (level[j] > level[i] || (level[j] == level[i] && (wj > wi || (wj == wi && j < i))))
                 ++before;
         }
         order[before] = i;

@@ -16,6 +16,7 @@ LIB_PATH = os.environ.get("ANN_LIBRARY_PATH", os.path.join(_HERE, "libann.so"))
 ANN_OK, ANN_ERR_INVALID, ANN_ERR_ALIGNMENT, ANN_ERR_UNKNOWN_CORPUS, ANN_ERR_LAUNCH, ANN_ERR_NOMEM = 0, -1, -2, -3, -4, -5
 ANN_F16, ANN_BF16, ANN_F32 = 0, 1, 2
 ANN_K_MAX, ANN_EF_MAX, ANN_R_MAX, ANN_D_MAX = 16, 16384, 256, 4096
+ANN_ENTRIES_MAX = 32
 
 _DTYPES = {torch.float16: ANN_F16, torch.bfloat16: ANN_BF16, torch.float32: ANN_F32}
 
@@ -24,7 +25,8 @@ EXPORTS = ("ann_version", "ann_last_error", "ann_flat_search_typed", "ann_flat_s
            "ann_set_default_dtype", "ann_flat_workspace_bytes", "ann_release_workspace",
            "ann_graph_search_nonstall_typed", "ann_graph_nonstall_workspace_bytes",
            "ann_graph_search_entries_typed", "ann_gather_ids", "ann_timing_enable", "ann_timing_read",
-           "ann_measure_mfma_rate", "ann_priority_order", "ann_flat_search_static")
+           "ann_measure_mfma_rate", "ann_priority_order", "ann_flat_search_static",
+           "ann_graph_search_multi_typed")
 
 
 class AnnError(RuntimeError):
@@ -59,8 +61,9 @@ def lib() -> ctypes.CDLL:
         L.ann_set_default_dtype.argtypes = [i32]
         L.ann_flat_workspace_bytes.argtypes = [i64, i32, i32, i32, i32]
         L.ann_flat_workspace_bytes.restype = i64
-        L.ann_graph_search_nonstall_typed.argtypes = [vp, i64, i32, i32, vp, i32, i32, vp, i32, i32, i32, vp,
+        L.ann_graph_search_nonstall_typed.argtypes = [vp, i64, i32, i32, vp, i32, i32, vp, i32, i32, i32, vp, i32,
                                                       c.c_float, i32, vp, vp, vp, vp, vp, vp]
+        L.ann_graph_search_multi_typed.argtypes = [vp, i64, i32, i32, vp, i32, vp, i32, vp, i32, i32, i32, vp, vp, vp]
         L.ann_graph_search_entries_typed.argtypes = [vp, i64, i32, i32, vp, i32, vp, vp, i32, i32, i32, vp, vp, vp]
         L.ann_gather_ids.argtypes = [vp, i64, vp, i64, vp, vp]
         L.ann_measure_mfma_rate.argtypes = [i32, i32, c.POINTER(c.c_double)]
@@ -204,9 +207,9 @@ def ann_graph_search_nonstall_typed(corpus: torch.Tensor, graph: torch.Tensor, e
         raise ValueError("stats must be a contiguous int32 [B, 3] device tensor")
     if ema.dtype != torch.float32 or tuple(ema.shape) != (B,) or not ema.is_contiguous() or not ema.is_cuda:
         raise ValueError("ema must be a contiguous float32 [B] device tensor")
-    entries_ptr = 0
+    entries_ptr, n_entries = 0, 0
     if entries is not None:
-        entries_ptr = _entries(entries, B).data_ptr()
+        entries_ptr, n_entries = _entries(entries, B).data_ptr(), (1 if entries.dim() == 1 else entries.shape[1])
     ready_ptr = 0
     if engine_ready is not None:
         if engine_ready.dtype != torch.int32 or engine_ready.numel() != 1 or \
@@ -216,17 +219,38 @@ def ann_graph_search_nonstall_typed(corpus: torch.Tensor, graph: torch.Tensor, e
     with torch.cuda.device(corpus.device):
         _check(lib().ann_graph_search_nonstall_typed(corpus.data_ptr(), N, d, _DTYPES[corpus.dtype], graph.data_ptr(),
                                                      graph.shape[1], int(entry), queries.data_ptr(), B, k, ef,
-                                                     entries_ptr, float(tau), int(window), ready_ptr, ids.data_ptr(),
+                                                     entries_ptr, n_entries, float(tau), int(window), ready_ptr, ids.data_ptr(),
                                                      scores.data_ptr(), stats.data_ptr(), ema.data_ptr(),
                                                      _stream(stream)))
     return ids, scores, stats, ema
 
 
 def _entries(entries: torch.Tensor, B: int) -> torch.Tensor:
-    if entries.dtype != torch.int32 or tuple(entries.shape) != (B,) or not entries.is_contiguous() or \
-            not entries.is_cuda:
-        raise ValueError("entries must be a contiguous int32 [B] device tensor")
+    ok_shape = tuple(entries.shape) == (B,) or (entries.dim() == 2 and entries.shape[0] == B and entries.shape[1] >= 1)
+    if entries.dtype != torch.int32 or not ok_shape or not entries.is_contiguous() or not entries.is_cuda:
+        raise ValueError("entries must be a contiguous int32 [B] or [B, E] device tensor")
     return entries
+
+
+def ann_graph_search_multi_typed(corpus: torch.Tensor, graph: torch.Tensor, entries: torch.Tensor,
+                                 queries: torch.Tensor, k: int, ef: int, *, ids=None, scores=None,
+                                 stream=None) -> Tuple[torch.Tensor, torch.Tensor]:
+    """Graph search with entries[B, E] entry nodes per query."""
+    _matrix(corpus, "corpus"), _matrix(queries, "queries")
+    if queries.dtype != corpus.dtype or queries.shape[1] != corpus.shape[1]:
+        raise ValueError("queries must have the corpus' element type and dimension")
+    (N, d), B = corpus.shape, queries.shape[0]
+    _graph(graph, N)
+    _entries(entries, B)
+    if entries.dim() != 2:
+        raise ValueError("entries must be [B, E]")
+    ids, scores = _outputs(B, k, corpus.device, ids, scores)
+    with torch.cuda.device(corpus.device):
+        _check(lib().ann_graph_search_multi_typed(corpus.data_ptr(), N, d, _DTYPES[corpus.dtype], graph.data_ptr(),
+                                                  graph.shape[1], entries.data_ptr(), entries.shape[1],
+                                                  queries.data_ptr(), B, k, ef, ids.data_ptr(), scores.data_ptr(),
+                                                  _stream(stream)))
+    return ids, scores
 
 
 def ann_graph_search_entries_typed(corpus: torch.Tensor, graph: torch.Tensor, entries: torch.Tensor,
@@ -238,7 +262,8 @@ def ann_graph_search_entries_typed(corpus: torch.Tensor, graph: torch.Tensor, en
         raise ValueError("queries must have the corpus' element type and dimension")
     (N, d), B = corpus.shape, queries.shape[0]
     _graph(graph, N)
-    _entries(entries, B)
+    if _entries(entries, B).dim() != 1:
+        raise ValueError("entries must be [B]")
     ids, scores = _outputs(B, k, corpus.device, ids, scores)
     with torch.cuda.device(corpus.device):
         _check(lib().ann_graph_search_entries_typed(corpus.data_ptr(), N, d, _DTYPES[corpus.dtype], graph.data_ptr(),

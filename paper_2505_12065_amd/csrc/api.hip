@@ -405,7 +405,9 @@ int ann_unregister_corpus(const void *corpus) {
 }
 
 int64_t ann_flat_workspace_bytes(int64_t N, int32_t d, int32_t dtype, int32_t B, int32_t k) {
-    if (N < 1 || d < 1 || d > ANN_D_MAX || B < 1 || k < 1 || k > ANN_K_MAX) return ANN_ERR_INVALID;
+    if (N < 1 || N > INT32_MAX || d < 1 || d > ANN_D_MAX || B < 1 || k < 1 || k > ANN_K_MAX || k > N) return ANN_ERR_INVALID;
+    if (dtype != ANN_F16 && dtype != ANN_BF16 && dtype != ANN_F32) return ANN_ERR_INVALID;
+    if ((d * elem_bytes(dtype)) % 16 != 0) return ANN_ERR_ALIGNMENT;
     std::lock_guard<std::mutex> lock(g_mu);
     DeviceState *st = nullptr;
     int cus = 256;
@@ -565,7 +567,7 @@ int64_t ann_graph_nonstall_workspace_bytes(int64_t N, int32_t B) {
 
 int ann_graph_search_nonstall_typed(const void *corpus, int64_t N, int32_t d, int32_t dtype, const int32_t *graph,
                                     int32_t R, int32_t entry, const void *queries, int32_t B, int32_t k, int32_t ef,
-                                    const int32_t *entries, float tau, int32_t window,
+                                    const int32_t *entries, int32_t n_entries, float tau, int32_t window,
                                     const int32_t *engine_ready, int32_t *ids, float *scores, int32_t *stats,
                                     float *ema, void *stream) {
     if (B == 0) return ANN_OK;                            // an empty batch: nothing to do
@@ -573,6 +575,8 @@ int ann_graph_search_nonstall_typed(const void *corpus, int64_t N, int32_t d, in
     if (int rc = check_graph(corpus, N, d, dtype, graph, R, entries ? 0 : entry, queries, B, k, ef, ids, scores, &L))
         return rc;
     if (reinterpret_cast<uintptr_t>(entries) & 3) return fail(ANN_ERR_ALIGNMENT, "entries must be 4-byte aligned");
+    if (entries && (n_entries < 1 || n_entries > ANN_ENTRIES_MAX))
+        return fail(ANN_ERR_INVALID, "n_entries = %d out of range [1, %d]", n_entries, ANN_ENTRIES_MAX);
     if (window < 1) return fail(ANN_ERR_INVALID, "window = %d must be at least 1", window);
     if (tau != tau) return fail(ANN_ERR_INVALID, "tau is not a number");
     if ((reinterpret_cast<uintptr_t>(engine_ready) | reinterpret_cast<uintptr_t>(stats) |
@@ -583,6 +587,7 @@ int ann_graph_search_nonstall_typed(const void *corpus, int64_t N, int32_t d, in
     if (int rc = device_state(&st)) return rc;
     NonStall ns;
     ns.entries = entries;
+    ns.n_entries = n_entries;
     ns.tau = tau;
     ns.alpha = 2.0f / ((float)window + 1.0f);
     ns.ready = engine_ready;
@@ -604,18 +609,19 @@ int ann_graph_search_nonstall_typed(const void *corpus, int64_t N, int32_t d, in
 // remembers, so they run on the kernel variant with the exact visited bitset, with an exit
 // threshold no average can exceed.
 static int graph_search_any(const void *corpus, int64_t N, int32_t d, int32_t dtype, const int32_t *graph, int32_t R,
-                            int32_t entry, const int32_t *entries, const void *queries, int32_t B, int32_t k,
+                            int32_t entry, const int32_t *entries, int32_t n_entries, const void *queries, int32_t B, int32_t k,
                             int32_t ef, int32_t *ids, float *scores, const GraphLds &L, hipStream_t s) {
     std::lock_guard<std::mutex> lock(g_mu);
     if (ef <= GRAPH_EF_DOUBLE) {
         TimedScope timed(ANN_KERNEL_GRAPH, s);
-        return check_launch("graph_search_kernel", launch_graph_search(dtype, corpus, N, d, graph, R, entry, entries,
+        return check_launch("graph_search_kernel", launch_graph_search(dtype, corpus, N, d, graph, R, entry, entries, n_entries,
                                                                        queries, B, k, ef, ids, scores, L, s));
     }
     DeviceState *st = nullptr;
     if (int rc = device_state(&st)) return rc;
     NonStall ns{};
     ns.entries = entries;
+    ns.n_entries = n_entries;
     ns.tau = INFINITY;
     ns.alpha = 0.f;
     ns.words = visited_words(N);
@@ -635,20 +641,28 @@ int ann_graph_search_typed(const void *corpus, int64_t N, int32_t d, int32_t dty
     if (B == 0) return ANN_OK;                            // an empty batch: nothing to do
     GraphLds L;
     if (int rc = check_graph(corpus, N, d, dtype, graph, R, entry, queries, B, k, ef, ids, scores, &L)) return rc;
-    return graph_search_any(corpus, N, d, dtype, graph, R, entry, nullptr, queries, B, k, ef, ids, scores, L,
+    return graph_search_any(corpus, N, d, dtype, graph, R, entry, nullptr, 0, queries, B, k, ef, ids, scores, L,
+                            static_cast<hipStream_t>(stream));
+}
+
+int ann_graph_search_multi_typed(const void *corpus, int64_t N, int32_t d, int32_t dtype, const int32_t *graph,
+                                 int32_t R, const int32_t *entries, int32_t n_entries, const void *queries, int32_t B,
+                                 int32_t k, int32_t ef, int32_t *ids, float *scores, void *stream) {
+    if (B == 0) return ANN_OK;                            // an empty batch: nothing to do
+    if (!entries) return fail(ANN_ERR_INVALID, "null entries pointer");
+    if (reinterpret_cast<uintptr_t>(entries) & 3) return fail(ANN_ERR_ALIGNMENT, "entries must be 4-byte aligned");
+    if (n_entries < 1 || n_entries > ANN_ENTRIES_MAX)
+        return fail(ANN_ERR_INVALID, "n_entries = %d out of range [1, %d]", n_entries, ANN_ENTRIES_MAX);
+    GraphLds L;
+    if (int rc = check_graph(corpus, N, d, dtype, graph, R, 0, queries, B, k, ef, ids, scores, &L)) return rc;
+    return graph_search_any(corpus, N, d, dtype, graph, R, 0, entries, n_entries, queries, B, k, ef, ids, scores, L,
                             static_cast<hipStream_t>(stream));
 }
 
 int ann_graph_search_entries_typed(const void *corpus, int64_t N, int32_t d, int32_t dtype, const int32_t *graph,
                                    int32_t R, const int32_t *entries, const void *queries, int32_t B, int32_t k,
                                    int32_t ef, int32_t *ids, float *scores, void *stream) {
-    if (B == 0) return ANN_OK;                            // an empty batch: nothing to do
-    if (!entries) return fail(ANN_ERR_INVALID, "null entries pointer");
-    if (reinterpret_cast<uintptr_t>(entries) & 3) return fail(ANN_ERR_ALIGNMENT, "entries must be 4-byte aligned");
-    GraphLds L;
-    if (int rc = check_graph(corpus, N, d, dtype, graph, R, 0, queries, B, k, ef, ids, scores, &L)) return rc;
-    return graph_search_any(corpus, N, d, dtype, graph, R, 0, entries, queries, B, k, ef, ids, scores, L,
-                            static_cast<hipStream_t>(stream));
+    return ann_graph_search_multi_typed(corpus, N, d, dtype, graph, R, entries, 1, queries, B, k, ef, ids, scores, stream);
 }
 
 int ann_gather_ids(const int32_t *table, int64_t M, const int32_t *idx, int64_t n, int32_t *out, void *stream) {

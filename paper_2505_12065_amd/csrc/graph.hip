@@ -23,7 +23,7 @@ GraphLds graph_lds_layout(int d, int elem_bytes, int R, int ef) {
         L.cache = off; off = up(off + (4u << bits));
         L.ctl = off; off = up(off + 16u);
         L.adj = off; off = up(off + 2u * 4u * RMAX_LDS);
-        L.um = off; off = up(off + 8u * (((uint32_t)ef + 63u) / 64u) + 8u);
+        L.um = off; off = up(off + 8u * (((uint32_t)ef + 63u) / 64u) + 32u);   // the scans use um[0 .. 3] at any ef
         L.rq = off; off = up(off + 4u * L.rp);
         L.co = off; off = up(off + 4u * L.rp);
         L.total = off;
@@ -74,10 +74,11 @@ hipError_t launch_dtype(int dtype, const void *X, int64_t N, int d, const int32_
 }  // namespace
 
 hipError_t launch_graph_search(int dtype, const void *X, int64_t N, int d, const int32_t *graph, int R, int entry,
-                               const int32_t *entries, const void *Q, int B, int k, int ef, int32_t *ids,
+                               const int32_t *entries, int n_entries, const void *Q, int B, int k, int ef, int32_t *ids,
                                float *scores, const GraphLds &L, hipStream_t stream) {
     NonStall ns{};
     ns.entries = entries;
+    ns.n_entries = n_entries;
     return launch_dtype<false>(dtype, X, N, d, graph, R, entry, Q, B, k, ef, ids, scores, L, ns, stream);
 }
 

@@ -186,20 +186,9 @@ __global__ __launch_bounds__(GRAPH_THREADS, 2) void graph_search_kernel(
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int b = blockIdx.x;
-    if (ns.entries) {                                     // per-query entry node
-        entry = ns.entries[b];
-        if ((unsigned)entry >= (unsigned)N) {             // not a node: this query gets padding only
-            for (int j = tid; j < k; j += GRAPH_THREADS) {
-                ids[(size_t)b * k + j] = -1;
-                scores[(size_t)b * k + j] = -INFINITY;
-            }
-            if (NS && tid == 0) {
-                if (ns.stats) { ns.stats[(size_t)b * 3] = 0; ns.stats[(size_t)b * 3 + 1] = 0; ns.stats[(size_t)b * 3 + 2] = 0; }
-                if (ns.ema) ns.ema[b] = 0.f;
-            }
-            return;
-        }
-    }
+    // entry nodes of this query: ns.n_entries of its own, or the one shared `entry`
+    const int32_t *my_entries = ns.entries ? ns.entries + (size_t)b * ns.n_entries : nullptr;
+    const int E = ns.entries ? ns.n_entries : 1;
     const int nch = d * T::bytes / 16;                    // 16-byte chunks per row
     const int RP = RPT ? RPT : (int)L.rp;
     constexpr bool PIPELINED = RPT == 32;                 // R <= 32: the software-pipelined loop
@@ -298,25 +287,58 @@ __global__ __launch_bounds__(GRAPH_THREADS, 2) void graph_search_kernel(
         return row_dots(v, x);
     };
 
-    // list <- [(score(entry), entry)]
-    if (grp == 0) {
-        const float s = score_row(entry);
-        if (sub == 0) {
-            ls(0)[0] = s;
-            li(0)[0] = (uint32_t)entry;
-            cache[((uint32_t)entry * 2654435761u) >> cache_shift] = entry;
-            if (NS) atomicOr(&seen_bits[entry >> 5], 1u << (entry & 31));
+    // list <- the entry nodes (at most 32, one row group each), scored and put in order; ids that
+    // are no nodes and ids named by an earlier slot are left out, a NaN score is never listed
+    int len = 0, n_dist = 0;                              // n_dist: scored nodes (used by the last wave)
+    {
+        int v0 = -1;
+        if (grp < E) {
+            v0 = my_entries ? my_entries[grp] : entry;
+            if ((unsigned)v0 >= (unsigned)N) v0 = -1;
+            for (int j = 0; j < grp && v0 >= 0; ++j)
+                if (my_entries[j] == v0) v0 = -1;
         }
+        float s0 = 0.f;
+        if (v0 >= 0) s0 = score_row(v0);
+        if (sub == 0) { cs[grp] = s0; ci[grp] = v0; }
+        __syncthreads();
+        const int cl = lane & 31;
+        const float c_s = cs[cl];
+        const int c_v = ci[cl];
+        const bool c_valid = lane < 32 && c_v >= 0, c_ok = c_valid && c_s == c_s;
+        const uint32_t ok_mask = (uint32_t)__builtin_amdgcn_ballot_w64(c_ok);
+        n_dist = __builtin_popcountll(__builtin_amdgcn_ballot_w64(c_valid));
+        len = min(ef, __builtin_popcount(ok_mask));
+        int r = 0;                                        // listed entries that precede this lane's
+        for (uint32_t m = ok_mask; m != 0; m &= m - 1) {
+            const int l = __builtin_ctz(m);
+            r += precedes01(__int_as_float(__builtin_amdgcn_readlane(__float_as_int(c_s), l)),
+                            __builtin_amdgcn_readlane(c_v, l), c_s, c_v);
+        }
+        if (wave == 0 && c_valid) {
+            if (c_ok && r < ef) { ls(0)[r] = c_s; li(0)[r] = (uint32_t)c_v; }
+            cache[((uint32_t)c_v * 2654435761u) >> cache_shift] = c_v;
+            if (NS) atomicOr(&seen_bits[c_v >> 5], 1u << (c_v & 31));
+        }
+        if (tid < 2) adj_id[tid] = -1;                    // adj[s] may hold the adjacency row of node adj_id[s]
+        __syncthreads();
     }
-    __syncthreads();
+    if (len == 0) {                                       // no entry that is a node with a score: padding only
+        for (int j = tid; j < k; j += GRAPH_THREADS) {
+            ids[(size_t)b * k + j] = -1;
+            scores[(size_t)b * k + j] = -INFINITY;
+        }
+        if (NS && tid == 0) {
+            if (ns.stats) { ns.stats[(size_t)b * 3] = 0; ns.stats[(size_t)b * 3 + 1] = n_dist; ns.stats[(size_t)b * 3 + 2] = 0; }
+            if (ns.ema) ns.ema[b] = 0.f;
+        }
+        return;
+    }
+    entry = (int)li(0)[0];                                // the best entry node is expanded first
 
-    // adj[s] may hold the adjacency row of node adj_id[s], read ahead of time (see below)
-    if (tid < 2) adj_id[tid] = -1;
-    __syncthreads();
-
-    int cur = 0, len = 1;
+    int cur = 0;
     float ema = 0.f;                                      // kept by the last wave, copied to the others
-    int n_dist = 1, n_expand = 0, early = 0;              // n_dist: last wave only
+    int n_expand = 0, early = 0;
     if constexpr (PIPELINED) {
     // ---- R <= 32: a software-pipelined loop -------------------------------------------------------
     // As soon as the neighbours of one expansion are scored, the next node to expand is known: the

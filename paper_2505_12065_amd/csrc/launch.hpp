@@ -79,7 +79,8 @@ struct GraphLds {
 // Maturity exit of the graph search (Section 3.3, Appendix B.2): leave once the moving
 // average of RQ exceeds tau and *ready != 0 (ready == nullptr: always ready).
 struct NonStall {
-    const int32_t *entries;   // [B] per-query entry nodes replacing `entry`, or null (both kernel variants)
+    const int32_t *entries;   // [B, n_entries] per-query entry nodes replacing `entry`, or null (both kernel variants)
+    int32_t n_entries;        // 1 .. 32 when entries is given
     float tau, alpha;
     const int32_t *ready;     // device-visible word the host may change while the kernel runs
     uint32_t *visited;        // [B][words] bitset, zero on entry
@@ -89,9 +90,9 @@ struct NonStall {
 };
 GraphLds graph_lds_layout(int d, int elem_bytes, int R, int ef);
 // dtype: ANN_F16 / ANN_BF16 / ANN_F32 codes 0 / 1 / 2
-// entries: null, or device [B] per-query entry nodes used instead of `entry`
+// entries: null, or device [B, n_entries] per-query entry nodes used instead of `entry`
 hipError_t launch_graph_search(int dtype, const void *X, int64_t N, int d, const int32_t *graph, int R, int entry,
-                               const int32_t *entries, const void *Q, int B, int k, int ef, int32_t *ids,
+                               const int32_t *entries, int n_entries, const void *Q, int B, int k, int ef, int32_t *ids,
                                float *scores, const GraphLds &L, hipStream_t stream);
 hipError_t launch_gather_ids(const int32_t *table, int64_t M, const int32_t *idx, int64_t n, int32_t *out,
                              hipStream_t stream);

@@ -23,7 +23,8 @@ __device__ __forceinline__ void block_min_max(double lo, double hi, double *scra
 
 // One workgroup: extremes of the three metrics, then
 //   level_i = largest j in [0, G) with R_i > T_{R,j} or W_i > T_{W,j} or C_i > T_{C,j}, else 0,
-//   T_{M,j} = min(M) + j/G (max(M) - min(M)), evaluated in binary64 as fma(j/G, max - min, min).
+//   T_{M,j} = min(M) + j/G (max(M) - min(M)), evaluated in binary64 exactly as written: the quotient,
+//   the difference, their product and the sum are each rounded once (no fused multiply-add).
 __global__ __launch_bounds__(PRIO_THREADS) void priority_level_kernel(const int32_t *__restrict__ R,
                                                                       const double *__restrict__ W,
                                                                       const int32_t *__restrict__ C, int n, int G,
@@ -45,25 +46,28 @@ __global__ __launch_bounds__(PRIO_THREADS) void priority_level_kernel(const int3
             const double f = (double)j / (double)G;
 #pragma unroll
             for (int m = 0; m < 3; ++m)
-                if (v[m] > fma(f, mx[m] - mn[m], mn[m])) best = j;
+                if (v[m] > __dadd_rn(mn[m], __dmul_rn(f, mx[m] - mn[m]))) best = j;
         }
         level[i] = best;
     }
 }
 
 // order[position of i] = i, position = number of requests that run before i: higher level first,
-// inside a level longer current queueing time first, equal times in index order.
+// inside a level longer current queueing time first, equal times in index order; a queueing time
+// that is NaN counts as the shortest possible wait (-inf), so every request gets exactly one place.
 __global__ __launch_bounds__(PRIO_THREADS) void priority_order_kernel(const int32_t *__restrict__ level,
                                                                       const double *__restrict__ Wcur, int n,
                                                                       int32_t *__restrict__ order) {
     const int i = blockIdx.x * PRIO_THREADS + threadIdx.x;
     if (i >= n) return;
     const int li = level[i];
-    const double wi = Wcur[i];
+    double wi = Wcur[i];
+    wi = wi == wi ? wi : -INFINITY;
     int before = 0;
     for (int j = 0; j < n; ++j) {
         const int lj = level[j];
-        const double wj = Wcur[j];
+        double wj = Wcur[j];
+        wj = wj == wj ? wj : -INFINITY;
         before += (int)(lj > li) | ((int)(lj == li) & ((int)(wj > wi) | ((int)(wj == wi) & (int)(j < i))));
     }
     order[before] = i;

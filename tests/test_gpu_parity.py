@@ -430,6 +430,100 @@ def test_graph_per_query_entries(dtype):
     assert torch.equal(a[0], b_[0]) and torch.equal(a[1], b_[1])
 
 
+@pytest.mark.parametrize("dtype,R,E,ef,k", [(torch.float16, 12, 4, 40, 5), (torch.float16, 32, 32, 64, 3),
+                                            (torch.bfloat16, 32, 7, 8, 8), (torch.float32, 40, 5, 300, 10),
+                                            (torch.float16, 20, 32, 3, 3), (torch.float16, 16, 2, 3000, 6)])
+def test_graph_several_entries_per_query(dtype, R, E, ef, k):
+    """entries[B, E]: the whole batch against the oracle started from the same lists, which hold ids that
+    are no nodes, repeated ids, and for some queries no usable id at all; through the plain and the
+    maturity entry points (counters included), both loops (R <= 32 and R > 32), short and long lists."""
+    N, B = 9000, 48
+    say(f"graph multi-entry: dtype={dtype} R={R} E={E} ef={ef} k={k}")
+    c = synth.make_corpus(N, 136 if dtype != torch.float32 else 132, 12, seed=61 + E, dtype=dtype, zipf_a=None, sigma=0.3)
+    q = synth.make_queries(c, B)
+    g = synth.ring_union(synth.knn_graph(c.x, R - 2)).contiguous()
+    gen = torch.Generator().manual_seed(E)
+    entries = torch.randint(-3, N + 3, (B, E), generator=gen, dtype=torch.int32)
+    entries[3, :] = -1                                   # nothing usable
+    entries[5, :] = entries[5, 0].clamp(0, N - 1)        # one node named E times
+    if E > 1:
+        entries[9, 1] = entries[9, 0]
+    xd, gd, qd, ed = c.x.to(DEV), g.to(DEV), q.to(DEV), entries.to(DEV)
+    ids, sc = ann.ann_graph_search_multi_typed(xd, gd, ed, qd, k, ef)
+    n_ids, n_sc, stats, ema = ann.ann_graph_search_nonstall_typed(xd, gd, 0, qd, k, ef, entries=ed, tau=float("inf"))
+    torch.cuda.synchronize()
+    name = np_dtype_name(c.x)
+    xn, qn, gn = to_np(c.x), to_np(q), g.numpy()
+    o_ids, _, o_sc64, nd, ne = oracle.graph_search(xn, gn, 0, qn, k, ef, entries=entries.numpy(), dtype=name)
+    assert (o_ids[3] == -1).all() and nd[3] == 0
+    strict, tolerant, n = compare_topk(ids.cpu().numpy(), sc.cpu().numpy(), o_ids, o_sc64, xn, qn, dtype=name)
+    say(f"  strict {strict}/{n}")
+    assert strict >= n - 2
+    assert torch.equal(ids, n_ids) and torch.equal(sc, n_sc)
+    st = stats.cpu().numpy()
+    for b in range(B):
+        if (int(st[b, 1]), int(st[b, 2])) != (int(nd[b]), int(ne[b])):
+            explain_divergence(xn, gn, qn, b, name, entries[b].tolist(), k, ef, o_ids[b].tolist(),
+                               (int(nd[b]), int(ne[b])), n_ids[b].tolist(), (int(st[b, 1]), int(st[b, 2])))
+
+
+def test_graph_several_entries_with_maturity_exit():
+    """The maturity exit started from several entries: entry nodes yield no sample."""
+    N, B, E, k, ef = 12_000, 64, 6, 3, 48
+    c = synth.make_corpus(N, 128, 16, seed=5, dtype=torch.float16, zipf_a=None, sigma=0.3)
+    q = synth.make_queries(c, B)
+    g = synth.ring_union(synth.knn_graph(c.x.to(DEV), 14).cpu()).contiguous()
+    gen = torch.Generator().manual_seed(3)
+    entries = torch.randint(0, N, (B, E), generator=gen, dtype=torch.int32)
+    gpu = ann.ann_graph_search_nonstall_typed(c.x.to(DEV), g.to(DEV), 0, q.to(DEV), k, ef, entries=entries.to(DEV),
+                                              tau=0.8, window=60)
+    torch.cuda.synchronize()
+    ids, sc, stats, ema = (t.cpu().numpy() for t in gpu)
+    xn, qn, gn = c.x.numpy(), q.numpy(), g.numpy()
+    o = oracle.graph_search_nonstall(xn, gn, 0, qn, k, ef, tau=0.8, window=60, entries=entries.numpy())
+    same = [b for b in range(B) if stats[b].tolist() == o[3][b].tolist()]
+    say(f"multi-entry maturity exit: same decision {len(same)}/{B}, early exits {int(stats[:, 0].sum())}")
+    assert len(same) >= B - 2 and int(stats[:, 0].sum()) >= B // 4
+    compare_topk(ids[same], sc[same], o[0][same], o[2][same], xn, qn, rows=same)
+    assert np.allclose(ema[same], o[4][same], rtol=5e-4, atol=5e-4)
+    for b in set(range(B)) - set(same):                  # a borderline decision: the average sits at tau
+        assert abs(float(ema[b]) - 0.8) < 2e-3 or abs(float(o[4][b]) - 0.8) < 2e-3, (b, ema[b], o[4][b])
+
+
+def test_nan_rows_are_never_listed():
+    """A corpus row of NaNs is scored and marked visited but never returned, listed or expanded,
+    as an entry node, as a neighbour, in the exact search; the oracle pins the same rule."""
+    N = 3000
+    c = synth.make_corpus(N, 64, 6, seed=13, dtype=torch.float16, zipf_a=None, sigma=0.3)
+    q = synth.make_queries(c, 12)
+    x = c.x.clone()
+    bad = [5, 77, 1500]
+    x[bad] = float("nan")
+    g = synth.ring_union(synth.knn_graph(c.x, 10)).contiguous()
+    xd, gd, qd = x.to(DEV), g.to(DEV), q.to(DEV)
+    xn, qn, gn = x.numpy(), q.numpy(), g.numpy()
+    for B, k in ((12, 3), (12, 10)):
+        f_ids, f_sc = ann.ann_flat_search_typed(xd, qd[:B].contiguous(), k)
+        torch.cuda.synchronize()
+        o_ids, _, o_sc64 = oracle.flat_search(xn, qn[:B], k)
+        compare_topk(f_ids.cpu().numpy(), f_sc.cpu().numpy(), o_ids, o_sc64, xn, qn[:B])
+        assert not np.isin(f_ids.cpu().numpy(), bad).any()
+    for entry in (5, 6):                                 # a NaN entry node, and a sound one next to it
+        ids, sc = ann.ann_graph_search_typed(xd, gd, entry, qd, 4, 24)
+        n_ids, _, stats, _ = ann.ann_graph_search_nonstall_typed(xd, gd, entry, qd, 4, 24, tau=float("inf"))
+        torch.cuda.synchronize()
+        o_ids, _, o_sc64, nd, ne = oracle.graph_search(xn, gn, entry, qn, 4, 24)
+        assert np.array_equal(ids.cpu().numpy(), o_ids) and torch.equal(ids, n_ids)
+        assert not np.isin(ids.cpu().numpy(), bad).any()
+        if entry == 5:
+            assert (o_ids == -1).all() and np.isneginf(sc.cpu().numpy()).all()
+            assert stats.cpu().numpy()[:, 1:].tolist() == [[1, 0]] * 12
+    e2 = torch.tensor([[5, 6]] * 12, dtype=torch.int32)
+    ids, _ = ann.ann_graph_search_multi_typed(xd, gd, e2.to(DEV), qd, 4, 24)
+    torch.cuda.synchronize()
+    assert np.array_equal(ids.cpu().numpy(), oracle.graph_search(xn, gn, 0, qn, 4, 24, entries=e2.numpy())[0])
+
+
 def test_gather_ids():
     gen = torch.Generator().manual_seed(4)
     table = torch.randint(0, 1 << 30, (1000,), generator=gen, dtype=torch.int32)
@@ -505,6 +599,22 @@ def test_priority_order_matches_oracle(n, G):
     o_level, o_order = oracle.priority_order(R, W, C, Wcur, G)
     assert np.array_equal(level.cpu().numpy(), o_level)
     assert np.array_equal(order.cpu().numpy(), o_order)
+
+
+def test_priority_order_with_nan_queueing_times():
+    n = 700
+    gen = np.random.default_rng(8)
+    R = gen.integers(0, 9, n).astype(np.int32)
+    C = gen.integers(100, 5000, n).astype(np.int32)
+    W = gen.random(n) * 30
+    Wcur = np.round(gen.random(n) * 4, 1)
+    Wcur[gen.random(n) < 0.2] = np.nan
+    level, order = ann.ann_priority_order(torch.from_numpy(R).to(DEV), torch.from_numpy(W).to(DEV),
+                                          torch.from_numpy(C).to(DEV), torch.from_numpy(Wcur).to(DEV), 6)
+    torch.cuda.synchronize()
+    o_level, o_order = oracle.priority_order(R, W, C, Wcur, 6)
+    assert np.array_equal(level.cpu().numpy(), o_level) and np.array_equal(order.cpu().numpy(), o_order)
+    assert sorted(order.cpu().tolist()) == list(range(n))
 
 
 def test_priority_order_bad_arguments():

@@ -504,6 +504,8 @@ def test_nan_scores_are_never_listed():
     g = path_graph(len(values))
     bad = corpus.copy()
     bad[2] = np.nan                      # the walk 0 -> 1 -> 2 -> 3 cannot pass node 2
+    f_ids, f_sc, _ = oracle.flat_search(bad, q, 8)
+    assert f_ids[0].tolist() == [3, 7, 5, 1, 4, 0, 6, -1] and np.isneginf(f_sc[0, 7])   # values .9 .9 .5 .3 .3 .1 .05
     ids, sc, _, nd, ne = oracle.graph_search(bad, g, 0, q, 3, 3)
     assert ids[0].tolist() == [1, 0, -1] and np.isneginf(sc[0, 2])
     assert (int(nd[0]), int(ne[0])) == (3, 2)                # node 2 is scored and counted, not listed
@@ -675,6 +677,16 @@ def test_priority_single_metric_closed_form():
             want = 0 if num == 0 else -(-num // (mx - mn)) - 1
             assert level[i] == want, (which, i, R[i])
     assert level[1] == G - 1
+
+
+def test_priority_nan_queueing_time_is_the_shortest_wait():
+    R = np.array([1, 1, 1, 9, 1], np.int32)
+    C = np.array([5, 5, 5, 5, 5], np.int32)
+    W = np.array([1.0, 1.0, 1.0, 1.0, 1.0])
+    Wcur = np.array([2.0, np.nan, 3.0, np.nan, np.nan])
+    level, order = oracle.priority_order(R, W, C, Wcur, 6)
+    assert level.tolist() == [0, 0, 0, 5, 0]
+    assert order.tolist() == [3, 2, 0, 1, 4]      # top level first; then 3.0, 2.0, and the NaNs in index order
 
 
 def test_priority_invariants_and_order():
