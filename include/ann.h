@@ -260,6 +260,10 @@ int ann_timing_enable(int32_t on);
  * number and the sum of their durations in milliseconds.  Host pointers. */
 int ann_timing_read(int32_t kernel, int32_t *launches, double *total_ms);
 
+/* The same, launch by launch: ms[i] = duration of the i-th recorded launch of `kernel`, in the order
+ * of the calls, for i < min(*launches, capacity); *launches = number recorded.  Host pointers. */
+int ann_timing_read_each(int32_t kernel, int32_t capacity, int32_t *launches, float *ms);
+
 /* Priority levels and execution order of the request scheduler (Section 3.2 "Priority
  * Scheduling", Eq. 1 and 2).  Metrics of request i: R[i] retrievals completed, W[i] waiting time
  * of the initial request, C[i] context length; for each metric M and level j in [0, G),

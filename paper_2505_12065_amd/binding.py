@@ -26,7 +26,7 @@ EXPORTS = ("ann_version", "ann_last_error", "ann_flat_search_typed", "ann_flat_s
            "ann_graph_search_nonstall_typed", "ann_graph_nonstall_workspace_bytes",
            "ann_graph_search_entries_typed", "ann_gather_ids", "ann_timing_enable", "ann_timing_read",
            "ann_measure_mfma_rate", "ann_priority_order", "ann_flat_search_static",
-           "ann_graph_search_multi_typed")
+           "ann_graph_search_multi_typed", "ann_timing_read_each")
 
 
 class AnnError(RuntimeError):
@@ -70,6 +70,7 @@ def lib() -> ctypes.CDLL:
         L.ann_priority_order.argtypes = [vp, vp, vp, vp, i32, i32, vp, vp, vp]
         L.ann_timing_enable.argtypes = [i32]
         L.ann_timing_read.argtypes = [i32, c.POINTER(i32), c.POINTER(c.c_double)]
+        L.ann_timing_read_each.argtypes = [i32, i32, c.POINTER(i32), c.POINTER(c.c_float)]
         L.ann_graph_nonstall_workspace_bytes.argtypes = [i64, i32]
         L.ann_graph_nonstall_workspace_bytes.restype = i64
         for name in EXPORTS:
@@ -321,6 +322,15 @@ def ann_timing_read(kernel: int) -> Tuple[int, float]:
     n, ms = ctypes.c_int32(0), ctypes.c_double(0.0)
     _check(lib().ann_timing_read(kernel, ctypes.byref(n), ctypes.byref(ms)))
     return n.value, ms.value
+
+
+def ann_timing_read_each(kernel: int):
+    """Durations (ms) of the recorded launches of the main kernel `kernel`, in call order."""
+    n = ctypes.c_int32(0)
+    _check(lib().ann_timing_read_each(kernel, 0, ctypes.byref(n), None))
+    buf = (ctypes.c_float * max(1, n.value))()
+    _check(lib().ann_timing_read_each(kernel, n.value, ctypes.byref(n), buf))
+    return [buf[i] for i in range(n.value)]
 
 
 def ann_graph_nonstall_workspace_bytes(N: int, B: int) -> int:

@@ -449,6 +449,25 @@ int ann_timing_read(int32_t kernel, int32_t *launches, double *total_ms) {
     return ANN_OK;
 }
 
+int ann_timing_read_each(int32_t kernel, int32_t capacity, int32_t *launches, float *ms) {
+    if (!launches || (capacity > 0 && !ms) || capacity < 0) return fail(ANN_ERR_INVALID, "bad arguments");
+    if (kernel < 0 || kernel >= ANN_KERNEL_COUNT) return fail(ANN_ERR_INVALID, "unknown kernel code %d", kernel);
+    std::lock_guard<std::mutex> lock(g_mu);
+    int n = 0;
+    for (const TimedLaunch &t : g_timed) {
+        if (t.kernel != kernel) continue;
+        float one = 0.f;
+        if (hipEventSynchronize(t.b) != hipSuccess || hipEventElapsedTime(&one, t.a, t.b) != hipSuccess) {
+            (void)hipGetLastError();
+            return fail(ANN_ERR_LAUNCH, "cannot read the events of a timed launch");
+        }
+        if (n < capacity) ms[n] = one;
+        ++n;
+    }
+    *launches = n;
+    return ANN_OK;
+}
+
 int ann_priority_order(const int32_t *R, const double *W, const int32_t *C, const double *Wcur, int32_t n, int32_t G,
                        int32_t *level, int32_t *order, void *stream) {
     if (n == 0) return ANN_OK;

@@ -334,7 +334,9 @@ __global__ __launch_bounds__(GRAPH_THREADS, 2) void graph_search_kernel(
         }
         return;
     }
-    entry = (int)li(0)[0];                                // the best entry node is expanded first
+    // the best entry node is expanded first (masked: thread 0 may already have set the entry's
+    // "expanded" bit below when a slower wave gets here; the id bits do not change)
+    entry = (int)(li(0)[0] & ~EXPANDED);
 
     int cur = 0;
     float ema = 0.f;                                      // kept by the last wave, copied to the others

@@ -30,6 +30,33 @@ def sample_rows(B, n=12):
     return np.unique(np.concatenate([np.arange(4), np.linspace(4, B - 5, n - 8).astype(int), np.arange(B - 4, B)]))
 
 
+class FlatOracle:
+    """The exact oracle over one corpus for a fixed set of query rows, computed once per k and
+    reused for every batch size (a batch is a prefix of the same queries, and the oracle's answer
+    for a query does not depend on the batch it is in)."""
+
+    def __init__(self, xh, qh, rows):
+        self.xh, self.qh, self.rows, self.done = xh, qh, np.asarray(rows), {}
+
+    def get(self, k):
+        if k not in self.done:
+            o_ids, _, o_sc64 = oracle.flat_search(self.xh, self.qh[self.rows], k)
+            self.done[k] = (o_ids, o_sc64)
+        return self.done[k]
+
+    def check(self, x, q, B, k=K):
+        """GPU search of the first B queries against the oracle on every held row below B."""
+        qb = q[:B].contiguous()
+        ids, sc = ann.ann_flat_search_typed(x, qb, k)
+        torch.cuda.synchronize()
+        o_ids, o_sc64 = self.get(k)
+        use = np.nonzero(self.rows < B)[0]
+        rows = self.rows[use]
+        strict, tolerant, n = compare_topk(ids.cpu().numpy()[rows], sc.cpu().numpy()[rows], o_ids[use], o_sc64[use],
+                                           self.xh, self.qh, rows=rows)
+        return strict, tolerant, n, ids
+
+
 def check_flat_sampled(x, xh, q, B, k=K):
     qb = q[:B].contiguous()
     ids, sc = ann.ann_flat_search_typed(x, qb, k)
@@ -51,12 +78,19 @@ def cfg1():
     return c, q, xh
 
 
-@pytest.mark.parametrize("B", [1, 16, 64, 256, 512])
-def test_cfg1_flat_full_size(cfg1, B):
+@pytest.fixture(scope="module")
+def cfg1_oracle(cfg1):
     c, q, xh = cfg1
-    strict, tolerant, n, _ = check_flat_sampled(c.x, xh, q, B)
-    say(f"cfg1 flat N=1,000,000 B={B}: oracle on {n} sampled queries, strict={strict} tolerant={tolerant}")
-    assert strict >= n - 1
+    return FlatOracle(xh, q.cpu().numpy(), np.arange(512))      # every query: about 17 s on 16 host threads
+
+
+@pytest.mark.parametrize("B", [1, 16, 64, 256, 512])
+def test_cfg1_flat_full_size(cfg1, cfg1_oracle, B):
+    """Every query of every batch size against the oracle (k = 3)."""
+    c, q, xh = cfg1
+    strict, tolerant, n, _ = cfg1_oracle.check(c.x, q, B)
+    say(f"cfg1 flat N=1,000,000 B={B}: oracle on all {n} queries, strict={strict} tolerant={tolerant}")
+    assert n == B and strict >= n - max(1, n // 100)
 
 
 @pytest.mark.parametrize("B,k", [(16, 10), (128, 5), (512, 5), (512, 16)])
@@ -140,10 +174,13 @@ def test_cfg3_flat_full_size():
     assert c.x.shape == (21_000_000, 768)
     q = synth.make_queries(c, 256)
     xh = c.x.cpu().numpy()
+    # the oracle takes about 0.7 s per query here: the first 16 queries (all of B = 1 and B = 16) and
+    # every fifth of the rest, 64 of the 256 in all
+    held = FlatOracle(xh, q.cpu().numpy(), np.unique(np.concatenate([np.arange(16), np.arange(16, 256, 5)])))
     for B in (1, 16, 256):
-        strict, tolerant, n, _ = check_flat_sampled(c.x, xh, q, B)
-        say(f"cfg3 flat N=21,000,000 B={B}: oracle on {n} sampled queries, strict={strict} tolerant={tolerant}")
-        assert strict >= n - 1
+        strict, tolerant, n, _ = held.check(c.x, q, B)
+        say(f"cfg3 flat N=21,000,000 B={B}: oracle on {n} of {B} queries, strict={strict} tolerant={tolerant}")
+        assert n == (B if B <= 16 else 64) and strict >= n - 1
     for B, k in ((16, 10), (256, 5)):
         strict, tolerant, n, _ = check_flat_sampled(c.x, xh, q, B, k)
         say(f"cfg3 flat N=21,000,000 B={B} k={k}: oracle on {n} sampled queries, strict={strict} tolerant={tolerant}")
