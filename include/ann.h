@@ -239,6 +239,14 @@ int ann_set_default_dtype(int32_t dtype);
 /* Bytes of device workspace a flat search of this shape needs. */
 int64_t ann_flat_workspace_bytes(int64_t N, int32_t d, int32_t dtype, int32_t B, int32_t k);
 
+/* Use a caller-owned device buffer as the workspace of the current device (so that, e.g., the
+ * caller's allocator owns the memory and no entry point ever allocates): every call that needs
+ * workspace (ann_flat_workspace_bytes, ann_graph_nonstall_workspace_bytes) then runs in it, and one
+ * that needs more than `bytes` fails with ANN_ERR_NOMEM instead of growing anything.
+ *   workspace  device pointer, 256-byte aligned, valid until it is replaced; NULL: back to the
+ *              library-owned buffers.  Not freed by the library.  Calls that use it must not overlap. */
+int ann_set_workspace(void *workspace, int64_t bytes);
+
 /* Release the library-owned workspace of the current device (synchronises it). */
 int ann_release_workspace(void);
 

@@ -25,7 +25,8 @@ import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "ann_oracle.c")
-_LIB = os.path.join(_HERE, "libann_oracle.so")
+# ANN_ORACLE_LIBRARY_PATH: use a build of ann_oracle.c made elsewhere (e.g. with sanitizers) instead
+_LIB = os.environ.get("ANN_ORACLE_LIBRARY_PATH", os.path.join(_HERE, "libann_oracle.so"))
 
 F16, BF16, F32 = 0, 1, 2
 _lib = None
@@ -33,6 +34,8 @@ _lib = None
 
 def build(force: bool = False) -> str:
     """Compile ann_oracle.c with gcc into oracle/libann_oracle.so."""
+    if "ANN_ORACLE_LIBRARY_PATH" in os.environ:
+        return _LIB
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
         subprocess.check_call(["gcc", "-O2", "-ffp-contract=off", "-fopenmp", "-fPIC", "-shared", "-std=c11",
                                "-Wall", "-Wextra", "-o", _LIB, _SRC, "-lm"])

@@ -26,7 +26,8 @@ EXPORTS = ("ann_version", "ann_last_error", "ann_flat_search_typed", "ann_flat_s
            "ann_graph_search_nonstall_typed", "ann_graph_nonstall_workspace_bytes",
            "ann_graph_search_entries_typed", "ann_gather_ids", "ann_timing_enable", "ann_timing_read",
            "ann_measure_mfma_rate", "ann_priority_order", "ann_flat_search_static",
-           "ann_graph_search_multi_typed", "ann_timing_read_each")
+           "ann_graph_search_multi_typed", "ann_timing_read_each",
+           "ann_set_workspace")
 
 
 class AnnError(RuntimeError):
@@ -68,6 +69,7 @@ def lib() -> ctypes.CDLL:
         L.ann_gather_ids.argtypes = [vp, i64, vp, i64, vp, vp]
         L.ann_measure_mfma_rate.argtypes = [i32, i32, c.POINTER(c.c_double)]
         L.ann_priority_order.argtypes = [vp, vp, vp, vp, i32, i32, vp, vp, vp]
+        L.ann_set_workspace.argtypes = [vp, i64]
         L.ann_timing_enable.argtypes = [i32]
         L.ann_timing_read.argtypes = [i32, c.POINTER(i32), c.POINTER(c.c_double)]
         L.ann_timing_read_each.argtypes = [i32, i32, c.POINTER(i32), c.POINTER(c.c_float)]
@@ -365,6 +367,18 @@ def ann_set_default_dtype(dtype: torch.dtype) -> None:
 
 def ann_flat_workspace_bytes(N: int, d: int, dtype: torch.dtype, B: int, k: int) -> int:
     return int(lib().ann_flat_workspace_bytes(N, d, _DTYPES[dtype], B, k))
+
+
+def ann_set_workspace(buf: Optional[torch.Tensor]) -> None:
+    """Use `buf` (a contiguous uint8 device tensor the caller keeps alive) as the workspace of its device;
+    None hands the workspace back to the library."""
+    if buf is None:
+        _check(lib().ann_set_workspace(None, 0))
+        return
+    if buf.dtype != torch.uint8 or not buf.is_cuda or not buf.is_contiguous():
+        raise ValueError("the workspace must be a contiguous uint8 device tensor")
+    with torch.cuda.device(buf.device):
+        _check(lib().ann_set_workspace(buf.data_ptr(), buf.numel()))
 
 
 def ann_release_workspace() -> None:

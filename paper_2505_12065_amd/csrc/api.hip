@@ -49,6 +49,8 @@ struct DeviceState {
     void *vis = nullptr;          // visited bitsets of the non-stall graph search
     size_t vis_bytes = 0;
     void *scratch_ptr = nullptr;  // this device's address of `scratch`
+    void *user_ws = nullptr;      // caller-owned workspace (ann_set_workspace), used instead of ws and vis
+    size_t user_bytes = 0;
 };
 
 std::mutex g_mu;
@@ -92,7 +94,20 @@ int grow(void **buf, size_t *have, size_t bytes) {
     return ANN_OK;
 }
 
-int ensure_workspace(DeviceState *st, size_t bytes) { return grow(&st->ws, &st->ws_bytes, bytes); }
+// The device buffer a call may use as workspace: the caller's when one was set (never grown: a call
+// that needs more fails), else the library's own, grown on demand.
+int workspace_for(DeviceState *st, void **own, size_t *own_bytes, size_t bytes, void **out) {
+    if (st->user_ws) {
+        if (bytes > st->user_bytes)
+            return fail(ANN_ERR_NOMEM, "this call needs %zu bytes of workspace, the buffer given to ann_set_workspace has %zu",
+                        bytes, st->user_bytes);
+        *out = st->user_ws;
+        return ANN_OK;
+    }
+    if (int rc = grow(own, own_bytes, bytes)) return rc;
+    *out = *own;
+    return ANN_OK;
+}
 
 // words of one query's visited bitset: one bit per node, rounded to 16-byte units
 int64_t visited_words(int64_t N) { return (N + 511) / 512 * 16; }
@@ -505,6 +520,17 @@ int ann_measure_mfma_rate(int32_t random_operands, int32_t iters, double *tflops
     return ANN_OK;
 }
 
+int ann_set_workspace(void *workspace, int64_t bytes) {
+    if (workspace && bytes < 1) return fail(ANN_ERR_INVALID, "ann_set_workspace: bytes = %lld", (long long)bytes);
+    if (reinterpret_cast<uintptr_t>(workspace) & 255) return fail(ANN_ERR_ALIGNMENT, "the workspace must be 256-byte aligned");
+    std::lock_guard<std::mutex> lock(g_mu);
+    DeviceState *st = nullptr;
+    if (int rc = device_state(&st)) return rc;
+    st->user_ws = workspace;
+    st->user_bytes = workspace ? (size_t)bytes : 0;
+    return ANN_OK;
+}
+
 int ann_release_workspace(void) {
     std::lock_guard<std::mutex> lock(g_mu);
     DeviceState *st = nullptr;
@@ -528,10 +554,10 @@ int ann_flat_search_typed(const void *corpus, int64_t N, int32_t d, int32_t dtyp
     if (int rc = device_state(&st)) return rc;
     const FlatPlan pl = flat_plan(st->cus, N, d, dtype, B, k);
     if (dtype != ANN_F32 && pl.nqg_max < 1) return fail(ANN_ERR_INVALID, "d = %d too large for LDS", d);
-    if (int rc = ensure_workspace(st, pl.ws_bytes)) return rc;
-    Cand *partial = static_cast<Cand *>(st->ws);
+    void *ws = nullptr;
+    if (int rc = workspace_for(st, &st->ws, &st->ws_bytes, pl.ws_bytes, &ws)) return rc;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    return flat_search_run(pl, corpus, N, d, dtype, queries, B, k, ids, scores, partial, s);
+    return flat_search_run(pl, corpus, N, d, dtype, queries, B, k, ids, scores, static_cast<Cand *>(ws), s);
 }
 
 int ann_flat_search(const void *corpus, int64_t N, int32_t d, const void *queries, int32_t B, int32_t k,
@@ -613,8 +639,9 @@ int ann_graph_search_nonstall_typed(const void *corpus, int64_t N, int32_t d, in
     ns.words = visited_words(N);
     ns.stats = stats;
     ns.ema = ema;
-    if (int rc = grow(&st->vis, &st->vis_bytes, (size_t)B * (size_t)ns.words * 4)) return rc;
-    ns.visited = static_cast<uint32_t *>(st->vis);
+    void *vis = nullptr;
+    if (int rc = workspace_for(st, &st->vis, &st->vis_bytes, (size_t)B * (size_t)ns.words * 4, &vis)) return rc;
+    ns.visited = static_cast<uint32_t *>(vis);
     hipStream_t s = static_cast<hipStream_t>(stream);
     if (int rc = check_launch("zero_words_kernel", launch_zero_words(ns.visited, (size_t)B * (size_t)ns.words, s)))
         return rc;
@@ -644,8 +671,9 @@ static int graph_search_any(const void *corpus, int64_t N, int32_t d, int32_t dt
     ns.tau = INFINITY;
     ns.alpha = 0.f;
     ns.words = visited_words(N);
-    if (int rc = grow(&st->vis, &st->vis_bytes, (size_t)B * (size_t)ns.words * 4)) return rc;
-    ns.visited = static_cast<uint32_t *>(st->vis);
+    void *vis = nullptr;
+    if (int rc = workspace_for(st, &st->vis, &st->vis_bytes, (size_t)B * (size_t)ns.words * 4, &vis)) return rc;
+    ns.visited = static_cast<uint32_t *>(vis);
     if (int rc = check_launch("zero_words_kernel", launch_zero_words(ns.visited, (size_t)B * (size_t)ns.words, s)))
         return rc;
     TimedScope timed(ANN_KERNEL_GRAPH, s);

@@ -161,6 +161,38 @@ def test_flat_short_entry_point_and_reuse_of_outputs():
     assert torch.equal(s_ids, t_ids)
 
 
+def test_caller_owned_workspace():
+    """ann_set_workspace: the searches run in the caller's buffer, give the same results, and a
+    buffer that is too small is an error, not an allocation."""
+    c = synth.make_corpus(40_000, 256, 8, seed=3, dtype=torch.float16, zipf_a=None, sigma=0.3)
+    q = synth.make_queries(c, 96)
+    g = synth.ring_union(synth.knn_graph(c.x.to(DEV), 10).cpu()).contiguous()
+    xd, qd, gd = c.x.to(DEV), q.to(DEV), g.to(DEV)
+    want = ann.ann_flat_search_typed(xd, qd, 3)
+    want_g = ann.ann_graph_search_nonstall_typed(xd, gd, 1, qd, 3, 40, tau=0.8, window=50)
+    torch.cuda.synchronize()
+    need = max(ann.ann_flat_workspace_bytes(40_000, 256, torch.float16, 96, 3), ann.ann_graph_nonstall_workspace_bytes(40_000, 96))
+    buf = torch.full((need + 4096,), 0xAB, dtype=torch.uint8, device=DEV)
+    try:
+        ann.ann_set_workspace(buf)
+        got = ann.ann_flat_search_typed(xd, qd, 3)
+        got_g = ann.ann_graph_search_nonstall_typed(xd, gd, 1, qd, 3, 40, tau=0.8, window=50)
+        torch.cuda.synchronize()
+        assert torch.equal(got[0], want[0]) and torch.equal(got[1], want[1])
+        for a, b in zip(got_g, want_g):
+            assert torch.equal(a, b)
+        assert bool((buf[:1024] != 0xAB).any())                  # the buffer was really used
+        ann.ann_set_workspace(buf[:256])
+        with pytest.raises(ann.AnnError) as e:
+            ann.ann_flat_search_typed(xd, qd, 3)
+        assert e.value.code == ann.binding.ANN_ERR_NOMEM
+    finally:
+        ann.ann_set_workspace(None)
+    again = ann.ann_flat_search_typed(xd, qd, 3)
+    torch.cuda.synchronize()
+    assert torch.equal(again[0], want[0])
+
+
 def test_flat_is_deterministic():
     c = synth.make_corpus(50_000, 768, 32, seed=21, dtype=torch.float16)
     q = synth.make_queries(c, 48)
