@@ -41,14 +41,14 @@ GraphLds graph_lds_layout(int d, int elem_bytes, int R, int ef) {
 }
 
 namespace {
-template <class T, int RPT, bool NS>
+template <class T, int RPT, bool NS, bool QREG = true>
 hipError_t launch_rp(const void *X, int64_t N, int d, const int32_t *graph, int R, int entry, const void *Q, int B,
                      int k, int ef, int32_t *ids, float *scores, const GraphLds &L, const NonStall &ns,
                      hipStream_t stream) {
     static size_t big = 0;
-    if (hipError_t e = allow_big_lds(reinterpret_cast<const void *>(&graph_search_kernel<T, RPT, NS>), L.total, &big))
+    if (hipError_t e = allow_big_lds(reinterpret_cast<const void *>(&graph_search_kernel<T, RPT, NS, QREG>), L.total, &big))
         return e;
-    hipLaunchKernelGGL((graph_search_kernel<T, RPT, NS>), dim3(B), dim3(GRAPH_THREADS), L.total, stream, X, N, d,
+    hipLaunchKernelGGL((graph_search_kernel<T, RPT, NS, QREG>), dim3(B), dim3(GRAPH_THREADS), L.total, stream, X, N, d,
                        graph, R, entry, Q, k, ef, ids, scores, L, ns);
     return hipGetLastError();
 }
@@ -57,6 +57,12 @@ template <class T, bool NS>
 hipError_t launch(const void *X, int64_t N, int d, const int32_t *graph, int R, int entry, const void *Q, int B,
                   int k, int ef, int32_t *ids, float *scores, const GraphLds &L, const NonStall &ns,
                   hipStream_t stream) {
+    // More queries than two workgroups per compute unit hold at once, and a layout small enough for
+    // three: the variant that reads the query from LDS and runs three per compute unit.
+    if constexpr (!NS) {
+        if (L.rp == 32 && B > GRAPH_DENSE_MIN_B && 3 * (size_t)L.total + 3 * 1024 <= LDS_MAX)
+            return launch_rp<T, 32, false, false>(X, N, d, graph, R, entry, Q, B, k, ef, ids, scores, L, ns, stream);
+    }
     return L.rp == 32 ? launch_rp<T, 32, NS>(X, N, d, graph, R, entry, Q, B, k, ef, ids, scores, L, ns, stream)
                       : launch_rp<T, 0, NS>(X, N, d, graph, R, entry, Q, B, k, ef, ids, scores, L, ns, stream);
 }

@@ -163,8 +163,12 @@ __device__ __forceinline__ int group_lower_bound_fast(const float *s, const uint
 // scored neighbours fully unrolled: the software-pipelined loop), 0 for wider graphs (the number
 // of slots, rounded up to 32, comes from the layout at run time: the plain loop).
 // NS: with the maturity exit (parameters in `ns`, ignored otherwise).
-template <class T, int RPT, bool NS>
-__global__ __launch_bounds__(GRAPH_THREADS, 2) void graph_search_kernel(
+// QREG: the lane's share of the query stays in registers (fastest for one resident round of
+// queries: two workgroups per compute unit).  Without it the products read the query from LDS and
+// the kernel fits three workgroups per compute unit: more queries in flight, for batches larger
+// than the chip holds at once, where throughput and not the latency of one query counts.
+template <class T, int RPT, bool NS, bool QREG = true>
+__global__ __launch_bounds__(GRAPH_THREADS, QREG ? 2 : 3) void graph_search_kernel(
     const void *__restrict__ X, int64_t N, int d, const int32_t *__restrict__ graph, int R, int entry,
     const void *__restrict__ Q, int k, int ef, int32_t *__restrict__ ids, float *__restrict__ scores,
     GraphLds L, NonStall ns) {
@@ -208,10 +212,18 @@ __global__ __launch_bounds__(GRAPH_THREADS, 2) void graph_search_kernel(
     // The lane's share of the first 128 chunks of the query (chunks sub, sub + 8, ...) stays in
     // registers for the whole search: up to 1024 16-bit dimensions are scored without reading
     // the query from LDS at all.
-    constexpr int BLK = 16 * LANES_PER_ROW;               // chunks per block of 16 loads per lane
-    u4 qr[16];
+    constexpr int NX = QREG ? 16 : 8;                     // 16-byte loads of a row a lane keeps in flight
+    constexpr int BLK = NX * LANES_PER_ROW;               // chunks of a row covered by those loads
+    constexpr int TAIL = 8 * LANES_PER_ROW;               // chunks per round of the loop over the rest of a row
+    u4 qr[QREG ? 16 : 1];
+    if constexpr (QREG) {
 #pragma unroll
-    for (int u = 0; u < 16; ++u) qr[u] = qs[min(sub + u * LANES_PER_ROW, nch - 1)];
+        for (int u = 0; u < 16; ++u) qr[u] = qs[min(sub + u * LANES_PER_ROW, nch - 1)];
+    }
+    auto q_chunk = [&](int u) -> u4 {
+        if constexpr (QREG) return qr[u];
+        else return qs[min(sub + u * LANES_PER_ROW, nch - 1)];
+    };
 
     // <q, x_v> by the 8 lanes of a row group; every lane of the group gets the sum.  All
     // of a lane's 16-byte loads of the row are issued before the first one is used, so a
@@ -221,13 +233,13 @@ __global__ __launch_bounds__(GRAPH_THREADS, 2) void graph_search_kernel(
     // row's last chunk instead and leaves the product out of the sum (`lim` is re-derived
     // per call on purpose: sixteen loop-invariant lane masks would not fit the scalar registers).
     // (in two halves, so that other work can be put between the loads and their use)
-    auto row_issue = [&](int v, u4 (&x)[16]) {
+    auto row_issue = [&](int v, u4 (&x)[NX]) {
         const char *rp = static_cast<const char *>(X) + (size_t)v * nch * 16;
         int lim = nch - sub;                              // chunk sub + 8u is in the row iff 8u < lim
         asm volatile("" : "+v"(lim));
         const char *rl = rp + sub * 16;
 #pragma unroll
-        for (int g = 0; g < 4; ++g)
+        for (int g = 0; g < NX / 4; ++g)
             if ((g + 1) * 4 * LANES_PER_ROW <= nch) {      // the whole run is inside: constant offsets
 #pragma unroll
                 for (int u = 4 * g; u < 4 * g + 4; ++u) x[u] = load_chunk(rl + u * LANES_PER_ROW * 16);
@@ -237,27 +249,27 @@ __global__ __launch_bounds__(GRAPH_THREADS, 2) void graph_search_kernel(
                     x[u] = load_chunk(rp + (size_t)(sub + min(u * LANES_PER_ROW, lim - 1)) * 16);
             }
     };
-    auto row_dots = [&](int v, u4 (&x)[16]) -> float {
+    auto row_dots = [&](int v, u4 (&x)[NX]) -> float {
         const char *rp = static_cast<const char *>(X) + (size_t)v * nch * 16;
         f4 acc = {0.f, 0.f, 0.f, 0.f};                    // four independent chains, added at the end
         int lim = nch - sub;
         asm volatile("" : "+v"(lim));
 #pragma unroll
-        for (int g = 0; g < 4; ++g)
+        for (int g = 0; g < NX / 4; ++g)
             if ((g + 1) * 4 * LANES_PER_ROW <= nch) {      // the whole run is inside the row
 #pragma unroll
-                for (int u = 4 * g; u < 4 * g + 4; ++u) dot_chunk4<T>(x[u], qr[u], acc);
+                for (int u = 4 * g; u < 4 * g + 4; ++u) dot_chunk4<T>(x[u], q_chunk(u), acc);
             } else if (g * 4 * LANES_PER_ROW < nch) {
 #pragma unroll
                 for (int u = 4 * g; u < 4 * g + 4; ++u) {
                     f4 t = acc;
-                    dot_chunk4<T>(x[u], qr[u], t);
+                    dot_chunk4<T>(x[u], q_chunk(u), t);
                     acc = u * LANES_PER_ROW < lim ? t : acc;
                 }
             }
-        for (int cb = BLK; cb < nch; cb += BLK / 2) {     // longer rows: the query comes from LDS
+        for (int cb = BLK; cb < nch; cb += TAIL) {        // longer rows: the query comes from LDS
             u4 qv[8];
-            lim -= cb == BLK ? BLK : BLK / 2;
+            lim -= cb == BLK ? BLK : TAIL;
 #pragma unroll
             for (int g = 0; g < 2; ++g)
                 if (cb + g * 4 * LANES_PER_ROW < nch) {
@@ -282,7 +294,7 @@ __global__ __launch_bounds__(GRAPH_THREADS, 2) void graph_search_kernel(
         return group_sum((acc[0] + acc[1]) + (acc[2] + acc[3]));
     };
     auto score_row = [&](int v) -> float {
-        u4 x[16];
+        u4 x[NX];
         row_issue(v, x);
         return row_dots(v, x);
     };
@@ -357,7 +369,7 @@ __global__ __launch_bounds__(GRAPH_THREADS, 2) void graph_search_kernel(
     int aid0 = -1, aid1 = -1, tog = 0;                    // whose adjacency rows adj[0], adj[1] hold
     int node = entry, p = 0;                              // the node being expanded and its list index
     if (tid == 0) li(0)[0] = (uint32_t)entry | EXPANDED;  // (scans leave entry p out by index as well)
-    u4 x[16];
+    u4 x[NX];
     int v = -1, fresh = 0;                                // this group's neighbour of `node`; to be scored?
     uint32_t seen = 0;                                    // NS: the word of the exact visited set that holds v
     float *ema_s = reinterpret_cast<float *>(adj_id + 3);

@@ -67,6 +67,7 @@ hipError_t launch_flat_f32(int kp, const float *X, int64_t N, int d, const float
 hipError_t launch_flat_merge(int kp, const Cand *partial, int P, int B, int k, int32_t *ids, float *scores,
                              const int *count, const Cand *cand, int cap, hipStream_t stream);
 
+constexpr int GRAPH_DENSE_MIN_B = 1280;   // batches beyond this run three graph-search workgroups per compute unit
 constexpr int GRAPH_EF_DOUBLE = 2048;    // candidate lists up to this length are double-buffered in LDS
 // cus workgroups of 8 waves, each wave iters x 8 MFMA 32x32x16 fp16 (32768 flop each) on register operands
 hipError_t launch_mfma_rate(bool random_operands, int cus, int iters, float *sink, hipStream_t stream);

@@ -405,27 +405,37 @@ def test_graph_random_configurations():
     assert strict_total >= total - max(2, total // 50)
 
 
-def test_graph_batch_larger_than_one_resident_round():
-    """More queries than workgroups fit on the chip at once (two per compute unit): later
-    workgroups start in LDS that earlier ones left behind.  Every row against the oracle."""
-    N, B = 20_000, 3000
-    c = synth.make_corpus(N, 64, 16, seed=31, dtype=torch.float16, zipf_a=None, sigma=0.3)
+@pytest.mark.parametrize("N,d,B,dtype", [(20_000, 64, 3000, torch.float16), (6000, 776, 1500, torch.float16),
+                                          (5000, 1032, 1400, torch.bfloat16), (5000, 260, 1400, torch.float32)])
+def test_graph_batch_larger_than_one_resident_round(N, d, B, dtype):
+    """More queries than workgroups fit on the chip at once: later workgroups start in LDS that earlier
+    ones left behind, and batches this large run the kernel variant that keeps the query in LDS (three
+    workgroups per compute unit; rows longer than 64 chunks go through its second loop).  Every row
+    against the oracle."""
+    c = synth.make_corpus(N, d, 16, seed=31, dtype=dtype, zipf_a=None, sigma=0.3)
     q = synth.make_queries(c, B)
     g = synth.ring_union(synth.knn_graph(c.x.to(DEV), 14).cpu()).contiguous()
     gen = torch.Generator().manual_seed(1)
     entries = torch.randint(0, N, (B, 3), generator=gen, dtype=torch.int32)
     xd, gd, qd = c.x.to(DEV), g.to(DEV), q.to(DEV)
-    xn, qn, gn = c.x.numpy(), q.numpy(), g.numpy()
+    name = np_dtype_name(c.x)
+    xn, qn, gn = to_np(c.x), to_np(q), g.numpy()
     for ef, ent in ((32, None), (32, entries), (600, None)):
         if ent is None:
             ids, sc = ann.ann_graph_search_typed(xd, gd, 9, qd, 3, ef)
         else:
             ids, sc = ann.ann_graph_search_multi_typed(xd, gd, ent.to(DEV), qd, 3, ef)
         torch.cuda.synchronize()
-        o_ids, _, o_sc64, _, _ = oracle.graph_search(xn, gn, 9, qn, 3, ef, entries=None if ent is None else ent.numpy())
-        strict, tolerant, n = compare_topk(ids.cpu().numpy(), sc.cpu().numpy(), o_ids, o_sc64, xn, qn)
-        say(f"graph B={B} ef={ef} entries={'shared' if ent is None else '3 per query'}: strict {strict}/{n}")
-        assert strict >= n - n // 200
+        o_ids, _, o_sc64, _, _ = oracle.graph_search(xn, gn, 9, qn, 3, ef, entries=None if ent is None else ent.numpy(), dtype=name)
+        strict, tolerant, n = compare_topk(ids.cpu().numpy(), sc.cpu().numpy(), o_ids, o_sc64, xn, qn, dtype=name)
+        say(f"graph N={N} d={d} B={B} ef={ef} entries={'shared' if ent is None else '3 per query'}: strict {strict}/{n}")
+        assert strict >= n - max(2, n // 200)
+        # a small batch of the same queries runs the other kernel variant: same answers
+        few, few_sc = (ann.ann_graph_search_typed(xd, gd, 9, qd[:64].contiguous(), 3, ef) if ent is None else
+                       ann.ann_graph_search_multi_typed(xd, gd, ent[:64].contiguous().to(DEV), qd[:64].contiguous(), 3, ef))
+        torch.cuda.synchronize()
+        assert torch.equal(few, ids[:64])
+        assert float((few_sc - sc[:64]).abs().max()) < 1e-5
 
 
 def test_graph_padding_when_few_nodes_are_reachable():
