@@ -313,6 +313,45 @@ def with_reverse_edges(graph: torch.Tensor, x: torch.Tensor, n_forward: Optional
     return out
 
 
+def diversity_pruned(graph: torch.Tensor, x: torch.Tensor, keep: int, *, row_block: int = 4096) -> Tuple[torch.Tensor, float]:
+    """The neighbour-selection heuristic of HNSW-style index builders applied to the rows of a k-NN graph
+    (the rows are sorted best first): a candidate c of node i is taken only if it is closer to i than to every
+    neighbour taken before it, score(c, i) > score(c, s) for all selected s; at most `keep` are taken, candidates
+    passed over fill what is left of the `keep` slots (in their order), the other slots are -1.  Returns the
+    pruned graph [N, R] (same shape) and the fraction of candidates the rule passed over.  Input preparation
+    only: the graph is an input of the search."""
+    N, R = graph.shape
+    dev = graph.device
+    out = torch.full_like(graph, -1)
+    passed_over = 0
+    total = 0
+    for r0 in range(0, N, row_block):
+        gi = graph[r0:r0 + row_block].long()
+        ok = gi >= 0
+        nb = x[gi.clamp(min=0)].float()                              # [rows, R, d]
+        to_node = (nb * x[r0:r0 + row_block].float()[:, None, :]).sum(-1)   # score(c, i)
+        among = torch.bmm(nb, nb.transpose(1, 2))                    # score(c, c')
+        rows = gi.shape[0]
+        taken = torch.zeros(rows, R, dtype=torch.bool, device=dev)
+        closest_taken = torch.full((rows, R), -math.inf, device=dev)  # max over taken s of score(c, s)
+        n_taken = torch.zeros(rows, dtype=torch.long, device=dev)
+        for c in range(R):
+            take = ok[:, c] & (to_node[:, c] > closest_taken[:, c]) & (n_taken < keep)
+            taken[:, c] = take
+            n_taken += take.long()
+            closest_taken = torch.where(take[:, None], torch.maximum(closest_taken, among[:, :, c]), closest_taken)
+        skipped = ok & ~taken
+        passed_over += int(skipped.sum())
+        total += int(ok.sum())
+        # selected first, then the passed-over candidates, each group in its order, `keep` slots in all
+        order = torch.argsort((~taken).to(torch.int8) + 2 * (~ok).to(torch.int8), dim=1, stable=True)
+        cand = torch.gather(gi, 1, order)
+        valid = torch.gather(ok, 1, order)
+        cand = torch.where(valid & (torch.arange(R, device=dev)[None, :] < keep), cand, torch.full_like(cand, -1))
+        out[r0:r0 + row_block] = cand.to(graph.dtype)
+    return out, passed_over / max(1, total)
+
+
 def ring_union(graph: torch.Tensor) -> torch.Tensor:
     """Append the two ring edges i -> i±1 (mod N) to every row: a strongly
     connected test graph for the 'ef >= N equals exact search' special case."""

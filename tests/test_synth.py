@@ -135,3 +135,20 @@ def test_reverse_edge_graph_matches_brute_force():
             loose += 1
     assert loose <= N // 100
     assert (hn[:, : R // 2] == gn[:, : R // 2])[gn[:, : R // 2] >= 0].all()
+
+
+def test_diversity_pruning_rule_on_a_line():
+    """Points on a line around node 0: candidates on the same side as an already selected closer neighbour are
+    passed over (they are closer to that neighbour than to the node), the first one on the other side is taken."""
+    import torch
+    from paper_2505_12065_amd import synth
+    # 1-d positions embedded on the unit circle at small angles, so that larger inner product = closer
+    ang = torch.tensor([0.0, 0.010, 0.020, 0.030, -0.015, -0.040])
+    x = torch.stack([torch.cos(ang), torch.sin(ang)], 1)
+    g = torch.tensor([[1, 4, 2, 3, 5], [-1] * 5, [-1] * 5, [-1] * 5, [-1] * 5, [-1] * 5], dtype=torch.int32)   # node 0: by closeness
+    pruned, frac = synth.diversity_pruned(g, x, keep=5)
+    # taken: 1 (closest), 4 (other side); passed over: 2 and 3 (closer to 1), 5 (closer to 4); they fill the row after the taken ones
+    assert pruned[0].tolist() == [1, 4, 2, 3, 5]
+    assert frac == 3 / 5
+    pruned2, _ = synth.diversity_pruned(g, x, keep=2)
+    assert pruned2[0].tolist() == [1, 4, -1, -1, -1]
