@@ -91,12 +91,30 @@ const char *ann_last_error(void);
  * Every corpus row is scored against every query; the score matrix is never
  * materialised.  Uses the library workspace of the current device: per query P
  * lists of 4 or 16 (score, id) pairs (P = number of corpus slabs, at most 2048) and,
- * for k > 4 on corpora of 128 Ki rows or more, a candidate array of 4096 pairs;
+ * for k > 4 on corpora of 128 Ki rows or more (at any corpus size when B > 64 and d is
+ * a multiple of 32), a candidate array of 4096 pairs;
  * ann_flat_workspace_bytes gives the exact size.
  */
 int ann_flat_search_typed(const void *corpus, int64_t N, int32_t d, int32_t dtype,
                           const void *queries, int32_t B, int32_t k,
                           int32_t *ids, float *scores, void *stream);
+
+/* Continuation of an exact retrieval (Section 2.1, exact search; the proximity graph of the
+ * approximate retriever is built offline from the same embeddings, Appendix B.3), for callers that
+ * need more than ANN_K_MAX rows per query, such as the k-NN rows of that graph: the k best rows
+ * among those that come strictly after the pair (after_scores[b], after_ids[b]) in the order, i.e.
+ * rows with a smaller score, or the same score and a larger id.  Feeding the last pair of one answer
+ * into the next call enumerates the corpus in order, k rows at a time; when fewer than k rows are
+ * left the tail is id -1, score -inf.  The boundary score is compared with the fp32 scores the
+ * kernels compute, so pass the scores as they were returned, and use the same B, k and element type
+ * for every page (each kernel variant sums in its own order; a row within one rounding of the
+ * boundary could otherwise be seen on the other side of it).
+ *   after_scores, after_ids   device [B] float / int32, both or neither; NULL = ann_flat_search_typed.
+ *                             A NaN boundary score excludes nothing for that query. */
+int ann_flat_search_after_typed(const void *corpus, int64_t N, int32_t d, int32_t dtype,
+                                const void *queries, int32_t B, int32_t k,
+                                const float *after_scores, const int32_t *after_ids,
+                                int32_t *ids, float *scores, void *stream);
 
 /* Same, for a corpus of the default element type (ANN_F16 unless changed by
  * ann_set_default_dtype). */

@@ -54,7 +54,8 @@ def _load():
         lib.oracle_score.argtypes = [c.c_void_p, c.c_int32, c.c_int, c.c_int64, c.c_void_p, c.c_int32]
         lib.oracle_flat_search.restype = c.c_int
         lib.oracle_flat_search.argtypes = [c.c_void_p, c.c_int64, c.c_int32, c.c_int, c.c_void_p,
-                                           c.c_int32, c.c_int32, c.c_void_p, c.c_void_p, c.c_void_p, c.c_int]
+                                           c.c_int32, c.c_int32, c.c_void_p, c.c_void_p,
+                                           c.c_void_p, c.c_void_p, c.c_void_p, c.c_int]
         lib.oracle_graph_search.restype = c.c_int
         lib.oracle_graph_search.argtypes = [c.c_void_p, c.c_int64, c.c_int32, c.c_int, c.c_void_p, c.c_int32,
                                             c.c_int32, c.c_void_p, c.c_int32, c.c_void_p, c.c_int32, c.c_int32, c.c_int32,
@@ -100,16 +101,27 @@ def score(corpus, queries, b: int, row: int, dtype: Optional[str] = None) -> flo
     return _load().oracle_score(corpus.ctypes.data, corpus.shape[1], code, row, queries.ctypes.data, b)
 
 
-def flat_search(corpus, queries, k: int, *, dtype: Optional[str] = None,
+def flat_search(corpus, queries, k: int, *, after=None, dtype: Optional[str] = None,
                 n_threads: int = 0) -> Tuple[np.ndarray, np.ndarray, np.ndarray]:
-    """Exact top-k.  Returns (ids int32 [B,k], scores fp32 [B,k], scores fp64 [B,k])."""
+    """Exact top-k.  Returns (ids int32 [B,k], scores fp32 [B,k], scores fp64 [B,k]).
+    after = (scores fp64 [B], ids int32 [B]): only rows that come strictly after that pair in the order
+    (score descending, id ascending) are candidates: the continuation of an earlier answer (pass the
+    binary64 scores this function returned)."""
     corpus, queries, code = _prep(corpus, queries, dtype)
     N, d = corpus.shape
     B = queries.shape[0]
     ids = np.empty((B, k), np.int32)
     sc = np.empty((B, k), np.float32)
     sc64 = np.empty((B, k), np.float64)
+    a_s = a_i = None
+    if after is not None:
+        a_s = np.ascontiguousarray(after[0], dtype=np.float64)
+        a_i = np.ascontiguousarray(after[1], dtype=np.int32)
+        if a_s.shape != (B,) or a_i.shape != (B,):
+            raise ValueError("after = (scores [B], ids [B]) expected")
     rc = _load().oracle_flat_search(corpus.ctypes.data, N, d, code, queries.ctypes.data, B, k,
+                                    a_s.ctypes.data if a_s is not None else None,
+                                    a_i.ctypes.data if a_i is not None else None,
                                     ids.ctypes.data, sc.ctypes.data, sc64.ctypes.data, n_threads)
     if rc != 0:
         raise ValueError("oracle_flat_search: bad arguments")

@@ -137,15 +137,23 @@ double oracle_score(const void *corpus, int32_t d, int dtype, int64_t row,
 /*
  * Exact retrieval.  ids[B,k], scores[B,k] (fp32), scores64[B,k] optional.
  * A row whose score is NaN has no place in the order and is left out; should fewer than
- * k rows remain, the tail is (id -1, score -inf).  Returns 0, or -1 on bad arguments /
- * allocation failure.
+ * k rows remain, the tail is (id -1, score -inf).
+ *
+ * Continuation ("the next k"): with after_scores / after_ids (both [B], or both NULL) only rows
+ * that come strictly after the pair (after_scores[b], after_ids[b]) in the order are candidates
+ * of query b, i.e. rows with a smaller score, or the same score and a larger id.  Feeding the
+ * last pair of one answer (its binary64 score) into the next call enumerates the corpus in
+ * order, k rows at a time.  A NaN after_score excludes nothing.
+ * Returns 0, or -1 on bad arguments / allocation failure.
  */
 int oracle_flat_search(const void *corpus, int64_t N, int32_t d, int dtype,
                        const void *queries, int32_t B, int32_t k,
+                       const double *after_scores, const int32_t *after_ids,
                        int32_t *ids, float *scores, double *scores64, int threads)
 {
     if (!corpus || !queries || !ids || !scores || N < 1 || d < 1 || B < 1 || k < 1 || k > N)
         return -1;
+    if ((after_scores == NULL) != (after_ids == NULL)) return -1;
     prepare_tables();
     int failed = 0;
 #pragma omp parallel for schedule(dynamic, 1) num_threads(use_threads(threads))
@@ -158,6 +166,9 @@ int oracle_flat_search(const void *corpus, int64_t N, int32_t d, int dtype,
         for (int64_t n = 0; n < N; ++n) {
             const double s = score_row(corpus, n, d, dtype, q);
             if (s != s) continue;
+            if (after_scores && after_scores[b] == after_scores[b] &&
+                !precedes(after_scores[b], after_ids[b], s, (int32_t)n))
+                continue;
             all[m].s = s;
             all[m].id = (int32_t)n;
             ++m;

@@ -27,7 +27,7 @@ EXPORTS = ("ann_version", "ann_last_error", "ann_flat_search_typed", "ann_flat_s
            "ann_graph_search_entries_typed", "ann_gather_ids", "ann_timing_enable", "ann_timing_read",
            "ann_measure_mfma_rate", "ann_priority_order", "ann_flat_search_static",
            "ann_graph_search_multi_typed", "ann_timing_read_each",
-           "ann_set_workspace")
+           "ann_set_workspace", "ann_flat_search_after_typed")
 
 
 class AnnError(RuntimeError):
@@ -54,6 +54,7 @@ def lib() -> ctypes.CDLL:
         L.ann_last_error.restype = c.c_char_p
         L.ann_flat_search_typed.argtypes = [vp, i64, i32, i32, vp, i32, i32, vp, vp, vp]
         L.ann_flat_search.argtypes = [vp, i64, i32, vp, i32, i32, vp, vp, vp]
+        L.ann_flat_search_after_typed.argtypes = [vp, i64, i32, i32, vp, i32, i32, vp, vp, vp, vp, vp]
         L.ann_flat_search_static.argtypes = [vp, i64, i32, i32, vp, i32, i32, vp, vp, vp]
         L.ann_graph_search_typed.argtypes = [vp, i64, i32, i32, vp, i32, i32, vp, i32, i32, i32, vp, vp, vp]
         L.ann_graph_search.argtypes = [vp, vp, i32, i32, vp, i32, i32, i32, vp, vp, vp]
@@ -119,17 +120,28 @@ def ann_last_error() -> str:
     return lib().ann_last_error().decode()
 
 
-def ann_flat_search_typed(corpus: torch.Tensor, queries: torch.Tensor, k: int, *, ids=None, scores=None,
+def ann_flat_search_typed(corpus: torch.Tensor, queries: torch.Tensor, k: int, *, after=None, ids=None, scores=None,
                           stream=None) -> Tuple[torch.Tensor, torch.Tensor]:
-    """Exact top-k of every query over the corpus; element type taken from the tensors."""
+    """Exact top-k of every query over the corpus; element type taken from the tensors.
+    after = (scores float32 [B], ids int32 [B]) device tensors: the continuation entry point, the k best rows
+    that come strictly after that pair in the order."""
     _matrix(corpus, "corpus"), _matrix(queries, "queries")
     if queries.dtype != corpus.dtype or queries.shape[1] != corpus.shape[1]:
         raise ValueError("queries must have the corpus' element type and dimension")
     (N, d), B = corpus.shape, queries.shape[0]
     ids, scores = _outputs(B, k, corpus.device, ids, scores)
     with torch.cuda.device(corpus.device):
-        _check(lib().ann_flat_search_typed(corpus.data_ptr(), N, d, _DTYPES[corpus.dtype], queries.data_ptr(), B, k,
-                                           ids.data_ptr(), scores.data_ptr(), _stream(stream)))
+        if after is None:
+            _check(lib().ann_flat_search_typed(corpus.data_ptr(), N, d, _DTYPES[corpus.dtype], queries.data_ptr(), B, k,
+                                               ids.data_ptr(), scores.data_ptr(), _stream(stream)))
+        else:
+            a_s, a_i = after
+            if a_s.dtype != torch.float32 or a_i.dtype != torch.int32 or tuple(a_s.shape) != (B,) or tuple(a_i.shape) != (B,) \
+                    or not (a_s.is_cuda and a_i.is_cuda and a_s.is_contiguous() and a_i.is_contiguous()):
+                raise ValueError("after must be (float32 [B], int32 [B]) contiguous device tensors")
+            _check(lib().ann_flat_search_after_typed(corpus.data_ptr(), N, d, _DTYPES[corpus.dtype], queries.data_ptr(),
+                                                     B, k, a_s.data_ptr(), a_i.data_ptr(), ids.data_ptr(),
+                                                     scores.data_ptr(), _stream(stream)))
     return ids, scores
 
 

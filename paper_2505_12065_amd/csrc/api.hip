@@ -196,7 +196,8 @@ struct FlatPlan {
 constexpr int WIDE_MIN_B = 65;   // smallest batch sent to the matrix-core path
 constexpr int EMIT_CAP = 4096;   // candidate-array entries per query (k > 4), a multiple of 16
 constexpr int SAMPLE_STRIDE = 64; // a sampling pass scores every 64th row
-constexpr int64_t SAMPLE_MIN_N = 64 * 1024, EMIT_MIN_N = 128 * 1024;
+constexpr int64_t SAMPLE_MIN_N = 64 * 1024;
+constexpr int64_t EMIT_MIN_N = 128 * 1024;   // smallest corpus with candidate arrays when the batch streams
 
 FlatPlan flat_plan(int cus, int64_t N, int d, int dtype, int B, int k, bool allow_emit = true) {
     FlatPlan pl;
@@ -212,7 +213,11 @@ FlatPlan flat_plan(int cus, int64_t N, int d, int dtype, int B, int k, bool allo
     // the k-th best of every 64th row (scored exactly by a short first pass), so about 64 k rows per
     // query pass it; an array that overflows all the same (heavily tied scores) is repaired by the
     // streaming kernel with lists of 16, which does no work otherwise.
-    if (allow_emit && dtype != ANN_F32 && pl.kp == 16 && N >= EMIT_MIN_N) {
+    // A batch large enough for the matrix-core kernel, which keeps no lists of 16, takes this path at
+    // any corpus size (a sample of fewer than k rows gives a bound of -inf: every row is a candidate);
+    // a small batch streams, and lists of 16 are fine until the corpus is large.
+    const bool wide_batch = B >= WIDE_MIN_B && d % 32 == 0;
+    if (allow_emit && dtype != ANN_F32 && pl.kp == 16 && (wide_batch || N >= EMIT_MIN_N)) {
         const FlatPlan st = flat_plan(cus, N, d, dtype, B, k, false);     // repair pass
         const FlatPlan m4 = flat_plan(cus, N, d, dtype, B, 4, false);     // geometry of sampling and main pass
         pl.emit = true;
@@ -225,7 +230,7 @@ FlatPlan flat_plan(int cus, int64_t N, int d, int dtype, int B, int k, bool allo
         pl.pstride = st.P;
         const int64_t nv = (N + SAMPLE_STRIDE - 1) / SAMPLE_STRIDE;
         if (pl.wide_ntg > 0) {
-            const int64_t stiles = (nv + 255) / 256;                       // >= 8
+            const int64_t stiles = (nv + 255) / 256;
             pl.sample_P = (int)(stiles < pl.P ? stiles : pl.P);
         } else {
             const int64_t swaves = (nv + 15) / 16;                         // one 16-row tile per wave at least
@@ -294,7 +299,8 @@ FlatPlan flat_plan(int cus, int64_t N, int d, int dtype, int B, int k, bool allo
 // 16-bit corpus, streaming kernel over all B queries in one launch: groups of 16 nqg_max queries are
 // served one after the other inside the kernel (kp 0: candidate-array mode)
 int flat_stream_all(int kp, int nqg_max, int P, const void *X, int64_t N, int d, int dtype, const void *Q, int B,
-                    Cand *partial, StreamOpts o, bool timed_launch, hipStream_t stream) {
+                    Cand *partial, StreamOpts o, After after, bool timed_launch, hipStream_t stream) {
+    o.after = after;
     const int group = 16 * nqg_max;
     const int nqg = B > group ? nqg_max : (B + 15) / 16;
     o.passes = B > group ? (B + group - 1) / group : 1;
@@ -308,7 +314,7 @@ int flat_stream_all(int kp, int nqg_max, int P, const void *X, int64_t N, int d,
 }
 
 int flat_search_emit(const FlatPlan &pl, const void *X, int64_t N, int d, int dtype, const void *Q, int B, int k,
-                     int32_t *ids, float *scores, char *ws, hipStream_t stream) {
+                     int32_t *ids, float *scores, char *ws, After after, hipStream_t stream) {
     Cand *partial = reinterpret_cast<Cand *>(ws);
     Cand *sample = reinterpret_cast<Cand *>(ws + pl.sample_ofs);
     float *thr = reinterpret_cast<float *>(ws + pl.thr_ofs);
@@ -317,12 +323,12 @@ int flat_search_emit(const FlatPlan &pl, const void *X, int64_t N, int d, int dt
     // sampling pass: every 64th row, the best 4 per slab and query
     if (pl.wide_ntg > 0) {
         hipError_t e = launch_flat_wide(dtype, 1, X, N, d, Q, B, sample, pl.sample_P, pl.wide_ntg, 0, nullptr, pl.sample_P,
-                                        0, nullptr, SAMPLE_STRIDE, stream);
+                                        0, nullptr, SAMPLE_STRIDE, after, stream);
         if (int rc = check_launch("flat_wide_kernel (sample)", e)) return rc;
     } else {
         StreamOpts o;
         o.row_stride = SAMPLE_STRIDE;
-        if (int rc = flat_stream_all(4, pl.nqg_max, pl.sample_P, X, N, d, dtype, Q, B, sample, o, false, stream)) return rc;
+        if (int rc = flat_stream_all(4, pl.nqg_max, pl.sample_P, X, N, d, dtype, Q, B, sample, o, after, false, stream)) return rc;
     }
     if (int rc = check_launch("flat_sample_kth_kernel", launch_flat_sample_kth(sample, pl.sample_P, B, k, thr, nullptr, 0, 0, cnt, stream)))
         return rc;
@@ -331,7 +337,7 @@ int flat_search_emit(const FlatPlan &pl, const void *X, int64_t N, int d, int dt
         hipError_t e;
         {
             TimedScope timed(ANN_KERNEL_FLAT_WIDE, stream);
-            e = launch_flat_wide(dtype, 2, X, N, d, Q, B, cand, pl.P, pl.wide_ntg, 0, thr, pl.emit_cap, 0, cnt, 1, stream);
+            e = launch_flat_wide(dtype, 2, X, N, d, Q, B, cand, pl.P, pl.wide_ntg, 0, thr, pl.emit_cap, 0, cnt, 1, after, stream);
         }
         if (int rc = check_launch("flat_wide_kernel (candidates)", e)) return rc;
     } else {
@@ -339,26 +345,26 @@ int flat_search_emit(const FlatPlan &pl, const void *X, int64_t N, int d, int dt
         o.thr = thr;
         o.count = cnt;
         o.cap = pl.emit_cap;
-        if (int rc = flat_stream_all(0, pl.nqg_max, pl.P, X, N, d, dtype, Q, B, cand, o, true, stream)) return rc;
+        if (int rc = flat_stream_all(0, pl.nqg_max, pl.P, X, N, d, dtype, Q, B, cand, o, after, true, stream)) return rc;
     }
     // repair pass: returns at once unless a candidate array overflowed
     StreamOpts o;
     o.need = cnt;
     o.need_above = pl.emit_cap;
-    if (int rc = flat_stream_all(pl.kp, pl.st_nqg_max, pl.st_P, X, N, d, dtype, Q, B, partial, o, false, stream)) return rc;
+    if (int rc = flat_stream_all(pl.kp, pl.st_nqg_max, pl.st_P, X, N, d, dtype, Q, B, partial, o, after, false, stream)) return rc;
     return check_launch("flat_merge_kernel",
                         launch_flat_merge(pl.kp, partial, pl.st_P, B, k, ids, scores, cnt, cand, pl.emit_cap, stream));
 }
 
 int flat_search_run(const FlatPlan &pl, const void *X, int64_t N, int d, int dtype, const void *Q, int B, int k,
-                    int32_t *ids, float *scores, Cand *partial, hipStream_t stream) {
-    if (pl.emit) return flat_search_emit(pl, X, N, d, dtype, Q, B, k, ids, scores, reinterpret_cast<char *>(partial), stream);
+                    int32_t *ids, float *scores, Cand *partial, After after, hipStream_t stream) {
+    if (pl.emit) return flat_search_emit(pl, X, N, d, dtype, Q, B, k, ids, scores, reinterpret_cast<char *>(partial), after, stream);
     if (dtype == ANN_F32) {
         hipError_t e;
         {
             TimedScope timed(ANN_KERNEL_FLAT_F32, stream);
             e = launch_flat_f32(pl.kp, static_cast<const float *>(X), N, d, static_cast<const float *>(Q), B, partial,
-                                pl.P, stream);
+                                pl.P, after, stream);
         }
         if (int rc = check_launch("flat_f32_kernel", e)) return rc;
     } else if (pl.wide_ntg > 0) {
@@ -368,7 +374,7 @@ int flat_search_run(const FlatPlan &pl, const void *X, int64_t N, int d, int dty
             float *thr = reinterpret_cast<float *>(reinterpret_cast<char *>(partial) + pl.thr_ofs);
             const bool skip = pl.sample_skip > 0;
             hipError_t e = launch_flat_wide(dtype, 1, X, skip ? (int64_t)pl.sample_skip * 256 : N, d, Q, B, sample, pl.sample_P,
-                                            pl.wide_ntg, 0, nullptr, pl.sample_P, 0, nullptr, skip ? 1 : SAMPLE_STRIDE, stream);
+                                            pl.wide_ntg, 0, nullptr, pl.sample_P, 0, nullptr, skip ? 1 : SAMPLE_STRIDE, after, stream);
             if (int rc = check_launch("flat_wide_kernel (sample)", e)) return rc;
             e = launch_flat_sample_kth(sample, pl.sample_P, B, k, thr, skip ? partial : nullptr, pl.pstride, pl.P, nullptr,
                                        stream);
@@ -379,11 +385,11 @@ int flat_search_run(const FlatPlan &pl, const void *X, int64_t N, int d, int dty
         {
             TimedScope timed(ANN_KERNEL_FLAT_WIDE, stream);
             e = launch_flat_wide(dtype, 0, X, N, d, Q, B, partial, pl.P, pl.wide_ntg, pl.sample_skip, thr0, pl.pstride, 0,
-                                 nullptr, 1, stream);
+                                 nullptr, 1, after, stream);
         }
         if (int rc = check_launch("flat_wide_kernel", e)) return rc;
     } else {
-        if (int rc = flat_stream_all(pl.kp, pl.nqg_max, pl.P, X, N, d, dtype, Q, B, partial, StreamOpts(), true, stream)) return rc;
+        if (int rc = flat_stream_all(pl.kp, pl.nqg_max, pl.P, X, N, d, dtype, Q, B, partial, StreamOpts(), after, true, stream)) return rc;
     }
     return check_launch("flat_merge_kernel", launch_flat_merge(pl.kp, partial, pl.pstride, B, k, ids, scores, nullptr, nullptr, 0, stream));
 }
@@ -546,9 +552,22 @@ int ann_release_workspace(void) {
 
 int ann_flat_search_typed(const void *corpus, int64_t N, int32_t d, int32_t dtype, const void *queries,
                           int32_t B, int32_t k, int32_t *ids, float *scores, void *stream) {
+    return ann_flat_search_after_typed(corpus, N, d, dtype, queries, B, k, nullptr, nullptr, ids, scores, stream);
+}
+
+int ann_flat_search_after_typed(const void *corpus, int64_t N, int32_t d, int32_t dtype, const void *queries,
+                                int32_t B, int32_t k, const float *after_scores, const int32_t *after_ids,
+                                int32_t *ids, float *scores, void *stream) {
     if (B == 0) return ANN_OK;                            // an empty batch: nothing to do
     if (int rc = check_common(corpus, N, d, dtype, queries, B, k, ids, scores)) return rc;
     if (k > ANN_K_MAX) return fail(ANN_ERR_INVALID, "k = %d exceeds ANN_K_MAX = %d", k, ANN_K_MAX);
+    if ((after_scores == nullptr) != (after_ids == nullptr))
+        return fail(ANN_ERR_INVALID, "after_scores and after_ids must be given together");
+    if ((reinterpret_cast<uintptr_t>(after_scores) | reinterpret_cast<uintptr_t>(after_ids)) & 3)
+        return fail(ANN_ERR_ALIGNMENT, "after_scores and after_ids must be 4-byte aligned");
+    After after;
+    after.s = after_scores;
+    after.id = after_ids;
     std::lock_guard<std::mutex> lock(g_mu);
     DeviceState *st = nullptr;
     if (int rc = device_state(&st)) return rc;
@@ -557,7 +576,7 @@ int ann_flat_search_typed(const void *corpus, int64_t N, int32_t d, int32_t dtyp
     void *ws = nullptr;
     if (int rc = workspace_for(st, &st->ws, &st->ws_bytes, pl.ws_bytes, &ws)) return rc;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    return flat_search_run(pl, corpus, N, d, dtype, queries, B, k, ids, scores, static_cast<Cand *>(ws), s);
+    return flat_search_run(pl, corpus, N, d, dtype, queries, B, k, ids, scores, static_cast<Cand *>(ws), after, s);
 }
 
 int ann_flat_search(const void *corpus, int64_t N, int32_t d, const void *queries, int32_t B, int32_t k,
@@ -585,7 +604,7 @@ int ann_flat_search_static(const void *corpus, int64_t N, int32_t d, int32_t dty
                     pl.ws_bytes, ANN_STATIC_WORKSPACE_BYTES);
     g_timing_off = true;                                  // event pairs would have to be created
     const int rc = flat_search_run(pl, corpus, N, d, dtype, queries, B, k, ids, scores,
-                                   static_cast<Cand *>(st->scratch_ptr), static_cast<hipStream_t>(stream));
+                                   static_cast<Cand *>(st->scratch_ptr), After(), static_cast<hipStream_t>(stream));
     g_timing_off = false;
     return rc;
 }

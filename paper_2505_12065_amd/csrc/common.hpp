@@ -224,6 +224,19 @@ __device__ __forceinline__ f16v mfma32<BF16>(u4 a, u4 b, f16v c) {
     return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(b8, a), __builtin_bit_cast(b8, b), c, 0, 0, 0);
 }
 
+// Continuation of an exact search: with a boundary pair per query, only rows that come strictly
+// after (s[q], id[q]) in the order are candidates of query q.  Null pointers: no boundary.
+struct After {
+    const float *s = nullptr;
+    const int *id = nullptr;
+};
+// The score of a row for the selection: unchanged when the row comes after the boundary (or the
+// boundary score is NaN: nothing excluded), NaN otherwise, and a NaN score is never listed.
+__device__ __forceinline__ float after_boundary(float s, int id, float bs, int bid) {
+    const bool keep = bs > s || (bs == s && bid < id) || bs != bs;
+    return keep ? s : __builtin_nanf("");
+}
+
 // One (score, id) pair as stored in the partial-result workspace.
 struct Cand {
     float s;

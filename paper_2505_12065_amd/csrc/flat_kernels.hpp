@@ -53,6 +53,15 @@ __device__ __forceinline__ void flat_stream_pass(const void *__restrict__ X, int
 
     TopList<KP> best[NQG];
     float thr[NQG];
+    float bnd_s[NQG];                                 // continuation: this lane's queries' boundary pairs
+    int bnd_id[NQG];
+    const bool bounded = o.after.s != nullptr;
+#pragma unroll
+    for (int g = 0; g < NQG; ++g) {
+        const int qb = min(q0 + g * 16 + (lane & 15), B - 1);
+        bnd_s[g] = bounded ? o.after.s[qb] : 0.f;
+        bnd_id[g] = bounded ? o.after.id[qb] : 0;
+    }
 #pragma unroll
     for (int g = 0; g < NQG; ++g) {
         best[g].init();
@@ -96,6 +105,12 @@ __device__ __forceinline__ void flat_stream_pass(const void *__restrict__ X, int
         }
 
         const int64_t rbase = tile * 16 + (lane >> 4) * 4;
+        if (bounded) {                                // rows at or before a query's boundary do not take part
+#pragma unroll
+            for (int g = 0; g < NQG; ++g)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) acc[g][i] = after_boundary(acc[g][i], (int)((rbase + i) * S), bnd_s[g], bnd_id[g]);
+        }
         static_for<NQG>([&](auto gc) {
             constexpr int g = decltype(gc)::value;
             const f4 a = acc[g];
@@ -193,7 +208,7 @@ __global__ __launch_bounds__(NWV * 64) void flat_stream_kernel(const void *__res
 template <int KP>
 __global__ __launch_bounds__(256) void flat_f32_kernel(const float *__restrict__ X, int64_t N, int d,
                                                        const float *__restrict__ Q, int B,
-                                                       Cand *__restrict__ partial) {
+                                                       Cand *__restrict__ partial, After after) {
     extern __shared__ __align__(16) unsigned char smem[];
     u4 *qs = reinterpret_cast<u4 *>(smem);            // [8][d/4]
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, nwaves = blockDim.x >> 6;
@@ -209,6 +224,9 @@ __global__ __launch_bounds__(256) void flat_f32_kernel(const float *__restrict__
     TopList<KP> best;
     best.init();
     const int r8 = lane >> 3, c8 = lane & 7;
+    const int qb = min(q0 + c8, B - 1);               // continuation: the boundary pair of this lane's query
+    const float bnd_s = after.s ? after.s[qb] : 0.f;
+    const int bnd_id = after.s ? after.id[qb] : 0;
     const int64_t ngroups = (N + 7) >> 3;
     for (int64_t grp = (int64_t)blockIdx.x * nwaves + wave; grp < ngroups; grp += (int64_t)P * nwaves) {
         const int64_t row = grp * 8 + r8;
@@ -231,6 +249,7 @@ __global__ __launch_bounds__(256) void flat_f32_kernel(const float *__restrict__
             v += __shfl_xor(v, 4);
             if (q == c8) mine = v;
         }
+        if (after.s) mine = after_boundary(mine, (int)row, bnd_s, bnd_id);
         if (row < N && best.admits(mine, (int)row)) best.insert(mine, (int)row);
     }
     best.merge_xor(8);

@@ -22,19 +22,19 @@ size_t f32_lds_bytes(int d, int waves, int kp) {
 
 namespace {
 template <int KP>
-hipError_t launch_f32(const float *X, int64_t N, int d, const float *Q, int B, Cand *partial, int P,
+hipError_t launch_f32(const float *X, int64_t N, int d, const float *Q, int B, Cand *partial, int P, After after,
                       hipStream_t stream) {
     static size_t big = 0;
     const size_t lds = f32_lds_bytes(d, 4, KP);
     if (hipError_t e = allow_big_lds(reinterpret_cast<const void *>(&flat_f32_kernel<KP>), lds, &big)) return e;
-    hipLaunchKernelGGL((flat_f32_kernel<KP>), dim3(P, (B + 7) / 8), dim3(256), lds, stream, X, N, d, Q, B, partial);
+    hipLaunchKernelGGL((flat_f32_kernel<KP>), dim3(P, (B + 7) / 8), dim3(256), lds, stream, X, N, d, Q, B, partial, after);
     return hipGetLastError();
 }
 }  // namespace
 
 hipError_t launch_flat_f32(int kp, const float *X, int64_t N, int d, const float *Q, int B, Cand *partial, int P,
-                           hipStream_t stream) {
-    return kp == 4 ? launch_f32<4>(X, N, d, Q, B, partial, P, stream) : launch_f32<16>(X, N, d, Q, B, partial, P, stream);
+                           After after, hipStream_t stream) {
+    return kp == 4 ? launch_f32<4>(X, N, d, Q, B, partial, P, after, stream) : launch_f32<16>(X, N, d, Q, B, partial, P, after, stream);
 }
 
 hipError_t launch_flat_merge(int kp, const Cand *partial, int P, int B, int k, int32_t *ids, float *scores,

@@ -111,7 +111,8 @@ __global__ __launch_bounds__(128 * NWN, 2) void flat_wide_kernel(const void *__r
                                                                     int64_t tile_begin,
                                                                     const float *__restrict__ thr_init,
                                                                     int pstride, int pslot0,
-                                                                    int *__restrict__ emit_count, int row_stride) {
+                                                                    int *__restrict__ emit_count, int row_stride,
+                                                                    After after) {
     constexpr bool SELECT = MODE == WIDE_SELECT;
     // WIDE_SELECT may scan every row_stride-th row only (rows 0, S, 2S, ...): all the tiling below
     // then runs over these NV "virtual" rows, and only addresses and reported ids use S
@@ -164,6 +165,15 @@ __global__ __launch_bounds__(128 * NWN, 2) void flat_wide_kernel(const void *__r
             const int q = n0 + tid < B ? n0 + tid : B - 1;
             thr_l[tid] = float_key(thr_init ? thr_init[q] : -INFINITY);
         }
+        // continuation: the boundary pairs of this lane's WNF queries
+        float bnd_s[WNF];
+        int bnd_id[WNF];
+        static_for<WNF>([&](auto jc) {
+            constexpr int j = decltype(jc)::value;
+            const int q = min(n0 + (wn * WNF + j) * 32 + l32, B - 1);
+            bnd_s[j] = after.s ? after.s[q] : 0.f;
+            bnd_id[j] = after.s ? after.id[q] : 0;
+        });
 
         // Block e of a stage (1 KB = 16 rows x 64 B): blocks 0..15 corpus rows, the rest
         // queries.  Lane l fetches row l/4 of the block; LDS slot l%4 of that row receives
@@ -268,13 +278,27 @@ __global__ __launch_bounds__(128 * NWN, 2) void flat_wide_kernel(const void *__r
                 const int rbase = (int)(tile * WIDE_BM) + wm * 128 + 4 * lhi;    // N < 2^31
                 const int nrows = (int)NV;
                 if ((tile + 1) * WIDE_BM > NV) {               // ragged last tile: rows >= N never score
+                    // (NaN, not -inf: a NaN passes no threshold and enters no list, whereas -inf would
+                    // pass a threshold of -inf, which is what a sample with fewer than k rows gives)
                     static_for<4>([&](auto ic) {
                         constexpr int i = decltype(ic)::value;
                         static_for<WNF>([&](auto jc) {
                             constexpr int j = decltype(jc)::value;
 #pragma unroll
                             for (int r = 0; r < 16; ++r)
-                                if (rbase + (i * 32 + 8 * (r / 4) + (r % 4)) >= nrows) acc[i][j][r] = -INFINITY;
+                                if (rbase + (i * 32 + 8 * (r / 4) + (r % 4)) >= nrows) acc[i][j][r] = __builtin_nanf("");
+                        });
+                    });
+                }
+                if (after.s) {                                 // rows at or before a query's boundary do not take part
+                    static_for<4>([&](auto ic) {
+                        constexpr int i = decltype(ic)::value;
+                        static_for<WNF>([&](auto jc) {
+                            constexpr int j = decltype(jc)::value;
+#pragma unroll
+                            for (int r = 0; r < 16; ++r)
+                                acc[i][j][r] = after_boundary(acc[i][j][r], (rbase + (i * 32 + 8 * (r / 4) + (r % 4))) * S,
+                                                              bnd_s[j], bnd_id[j]);
                         });
                     });
                 }

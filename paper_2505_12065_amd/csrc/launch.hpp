@@ -34,6 +34,7 @@ struct StreamOpts {
     int need_above = 0;          //      one of them (repair pass behind the candidate arrays)
     int passes = 1;              // consecutive groups of nqg * 16 queries served by the launch, from q0 on
     int row_stride = 1;          // S > 1: only rows 0, S, 2S, ... are scored (sampling pass)
+    After after;                 // continuation: per-query boundary pairs, or null pointers
     const float *thr = nullptr;  // candidate-array mode: [B] lower bounds of the final k-th best score,
     int *count = nullptr;        //   [B] entry counters (zero on entry; a count past cap means overflow),
     int cap = 0;                 //   entries per query in the candidate array that `partial` then is
@@ -55,13 +56,13 @@ hipError_t launch_flat_stream_bf16(int nqg, int kp, const void *X, int64_t N, in
 int wide_query_tile(int B);
 hipError_t launch_flat_wide(int dtype, int mode, const void *X, int64_t N, int d, const void *Q, int B,
                             Cand *partial, int P, int NTG, int64_t tile_begin, const float *thr_init, int pstride,
-                            int pslot0, int *emit_count, int row_stride, hipStream_t stream);
+                            int pslot0, int *emit_count, int row_stride, After after, hipStream_t stream);
 // thr[q] = k-th best score among the Ps sampled lists of 4 of query q (-inf if fewer), k <= 16;
 // with dst, the 4 best of the sample also become slab pslot of dst[B, pstride, 4]; with count, count[q] = 0
 hipError_t launch_flat_sample_kth(const Cand *src, int Ps, int B, int k, float *thr, Cand *dst, int pstride, int pslot,
                                   int *count, hipStream_t stream);
 hipError_t launch_flat_f32(int kp, const float *X, int64_t N, int d, const float *Q, int B, Cand *partial, int P,
-                           hipStream_t stream);
+                           After after, hipStream_t stream);
 // count == null: merge the P lists of every query.  count given: query q's input is its candidate
 // array cand[q cap ..) of count[q] entries, or, when that overflowed, its P lists (repair pass).
 hipError_t launch_flat_merge(int kp, const Cand *partial, int P, int B, int k, int32_t *ids, float *scores,

@@ -99,6 +99,56 @@ def test_flat_shapes(dtype, N, d, B, k):
     assert strict >= n - max(2, n // 20), (strict, n)
 
 
+@pytest.mark.parametrize("dtype,N,d,B,k", [
+    (torch.float16, 30_000, 128, 9, 16),        # streaming kernel, lists of 16
+    (torch.float16, 200_000, 64, 20, 16),       # streaming kernel, candidate arrays
+    (torch.bfloat16, 70_000, 96, 300, 4),       # matrix-core kernel, lists, sampled thresholds
+    (torch.float16, 700_000, 64, 100, 3),       # matrix-core kernel, the sample is the first tile of every slab
+    (torch.float16, 150_000, 128, 260, 16),     # matrix-core kernel, candidate arrays
+    (torch.float32, 9_000, 64, 11, 16),         # fp32 kernel
+    (torch.float16, 40, 64, 5, 16),             # pages run past the end of a small corpus
+    (torch.float16, 40, 64, 200, 16),           # the same through the matrix-core kernel: the sample has < k rows
+    (torch.bfloat16, 300, 96, 700, 16),         # ragged last tile of 256 rows, threshold of -inf, three query tiles
+    (torch.float16, 5000, 64, 90, 9),           # candidate arrays on a corpus of a few thousand rows
+])
+def test_flat_continuation_pages(dtype, N, d, B, k):
+    """The next k rows after a boundary pair, three pages in a row: each side continues from its own last
+    pair (the GPU from its fp32 score, the oracle from its binary64 score), page against page, and the GPU's
+    pages together against one oracle answer of 3 k rows.  A quarter of the corpus is a copy of other
+    rows, so page boundaries cut through tied scores."""
+    say(f"flat continuation: dtype={dtype} N={N} d={d} B={B} k={k}")
+    c = synth.make_corpus(N, d, 8, seed=N % 89, dtype=dtype, zipf_a=None, sigma=0.3)
+    x = c.x.clone()
+    x[N // 2: N // 2 + N // 4] = x[: N // 4]
+    q = synth.make_queries(c, B)
+    xd, qd = x.to(DEV), q.to(DEV)
+    name = np_dtype_name(x)
+    xn, qn = to_np(x), to_np(q)
+    after_gpu, after_o, pages = None, None, []
+    for page in range(3):
+        ids, sc = ann.ann_flat_search_typed(xd, qd, k, after=after_gpu)
+        torch.cuda.synchronize()
+        o_ids, o_sc, o_sc64 = oracle.flat_search(xn, qn, k, after=after_o, dtype=name)
+        assert int(ids.max()) < N and int(ids.min()) >= -1, page     # padding is -1, never a row number >= N
+        strict, tolerant, n = compare_topk(ids.cpu().numpy(), sc.cpu().numpy(), o_ids, o_sc64, xn, qn, dtype=name)
+        assert strict >= n - max(1, n // 50), (page, strict, n)
+        pages.append(ids.cpu().numpy())
+        if (o_ids[:, -1] < 0).any():
+            break
+        after_gpu = (sc[:, -1].contiguous(), ids[:, -1].contiguous())
+        after_o = (o_sc64[:, -1], o_ids[:, -1])
+    got = np.concatenate(pages, 1)
+    want, _, _ = oracle.flat_search(xn, qn, min(N, got.shape[1]), dtype=name)
+    exact_rows = sum(got[b, :want.shape[1]].tolist() == want[b].tolist() for b in range(B))
+    say(f"  pages concatenated equal one answer of {want.shape[1]} rows for {exact_rows}/{B} queries")
+    assert exact_rows >= B - max(1, B // 50)
+    for b in range(B):
+        row = [i for i in got[b].tolist() if i >= 0]
+        assert len(set(row)) == len(row), b                     # no row twice
+    if N == 40:
+        assert (got[:, 40:] == -1).all() and (np.sort(got[:, :40], 1) == np.arange(40)).all()
+
+
 def test_flat_ties_go_to_lower_id():
     c = synth.make_corpus(4000, 128, 4, seed=5, dtype=torch.float16, zipf_a=None, sigma=0.3)
     x = c.x.clone()
@@ -587,6 +637,48 @@ def test_nan_rows_are_never_listed():
     ids, _ = ann.ann_graph_search_multi_typed(xd, gd, e2.to(DEV), qd, 4, 24)
     torch.cuda.synchronize()
     assert np.array_equal(ids.cpu().numpy(), oracle.graph_search(xn, gn, 0, qn, 4, 24, entries=e2.numpy())[0])
+
+
+@pytest.mark.parametrize("N,d,C,R,dtype", [(50_000, 768, 51, 32, torch.float16), (3000, 64, 40, 32, torch.float16),
+                                            (20_000, 128, 16, 20, torch.bfloat16)])
+def test_graph_rows_built_by_the_library_match_the_generator(N, d, C, R, dtype):
+    """k-NN rows through the library's paged exact search (R + 1 = 33 results per point, 16 per call)
+    against the generator's torch matmul + top-k on the same corpus: rows identical, except where scores
+    within 1e-6 of each other swap (the two sum in different orders); clusters smaller than a page and
+    pools smaller than R included."""
+    from paper_2505_12065_amd import graph_build
+    c = synth.make_corpus(N, d, C, seed=17, sigma=(0.2, 0.5), zipf_a=1.1, dtype=dtype, device=DEV)
+    got = graph_build.knn_rows_by_cluster(c.x, c.labels, c.centroids, R, 8)
+    want = synth.knn_graph_cluster_restricted(c, R, 8)
+    torch.cuda.synchronize()
+    same = (got == want).all(dim=1)
+    say(f"graph rows by the library: N={N} d={d} C={C} R={R}: identical rows {int(same.sum())}/{N}")
+    assert float(same.float().mean()) >= 0.99
+    xf = c.x.float()
+    for i in (~same).nonzero().flatten().tolist()[:200]:
+        a, b = got[i].long(), want[i].long()
+        assert (a >= 0).sum() == (b >= 0).sum(), i
+        sa = torch.sort((xf[a[a >= 0]] * xf[i]).sum(1)).values
+        sb = torch.sort((xf[b[b >= 0]] * xf[i]).sum(1)).values
+        assert torch.allclose(sa, sb, atol=2e-6), i
+        assert i not in a.tolist()
+    # the oracle's exact answer over the pool, for a few rows
+    xn, labels = to_np(c.x), c.labels.numpy()
+    cn = (c.centroids / c.centroids.norm(dim=1, keepdim=True)).numpy().astype(np.float64)
+    name = np_dtype_name(c.x)
+    rng = np.random.default_rng(3)
+    xd = xn.view(np.uint16) if name == "bf16" else xn
+    for i in rng.integers(0, N, 4).tolist():
+        xi = c.x[i].float().cpu().numpy().astype(np.float64)
+        near = np.argsort(-(cn @ xi), kind="stable")[:8]
+        pool = np.nonzero(np.isin(labels, near))[0]
+        o_ids, _, o64 = oracle.flat_search(xd[pool], xd[i:i + 1], min(R + 1, len(pool)), dtype=name)
+        ref = [int(pool[j]) for j in o_ids[0] if j >= 0 and pool[j] != i][:R]
+        row = [v for v in got[i].tolist() if v >= 0]
+        if row != ref:
+            assert sorted(row) == sorted(ref) or np.allclose(
+                np.sort((c.x[row].float().cpu().numpy().astype(np.float64) @ xi)),
+                np.sort((c.x[ref].float().cpu().numpy().astype(np.float64) @ xi)), atol=2e-6), i
 
 
 def test_gather_ids():

@@ -104,6 +104,32 @@ def test_flat_ties_go_to_lower_id():
     assert sc64[0, 0] == sc64[0, 1] == sc64[0, 2]
 
 
+def test_flat_continuation_enumerates_the_corpus_in_order():
+    """Pages of k rows, each started after the last pair of the one before, concatenate to the one answer
+    with all rows; tied scores are split between pages by id."""
+    n, d = 57, 6
+    corpus = unit_rows(n, d)
+    corpus[10] = corpus[3]
+    corpus[41] = corpus[3]                      # three identical rows: a tie that a page boundary will cut
+    q = unit_rows(4, d)
+    full_ids, _, full_sc = oracle.flat_search(corpus, q, n)
+    for k in (1, 5, 16):
+        after, got = None, []
+        for _ in range((n + k - 1) // k):
+            ids, _, sc = oracle.flat_search(corpus, q, k, after=after)
+            got.append(ids)
+            last = np.array([[j for j in range(k) if ids[b, j] >= 0][-1] for b in range(4)])
+            after = (sc[np.arange(4), last], ids[np.arange(4), last])
+        got = np.concatenate(got, 1)
+        assert np.array_equal(got[:, :n], full_ids)
+        assert (got[:, n:] == -1).all()
+    # nothing excluded: a NaN boundary; everything excluded: a boundary after the last row
+    ids, _, _ = oracle.flat_search(corpus, q, 3, after=(np.full(4, np.nan), np.zeros(4, np.int32)))
+    assert np.array_equal(ids, full_ids[:, :3])
+    ids, sc, _ = oracle.flat_search(corpus, q, 3, after=(full_sc[:, -1], full_ids[:, -1]))
+    assert (ids == -1).all() and np.isneginf(sc).all()
+
+
 def test_flat_rejects_bad_arguments():
     corpus = unit_rows(10, 8)
     with pytest.raises(ValueError):
