@@ -677,7 +677,7 @@ static int graph_search_any(const void *corpus, int64_t N, int32_t d, int32_t dt
                             int32_t entry, const int32_t *entries, int32_t n_entries, const void *queries, int32_t B, int32_t k,
                             int32_t ef, int32_t *ids, float *scores, const GraphLds &L, hipStream_t s) {
     std::lock_guard<std::mutex> lock(g_mu);
-    if (ef <= GRAPH_EF_DOUBLE) {
+    if (ef <= GRAPH_EF_DOUBLE && !L.two_level) {
         TimedScope timed(ANN_KERNEL_GRAPH, s);
         return check_launch("graph_search_kernel", launch_graph_search(dtype, corpus, N, d, graph, R, entry, entries, n_entries,
                                                                        queries, B, k, ef, ids, scores, L, s));

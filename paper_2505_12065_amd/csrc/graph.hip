@@ -7,7 +7,7 @@ GraphLds graph_lds_layout(int d, int elem_bytes, int R, int ef) {
     auto up = [](uint32_t x) { return (x + 15u) & ~15u; };
     const bool inplace = ef > GRAPH_EF_DOUBLE;           // long lists: one buffer, merged in place
     auto lay = [&](uint32_t bits) {
-        GraphLds L;
+        GraphLds L{};
         uint32_t off = 0;
         L.rp = (uint32_t)((R + ROWS_PER_PASS - 1) / ROWS_PER_PASS * ROWS_PER_PASS);
         L.cache_bits = bits;
@@ -29,6 +29,41 @@ GraphLds graph_lds_layout(int d, int elem_bytes, int R, int ef) {
         L.total = off;
         return L;
     };
+    // Long lists on graphs of at most 32 slots per node: the two-level list.  The large part has one
+    // buffer of ef entries, the small part two of GRAPH_DELTA; the adjacency rows read ahead take 32
+    // slots each; the words of um double as the position marks of a rebuild.
+    auto lay2 = [&](uint32_t bits) {
+        GraphLds L{};
+        uint32_t off = 0;
+        L.rp = ROWS_PER_PASS;
+        L.cache_bits = bits;
+        L.two_level = 1;
+        L.q = off; off = up(off + (uint32_t)d * elem_bytes);
+        L.ms = off; off = up(off + 4u * (uint32_t)ef);
+        L.mi = off; off = up(off + 4u * (uint32_t)ef);
+        L.ls0 = off; off = up(off + 4u * GRAPH_DELTA);
+        L.li0 = off; off = up(off + 4u * GRAPH_DELTA);
+        L.ls1 = off; off = up(off + 4u * GRAPH_DELTA);
+        L.li1 = off; off = up(off + 4u * GRAPH_DELTA);
+        L.cs = off; off = up(off + 4u * L.rp);
+        L.ci = off; off = up(off + 4u * L.rp);
+        L.cpos = off; off = up(off + 4u * L.rp);
+        L.cache = off; off = up(off + (4u << bits));
+        L.ctl = off; off = up(off + 16u);
+        L.adj = off; off = up(off + 2u * 4u * 32u);
+        L.um = off; off = up(off + 8u * (((uint32_t)ef + 63u) / 64u) + 32u);
+        L.rq = L.co = L.um;                                // (used by the plain loop only)
+        L.total = off;
+        return L;
+    };
+    if (ef > GRAPH_EF_TWO_LEVEL && R <= ROWS_PER_PASS) {
+        uint32_t bits = 14;
+        if (lay2(11).total <= LDS_MAX / 2)
+            while (bits > 11 && lay2(bits).total > LDS_MAX / 2) --bits;
+        while (bits > 10 && lay2(bits).total > LDS_MAX) --bits;
+        const GraphLds L2 = lay2(bits);
+        if (L2.total <= LDS_MAX) return L2;
+    }
     // cache slots: a few times the number of nodes a search scores (about 10 ef), at most 2^14;
     // fewer when that lets two workgroups share a compute unit, or when the list needs the room
     uint32_t want = 10;
@@ -41,14 +76,14 @@ GraphLds graph_lds_layout(int d, int elem_bytes, int R, int ef) {
 }
 
 namespace {
-template <class T, int RPT, bool NS, bool QREG = true>
+template <class T, int RPT, bool NS, bool QREG = true, bool LONG = false>
 hipError_t launch_rp(const void *X, int64_t N, int d, const int32_t *graph, int R, int entry, const void *Q, int B,
                      int k, int ef, int32_t *ids, float *scores, const GraphLds &L, const NonStall &ns,
                      hipStream_t stream) {
     static size_t big = 0;
-    if (hipError_t e = allow_big_lds(reinterpret_cast<const void *>(&graph_search_kernel<T, RPT, NS, QREG>), L.total, &big))
+    if (hipError_t e = allow_big_lds(reinterpret_cast<const void *>(&graph_search_kernel<T, RPT, NS, QREG, LONG>), L.total, &big))
         return e;
-    hipLaunchKernelGGL((graph_search_kernel<T, RPT, NS, QREG>), dim3(B), dim3(GRAPH_THREADS), L.total, stream, X, N, d,
+    hipLaunchKernelGGL((graph_search_kernel<T, RPT, NS, QREG, LONG>), dim3(B), dim3(GRAPH_THREADS), L.total, stream, X, N, d,
                        graph, R, entry, Q, k, ef, ids, scores, L, ns);
     return hipGetLastError();
 }
@@ -62,6 +97,12 @@ hipError_t launch(const void *X, int64_t N, int d, const int32_t *graph, int R, 
     if constexpr (!NS) {
         if (L.rp == 32 && B > GRAPH_DENSE_MIN_B && 3 * (size_t)L.total + 3 * 1024 <= LDS_MAX)
             return launch_rp<T, 32, false, false>(X, N, d, graph, R, entry, Q, B, k, ef, ids, scores, L, ns, stream);
+    }
+    if constexpr (NS) {
+        if (L.two_level)
+            return launch_rp<T, 32, true, true, true>(X, N, d, graph, R, entry, Q, B, k, ef, ids, scores, L, ns, stream);
+    } else if (L.two_level) {
+        return hipErrorInvalidValue;                      // long lists run with the exact visited set
     }
     return L.rp == 32 ? launch_rp<T, 32, NS>(X, N, d, graph, R, entry, Q, B, k, ef, ids, scores, L, ns, stream)
                       : launch_rp<T, 0, NS>(X, N, d, graph, R, entry, Q, B, k, ef, ids, scores, L, ns, stream);

@@ -94,22 +94,23 @@ __device__ __forceinline__ int group_sum(int x) {
     return x;
 }
 
-// The same count for lists of up to 512 entries, in at most two LDS round trips.  First the 8
+// The same count for lists of up to 64 NBLK entries (512, or 256 for NBLK = 4), in at most two LDS round trips.  First the 8
 // lanes probe the last entries of the 8 blocks of 64 (skipped for lists of up to 64), which
 // names the block the answer lies in; then every lane reads 8 neighbouring entries of that
 // block with wide loads and counts.  *listed is set when the block holds `vid` itself: the node
 // is in the list already (then it sits exactly at the returned position).  Reads may run up to
 // 63 entries past `len` (never past the end of LDS: the list buffers are not the last region);
 // what they return is masked out.
+template <int NBLK = LANES_PER_ROW>
 __device__ __forceinline__ int group_lower_bound_512(const float *s, const uint32_t *id, int len, float v, int vid,
                                                      int sub, int lane, bool *listed) {
     const int gshift = lane & ~(LANES_PER_ROW - 1);
     int blk = 0;
     if (len > 64) {
-        const int m = 64 * sub + 63;
-        const bool pr = m < len && precedes(s[m], (int)(id[m] & ~EXPANDED), v, vid);
+        const int m = 64 * min(sub, NBLK - 1) + 63;
+        const bool pr = sub < NBLK && m < len && precedes(s[m], (int)(id[m] & ~EXPANDED), v, vid);
         blk = __builtin_popcount((unsigned)(__builtin_amdgcn_ballot_w64(pr) >> gshift) & 0xffu);
-        if (blk == LANES_PER_ROW) { *listed = false; return 512; }
+        if (blk == NBLK) { *listed = false; return 64 * NBLK; }
     }
     const int j0 = 64 * blk + 8 * sub;
     const f4 sa = *reinterpret_cast<const f4 *>(s + j0), sb = *reinterpret_cast<const f4 *>(s + j0 + 4);
@@ -131,19 +132,21 @@ __device__ __forceinline__ int group_lower_bound_512(const float *s, const uint3
 // (set when the kernel starts, never written afterwards) the length does not either: two
 // comparisons and two carries per entry.  Any lane that meets the score v itself sends its
 // whole group to the general routine.
+template <int NBLK = LANES_PER_ROW>
 __device__ __forceinline__ int group_lower_bound_fast(const float *s, const uint32_t *id, int len, float v, int vid,
                                                       int sub, int lane, bool *listed) {
     const int gshift = lane & ~(LANES_PER_ROW - 1);
     int blk = 0;
     bool tie = false;
     if (len > 64) {
-        const int m = 64 * sub + 63;
+        const int m = 64 * min(sub, NBLK - 1) + 63;
         const float es = s[m];
-        tie = m < len && es == v;
-        blk = __builtin_popcount((unsigned)(__builtin_amdgcn_ballot_w64(m < len && es > v) >> gshift) & 0xffu);
+        const bool in = sub < NBLK && m < len;
+        tie = in && es == v;
+        blk = __builtin_popcount((unsigned)(__builtin_amdgcn_ballot_w64(in && es > v) >> gshift) & 0xffu);
     }
     int gt = 0, ge = 0;
-    if (blk < LANES_PER_ROW) {
+    if (blk < NBLK) {
         const int j0 = 64 * blk + 8 * sub;
         const f4 sa = *reinterpret_cast<const f4 *>(s + j0), sb = *reinterpret_cast<const f4 *>(s + j0 + 4);
 #pragma unroll
@@ -154,7 +157,7 @@ __device__ __forceinline__ int group_lower_bound_fast(const float *s, const uint
     }
     tie |= gt != ge;
     if (((unsigned)(__builtin_amdgcn_ballot_w64(tie) >> gshift) & 0xffu) != 0)
-        return group_lower_bound_512(s, id, len, v, vid, sub, lane, listed);
+        return group_lower_bound_512<NBLK>(s, id, len, v, vid, sub, lane, listed);
     *listed = false;
     return 64 * blk + group_sum(gt);
 }
@@ -167,7 +170,9 @@ __device__ __forceinline__ int group_lower_bound_fast(const float *s, const uint
 // queries: two workgroups per compute unit).  Without it the products read the query from LDS and
 // the kernel fits three workgroups per compute unit: more queries in flight, for batches larger
 // than the chip holds at once, where throughput and not the latency of one query counts.
-template <class T, int RPT, bool NS, bool QREG = true>
+// LONG: the two-level candidate list for search ranges beyond GRAPH_EF_TWO_LEVEL (R <= 32, exact visited
+// set, i.e. NS): see "two-level list" below.
+template <class T, int RPT, bool NS, bool QREG = true, bool LONG = false>
 __global__ __launch_bounds__(GRAPH_THREADS, QREG ? 2 : 3) void graph_search_kernel(
     const void *__restrict__ X, int64_t N, int d, const int32_t *__restrict__ graph, int R, int entry,
     const void *__restrict__ Q, int k, int ef, int32_t *__restrict__ ids, float *__restrict__ scores,
@@ -182,7 +187,9 @@ __global__ __launch_bounds__(GRAPH_THREADS, QREG ? 2 : 3) void graph_search_kern
     int *ci = reinterpret_cast<int *>(smem + L.ci);
     int *cpos = reinterpret_cast<int *>(smem + L.cpos);
     int *cache = reinterpret_cast<int *>(smem + L.cache);
-    int *adj = reinterpret_cast<int *>(smem + L.adj);     // [2][RMAX_LDS] adjacency rows read ahead
+    static_assert(!LONG || (NS && RPT == 32 && QREG), "the two-level list needs the exact visited set and R <= 32");
+    constexpr int ADJ = LONG ? 32 : RMAX_LDS;             // row stride of the adjacency rows read ahead
+    int *adj = reinterpret_cast<int *>(smem + L.adj);     // [2][ADJ] adjacency rows read ahead
     int *adj_id = reinterpret_cast<int *>(smem + L.ctl);  // [2] whose rows they are
     uint64_t *um = reinterpret_cast<uint64_t *>(smem + L.um);   // [ef/64] "unexpanded" bit masks
     float *rq = reinterpret_cast<float *>(smem + L.rq);   // RQ of each scored neighbour, NaN = no sample
@@ -203,7 +210,8 @@ __global__ __launch_bounds__(GRAPH_THREADS, QREG ? 2 : 3) void graph_search_kern
         qs[c] = load_chunk(static_cast<const char *>(Q) + ((size_t)b * nch + c) * 16);
     for (int i = tid; i < (1 << L.cache_bits); i += GRAPH_THREADS) cache[i] = -1;
     // list scores start as -inf up to the next multiple of 64 entries (see group_lower_bound_fast)
-    for (int i = tid; i < ((ef + 63) & ~63); i += GRAPH_THREADS) { ls(0)[i] = -INFINITY; ls(1)[i] = -INFINITY; }
+    constexpr int DCAP = GRAPH_DELTA;                     // LONG: entries of the small part of the list
+    for (int i = tid; i < (LONG ? DCAP : ((ef + 63) & ~63)); i += GRAPH_THREADS) { ls(0)[i] = -INFINITY; ls(1)[i] = -INFINITY; }
     __syncthreads();
 
     const int sub = lane & (LANES_PER_ROW - 1);           // lane's position inside its row group
@@ -353,6 +361,10 @@ __global__ __launch_bounds__(GRAPH_THREADS, QREG ? 2 : 3) void graph_search_kern
     int cur = 0;
     float ema = 0.f;                                      // kept by the last wave, copied to the others
     int n_expand = 0, early = 0;
+    // LONG: the large part M of the list (the small part D is the list ls / li / len of the code below)
+    float *Ms = reinterpret_cast<float *>(smem + (LONG ? L.ms : L.ls0));
+    uint32_t *Mi = reinterpret_cast<uint32_t *>(smem + (LONG ? L.mi : L.li0));
+    int mlen = 0;
     if constexpr (PIPELINED) {
     // ---- R <= 32: a software-pipelined loop -------------------------------------------------------
     // As soon as the neighbours of one expansion are scored, the next node to expand is known: the
@@ -365,7 +377,7 @@ __global__ __launch_bounds__(GRAPH_THREADS, QREG ? 2 : 3) void graph_search_kern
     // The second barrier waits for LDS traffic only: __syncthreads() would also wait for the rows.
     auto lds_barrier = [] { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); };
     const int gbase = lane & ~(LANES_PER_ROW - 1);
-    const bool inplace = L.ls1 == L.ls0;
+    const bool inplace = !LONG && L.ls1 == L.ls0;
     int aid0 = -1, aid1 = -1, tog = 0;                    // whose adjacency rows adj[0], adj[1] hold
     int node = entry, p = 0;                              // the node being expanded and its list index
     if (tid == 0) li(0)[0] = (uint32_t)entry | EXPANDED;  // (scans leave entry p out by index as well)
@@ -373,6 +385,10 @@ __global__ __launch_bounds__(GRAPH_THREADS, QREG ? 2 : 3) void graph_search_kern
     int v = -1, fresh = 0;                                // this group's neighbour of `node`; to be scored?
     uint32_t seen = 0;                                    // NS: the word of the exact visited set that holds v
     float *ema_s = reinterpret_cast<float *>(adj_id + 3);
+    // the samples are followed only when they can end the search or the caller wants the counters
+    // (a plain search with a long list runs here with tau = inf and no counters)
+    const bool track = NS && (ns.tau < INFINITY || ns.stats != nullptr || ns.ema != nullptr);
+    if (NS && tid == 0) ema_s[0] = 0.f;
 
     // neighbour `grp` of node nd: duplicates within the row and ids the cache knows are dropped,
     // the row of a remaining one is requested
@@ -389,7 +405,7 @@ __global__ __launch_bounds__(GRAPH_THREADS, QREG ? 2 : 3) void graph_search_kern
             typedef __attribute__((address_space(3))) const int lds_int;
             typedef int int4v __attribute__((ext_vector_type(4)));
             typedef __attribute__((address_space(3))) const int4v lds_int4;
-            lds_int *row = (lds_int *)(adj + have * RMAX_LDS);
+            lds_int *row = (lds_int *)(adj + have * ADJ);
             v = row[vslot];
             const int4v o = *(lds_int4 *)(row + sub * 4);
             o4[0] = o[0]; o4[1] = o[1]; o4[2] = o[2]; o4[3] = o[3];
@@ -421,7 +437,170 @@ __global__ __launch_bounds__(GRAPH_THREADS, QREG ? 2 : 3) void graph_search_kern
     request_row(node);
     request_rest();
 
+    // ---- LONG: the two-level list ------------------------------------------------------------------
+    // A list of thousands of entries is not moved for every insertion.  It is kept as a large part M
+    // (ordered, rewritten only by a rebuild) and a small part D (ordered, at most DCAP entries: the
+    // double-buffered list ls / li / len of the code below); the candidate list of the method is the
+    // merge of the two, cut at ef entries.  New entries go into D; when D is nearly full, it is
+    // merged into M in one pass over M (once in some tens of expansions).
+    //   * the worst entry of the list is the worse of the two tails.  A merge of new entries into D
+    //     that takes the total past ef is followed, before the next expansion looks at the list, by
+    //     dropping that many entries from the two tails, worst first (`pend`, `cut_tails`);
+    //   * the best unexpanded entry is the better of D's (the scan below) and M's first unexpanded
+    //     one, found through one bit per entry of M (um) and held in registers until it is
+    //     expanded itself;
+    //   * the exact visited set scores no node twice, so M is never searched for an id, and a new
+    //     score is only compared with the worst entry and placed in D.
+    // Order of expansions, contents of the list and counters are those of the single list.
+    int pend = 0;                                         // entries still to be dropped from the tails
+    bool stale_worst = true;                              // w_s, w_v are to be read again
+    int m1 = -1, m1_v = -1;                               // M's first unexpanded entry (position, node), -1: none
+    float m1_s = 0.f;
+    float w_s = 0.f;                                      // the worst entry of the list (w_v < 0: the list is empty)
+    int w_v = -1;
+    // m1 <- first position >= from whose bit is set
+    // (Lane and thread numbers go through an empty asm in these routines, so that nothing computed
+    // from them is kept in a register across the whole search loop, where registers are short.)
+    auto opaque = [](int x) { asm volatile("" : "+v"(x)); return x; };
+    auto m_find = [&](int from) {
+        m1 = -1;
+        const int nw = (mlen + 63) >> 6;
+        const int lane_ = opaque(lane);
+        for (int w0 = from >> 6; w0 < nw; w0 += WAVE) {
+            const int w = w0 + lane_;
+            uint64_t word = w < nw ? um[w] : 0ull;
+            if (w == (from >> 6)) word &= ~0ull << (from & 63);
+            if (w == nw - 1 && (mlen & 63) != 0) word &= (1ull << (mlen & 63)) - 1ull;
+            const uint64_t any = __builtin_amdgcn_ballot_w64(word != 0);
+            if (any != 0) {
+                const int l = __builtin_ctzll(any);
+                const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)word, l);
+                const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(word >> 32), l);
+                m1 = (w0 + l) * 64 + __builtin_ctzll(((uint64_t)hi << 32) | lo);
+                break;
+            }
+        }
+        if (m1 >= 0) {
+            m1_s = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(Ms[m1])));
+            m1_v = __builtin_amdgcn_readfirstlane((int)(Mi[m1] & ~EXPANDED));
+        }
+    };
+    // The `pend` worst entries of M and D together leave: lane j asks whether M's j-th entry from the
+    // end is among them, i.e. whether fewer than pend - j entries of D are worse than it.
+    auto cut_tails = [&] {
+        bool c = false;
+        const int lane_ = opaque(lane);
+        if (lane_ < pend) {
+            const int ia = mlen - 1 - lane_, ib = len - pend + lane_;
+            if (ia >= 0)
+                c = ib < 0 || precedes(ls(cur)[ib], (int)(li(cur)[ib] & ~EXPANDED), Ms[ia], (int)(Mi[ia] & ~EXPANDED));
+        }
+        const int tm = __builtin_popcountll(__builtin_amdgcn_ballot_w64(c));
+        mlen -= tm;
+        len -= pend - tm;
+        pend = 0;
+        if (m1 >= mlen) m1 = -1;
+    };
+    auto find_worst = [&] {
+        float a_s = 0.f, d_s = 0.f;
+        int a_v = -1, d_v = -1;
+        if (mlen > 0) { a_s = Ms[mlen - 1]; a_v = (int)(Mi[mlen - 1] & ~EXPANDED); }
+        if (len > 0) { d_s = ls(cur)[len - 1]; d_v = (int)(li(cur)[len - 1] & ~EXPANDED); }
+        const bool take_d = d_v >= 0 && (a_v < 0 || precedes(a_s, a_v, d_s, d_v));
+        w_s = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(take_d ? d_s : a_s)));
+        w_v = __builtin_amdgcn_readfirstlane(take_d ? d_v : a_v);
+    };
+    // M <- merge of M and D, in place; D <- empty.  Thread t places D's entry t: its final position
+    // is (entries of M that precede it) + t.  Those positions are marked in a bit per final position
+    // (the words of um from the lowest marked position's block of 1024 on: um is rewritten there
+    // anyway), with the number of marks before every word beside it; then every final position,
+    // 1024 at a time from the top down, takes D's entry (rank) if marked and M's entry
+    // (position - rank) if not.  Its sources lie at most DCAP below it, so one barrier between the
+    // reads and the writes of a block suffices.  The expanded flags travel with the ids and give
+    // the new bits of um.
+    auto rebuild = [&] {
+        constexpr int BLOCK = 4 * GRAPH_THREADS;
+        const int tid_ = opaque(tid), lane_ = tid_ & (WAVE - 1), wave_ = tid_ >> 6;
+        const int dn = len, total = mlen + dn;            // total <= ef: the tails have been cut
+        int f = -1;
+        if (tid_ < dn) {
+            const float ds = ls(cur)[tid_];
+            const int dv = (int)(li(cur)[tid_] & ~EXPANDED);
+            int lo = 0, hi = mlen;
+            while (lo < hi) {
+                const int mid = (lo + hi) >> 1;
+                if (precedes(Ms[mid], (int)(Mi[mid] & ~EXPANDED), ds, dv)) lo = mid + 1; else hi = mid;
+            }
+            f = lo + tid_;
+        }
+        if (tid_ == 0) adj_id[2] = f;
+        lds_barrier();
+        const int f0 = adj_id[2];                         // lowest position that changes
+        const int lo_b = f0 & ~(BLOCK - 1);
+        const int w_lo = lo_b >> 6, w_hi = (total + 63) >> 6;
+        for (int w = w_lo + tid_; w < w_hi; w += GRAPH_THREADS) um[w] = 0ull;
+        lds_barrier();
+        if (f >= 0) atomicOr(reinterpret_cast<uint32_t *>(um) + (f >> 5), 1u << (f & 31));
+        lds_barrier();
+        int *rk = reinterpret_cast<int *>(ls(cur ^ 1));   // marks before word w_lo + t (D's other buffer is free)
+        int *wt = reinterpret_cast<int *>(li(cur ^ 1));
+        {
+            const int w = w_lo + tid_;                     // w_hi - w_lo <= ef / 64 <= GRAPH_THREADS
+            const int c = w < w_hi ? __builtin_popcountll(um[w]) : 0;
+            int incl = c;
+            for (int o = 1; o < WAVE; o <<= 1) {
+                const int t = __shfl_up(incl, o);
+                if (lane_ >= o) incl += t;
+            }
+            if (lane_ == WAVE - 1) wt[wave_] = incl;
+            lds_barrier();
+            int off = 0;
+            for (int ww = 0; ww < wave_; ++ww) off += wt[ww];
+            rk[tid_] = off + incl - c;
+        }
+        lds_barrier();
+        for (int base = (total - 1) & ~(BLOCK - 1); base >= lo_b; base -= BLOCK) {
+            float vs[4];
+            uint32_t ve[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int g = base + u * GRAPH_THREADS + tid_;
+                vs[u] = 0.f;
+                ve[u] = EXPANDED;
+                if (g < total) {
+                    const uint64_t word = um[g >> 6];
+                    const int bit = g & 63;
+                    const int r = rk[(g >> 6) - w_lo] + __builtin_popcountll(word & ((1ull << bit) - 1ull));
+                    if ((word >> bit) & 1ull) { vs[u] = ls(cur)[r]; ve[u] = li(cur)[r]; }
+                    else { vs[u] = Ms[g - r]; ve[u] = Mi[g - r]; }
+                }
+            }
+            lds_barrier();
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int g = base + u * GRAPH_THREADS + tid_;
+                if (g < total) { Ms[g] = vs[u]; Mi[g] = ve[u]; }
+                const uint64_t un = __builtin_amdgcn_ballot_w64(g < total && !(ve[u] & EXPANDED));
+                const int w = (base + u * GRAPH_THREADS + wave_ * WAVE) >> 6;
+                if (lane_ == 0 && w < w_hi) um[w] = un;
+            }
+        }
+        lds_barrier();                                    // D and its other buffer have been read
+        for (int i = tid_; i < DCAP; i += GRAPH_THREADS) { ls(0)[i] = -INFINITY; ls(1)[i] = -INFINITY; }
+        const int from = min(m1 >= 0 ? m1 : total, f0);   // nothing unexpanded lies below either
+        mlen = total;
+        len = 0;
+        cur = 0;
+        lds_barrier();
+        m_find(from);
+    };
+
     for (;;) {
+        if constexpr (LONG) {
+            if (pend > 0) cut_tails();
+            if (stale_worst) find_worst();                // (the tails change only when entries go in)
+            stale_worst = false;
+        }
         // the runner-up: first unexpanded entry other than p (everything before p is expanded)
         int p2 = -1, node2 = -1;
         float s2 = 0.f;
@@ -455,7 +634,7 @@ __global__ __launch_bounds__(GRAPH_THREADS, QREG ? 2 : 3) void graph_search_kern
             }
             // nothing unexpanded among those 256 (rare): the rest, 256 entries per round, one ballot per
             // wave handed round through LDS
-            if (p2 < 0 && base0 + GRAPH_THREADS < len) {
+            if (!LONG && p2 < 0 && base0 + GRAPH_THREADS < len) {
                 for (int base = base0 + GRAPH_THREADS; base < len; base += GRAPH_THREADS) {
                     const int j = base + tid;
                     const uint64_t m = __builtin_amdgcn_ballot_w64(j < len && !(li(cur)[j] & EXPANDED));
@@ -475,9 +654,18 @@ __global__ __launch_bounds__(GRAPH_THREADS, QREG ? 2 : 3) void graph_search_kern
                 }
             }
         }
+        bool from_m = false;                              // LONG: the runner-up is M's first unexpanded entry
+        if constexpr (LONG) {
+            if (m1 >= 0 && (p2 < 0 || precedes(m1_s, m1_v, s2, node2))) {
+                from_m = true;
+                p2 = -1;
+                node2 = m1_v;
+                s2 = m1_s;
+            }
+        }
         // Read-ahead: the runner-up is the most likely next expansion, so its adjacency row is
         // fetched now, behind the rows already requested; it is stored once those are used.
-        const bool have2 = node2 < 0 || aid0 == node2 || aid1 == node2;
+        const bool have2 = (LONG ? (unsigned)node2 >= (unsigned)N : node2 < 0) || aid0 == node2 || aid1 == node2;
         int ahead = -1;
         if (!have2 && tid < R) ahead = graph[(size_t)node2 * R + tid];
 
@@ -492,7 +680,14 @@ __global__ __launch_bounds__(GRAPH_THREADS, QREG ? 2 : 3) void graph_search_kern
         }
         int pos = -1;
         if (fresh && s == s) {                             // a NaN score is never listed
-            if (len <= 512) {
+            if constexpr (LONG) {
+                // a full list takes what beats its worst entry; the position is the one in D
+                if (mlen + len < ef || precedes(s, v, w_s, w_v)) {
+                    bool listed;
+                    pos = group_lower_bound_fast<DCAP / 64>(ls(cur), li(cur), len, s, v, sub, lane, &listed);
+                    if (listed) pos = -1;
+                }
+            } else if (len <= 512) {
                 bool listed;
                 pos = group_lower_bound_fast(ls(cur), li(cur), len, s, v, sub, lane, &listed);
                 if (pos >= ef || listed) pos = -1;
@@ -508,17 +703,40 @@ __global__ __launch_bounds__(GRAPH_THREADS, QREG ? 2 : 3) void graph_search_kern
         }
         if (!have2) {
             const int into = aid0 == node ? 0 : (aid1 == node ? 1 : (tog ^= 1));
-            if (tid < R) adj[into * RMAX_LDS + tid] = ahead;
+            if (tid < R) adj[into * ADJ + tid] = ahead;
             if (into == 0) aid0 = node2; else aid1 = node2;
         }
         __syncthreads();
+
+        // LONG: D needs room for the entries of one expansion.  The rebuild runs here, where no rows
+        // are in flight (their registers are free); it leaves D empty, so the position in D of every
+        // new entry becomes 0, and the runner-up, the same entry as before, is now M's first
+        // unexpanded one.
+        bool rebuilt = false;
+        if constexpr (LONG) {
+            if (len > DCAP - ROWS_PER_PASS) {
+                rebuild();
+                rebuilt = true;
+                p = -1;
+                p2 = -1;
+                from_m = m1 >= 0;
+            }
+        }
 
         // NS: the relative quality of every newly scored node against the best and worst entries of
         // the list as it stands before they go in, into the moving average in slot order (a slot
         // holds a sample exactly when it scored a node: later slots that name the same id were
         // dropped with the row).  Kept by the last wave, handed to the others through LDS.
-        if (NS && wave == GRAPH_WAVES - 1) {
-            const float s_best = ls(cur)[0], s_worst = ls(cur)[len - 1];
+        if (NS && track && wave == GRAPH_WAVES - 1) {
+            float s_best, s_worst;
+            if constexpr (LONG) {
+                s_best = len > 0 ? ls(cur)[0] : -INFINITY;
+                if (mlen > 0) s_best = fmaxf(s_best, Ms[0]);
+                s_worst = w_s;
+            } else {
+                s_best = ls(cur)[0];
+                s_worst = ls(cur)[len - 1];
+            }
             float r = NAN;                                // NaN: no sample; -inf: one, but best == worst
             if (lane < 32 && ci[lane] >= 0) r = s_best != s_worst ? (s_best - cs[lane]) / (s_best - s_worst) : -INFINITY;
             const uint32_t mag = __float_as_uint(r) & 0x7fffffffu;
@@ -533,8 +751,10 @@ __global__ __launch_bounds__(GRAPH_THREADS, QREG ? 2 : 3) void graph_search_kern
         // what is inserted (lane i < 32 of every wave looks at neighbour i) and which node is next
         const int cl = lane & 31;
         const float c_s = cs[cl];
-        const int c_v = ci[cl], c_p = cpos[cl];
+        const int c_v = ci[cl];
+        int c_p = cpos[cl];
         asm volatile("" ::"v"(c_s), "v"(c_v));            // all three reads now, in one round trip
+        if (LONG && rebuilt) c_p = min(c_p, 0);
         const bool c_ok = lane < 32 && c_p >= 0;
         const uint32_t new_mask = (uint32_t)__builtin_amdgcn_ballot_w64(c_ok);
         const int n_new = __builtin_popcount(new_mask);
@@ -561,7 +781,10 @@ __global__ __launch_bounds__(GRAPH_THREADS, QREG ? 2 : 3) void graph_search_kern
             const float lsc = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(c_s), l));
             if (node2 < 0 || precedes(lsc, lv, s2, node2)) { best_l = l; best_v = lv; }
         }
-        const bool last = best_v < 0;                     // nothing left to expand: natural stop
+        // nothing left to expand: natural stop (LONG: an id that is no node, or more expansions than
+        // there are nodes, neither of which a sound list ever shows, end the search as well instead
+        // of being followed into the graph or spinning)
+        const bool last = LONG ? ((unsigned)best_v >= (unsigned)N || (int64_t)n_expand > N + ROWS_PER_PASS) : best_v < 0;
         if (!NS && last) break;                           // (NS: after the maturity test below)
 
         // New entries at or before list position j.  A few insertions (the rule once the list has
@@ -607,7 +830,8 @@ __global__ __launch_bounds__(GRAPH_THREADS, QREG ? 2 : 3) void graph_search_kern
             int new_at = -1;
             float new_s = 0.f;
             uint32_t new_e = 0;
-            const int gpos = cpos[grp];
+            int gpos = cpos[grp];
+            if (LONG && rebuilt) gpos = min(gpos, 0);
             if (gpos >= 0) {
                 new_s = cs[grp];
                 const int new_v = ci[grp];
@@ -689,9 +913,24 @@ __global__ __launch_bounds__(GRAPH_THREADS, QREG ? 2 : 3) void graph_search_kern
                 lds_barrier();                            // every old entry is out of the way
                 if (new_at >= 0) { ls(cur)[new_at] = new_s; li(cur)[new_at] = new_e; }
             }
-            len = min(ef, len + n_new);
-        } else if (tid == 0 && !last) {
+            if constexpr (LONG) {
+                len += n_new;                             // at most DCAP; what exceeds ef in all leaves next
+                pend = max(0, mlen + len - ef);
+                stale_worst = true;
+            } else {
+                len = min(ef, len + n_new);
+            }
+        } else if (tid == 0 && !last && p2 >= 0) {
             li(cur)[p2] |= EXPANDED;                      // the list stays as it is
+        }
+        if constexpr (LONG) {
+            if (!last && best_l < 0 && from_m) {          // the next node is M's first unexpanded entry
+                if (tid == 0) {
+                    Mi[m1] |= EXPANDED;
+                    um[m1 >> 6] &= ~(1ull << (m1 & 63));
+                }
+                m_find(m1 + 1);                           // (looks only at bits above the one just cleared)
+            }
         }
         if (!last && !held) request_rest();
         lds_barrier();
@@ -710,6 +949,10 @@ __global__ __launch_bounds__(GRAPH_THREADS, QREG ? 2 : 3) void graph_search_kern
         }
         node = best_v;
         p = next_p;
+    }
+    if constexpr (LONG) {                                 // (both exits follow the barrier that ends a merge)
+        if (pend > 0) cut_tails();
+        if (len > 0) rebuild();
     }
     } else {
     // ---- R > 32: the plain loop, 32 graph slots per scoring pass -----------------------------------
@@ -962,9 +1205,15 @@ __global__ __launch_bounds__(GRAPH_THREADS, QREG ? 2 : 3) void graph_search_kern
     }   // plain loop
 
     for (int j = tid; j < k; j += GRAPH_THREADS) {
-        const bool has = j < len;
-        ids[(size_t)b * k + j] = has ? (int)(li(cur)[j] & ~EXPANDED) : -1;
-        scores[(size_t)b * k + j] = has ? ls(cur)[j] : -INFINITY;
+        if constexpr (LONG) {                             // (everything is in M by now)
+            const bool has = j < mlen;
+            ids[(size_t)b * k + j] = has ? (int)(Mi[j] & ~EXPANDED) : -1;
+            scores[(size_t)b * k + j] = has ? Ms[j] : -INFINITY;
+        } else {
+            const bool has = j < len;
+            ids[(size_t)b * k + j] = has ? (int)(li(cur)[j] & ~EXPANDED) : -1;
+            scores[(size_t)b * k + j] = has ? ls(cur)[j] : -INFINITY;
+        }
     }
     if (NS && tid == GRAPH_THREADS - WAVE) {
         if (ns.stats) {

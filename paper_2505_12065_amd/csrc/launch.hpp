@@ -70,6 +70,7 @@ hipError_t launch_flat_merge(int kp, const Cand *partial, int P, int B, int k, i
 
 constexpr int GRAPH_DENSE_MIN_B = 1280;   // batches beyond this run three graph-search workgroups per compute unit
 constexpr int GRAPH_EF_DOUBLE = 2048;    // candidate lists up to this length are double-buffered in LDS
+constexpr int GRAPH_EF_TWO_LEVEL = 512;  // beyond this, graphs of at most 32 slots per node use the two-level list
 // cus workgroups of 8 waves, each wave iters x 8 MFMA 32x32x16 fp16 (32768 flop each) on register operands
 hipError_t launch_mfma_rate(bool random_operands, int cus, int iters, float *sink, hipStream_t stream);
 
@@ -77,7 +78,11 @@ struct GraphLds {
     // byte offsets into dynamic LDS; all 16-byte aligned
     uint32_t q, ls0, ls1, li0, li1, cs, ci, cpos, cache, ctl, adj, um, rq, co, total;
     uint32_t cache_bits, rp;
+    // two-level list (search ranges beyond GRAPH_EF_TWO_LEVEL on graphs of at most 32 slots per node):
+    // ms / mi hold the large part of the list, ls0 .. li1 the small part (GRAPH_DELTA entries each)
+    uint32_t two_level, ms, mi;
 };
+constexpr int GRAPH_DELTA = 256;
 // Maturity exit of the graph search (Section 3.3, Appendix B.2): leave once the moving
 // average of RQ exceeds tau and *ready != 0 (ready == nullptr: always ready).
 struct NonStall {

@@ -50,7 +50,8 @@ def small():
 
 @pytest.mark.parametrize("ef,tau,window", [(32, 0.9, 500), (64, 0.8, 100), (64, 0.6, 30), (128, 0.9, 200),
                                            (16, 0.5, 10), (256, 0.95, 500),
-                                           (64, 6.0, 500), (64, 10.0, 500)])   # these two: early and natural stops mixed
+                                           (64, 6.0, 500), (64, 10.0, 500),    # these two: early and natural stops mixed
+                                           (2500, 0.9, 500), (3000, 1.5, 300)])   # two-level list
 def test_nonstall_matches_oracle(small, ef, tau, window):
     c, q, g = small
     say(f"non-stall: N=20000 R={g.shape[1]} ef={ef} tau={tau} window={window}")

@@ -350,9 +350,11 @@ def test_graph_shapes(R, ef, k):
 
 
 @pytest.mark.parametrize("ef,R,dtype", [(2049, 32, torch.float16), (3000, 12, torch.float16), (6000, 32, torch.bfloat16),
-                                        (16384, 40, torch.float16), (5000, 32, torch.float32)])
+                                        (16384, 40, torch.float16), (5000, 32, torch.float32), (16384, 32, torch.float16),
+                                        (8192, 24, torch.float16)])
 def test_graph_long_lists(ef, R, dtype):
-    """Lists longer than 2048 entries: one LDS buffer merged in place, exact visited bitset."""
+    """Lists longer than 2048 entries, exact visited bitset: the two-level list (R <= 32) and the single
+    buffer merged in place (R > 32); results and counters against the oracle."""
     N = 30_000
     say(f"graph long list: ef={ef} R={R} {dtype}")
     c = synth.make_corpus(N, 64, 12, seed=ef, dtype=dtype, zipf_a=None, sigma=0.35)
@@ -378,7 +380,7 @@ def test_graph_long_lists(ef, R, dtype):
         say(f"  query {b}: walk differs at a near-tie: " + ", ".join(f"nodes {a}/{c2} gap {gap:.2e}" for a, c2, gap in pairs))
 
 
-@pytest.mark.parametrize("ef,R,k", [(16, 8, 5), (200, 32, 10), (700, 32, 16), (48, 40, 7)])
+@pytest.mark.parametrize("ef,R,k", [(16, 8, 5), (200, 32, 10), (700, 32, 16), (48, 40, 7), (2100, 32, 16), (2600, 16, 8)])
 def test_graph_ties_go_to_lower_id(ef, R, k):
     """Every vector occurs four times under scattered ids, so a query scores the copies exactly alike (in fp32
     on the GPU as in fp64 in the oracle) and the order (score descending, id ascending) decides every one of
@@ -547,7 +549,8 @@ def test_graph_per_query_entries(dtype):
 
 @pytest.mark.parametrize("dtype,R,E,ef,k", [(torch.float16, 12, 4, 40, 5), (torch.float16, 32, 32, 64, 3),
                                             (torch.bfloat16, 32, 7, 8, 8), (torch.float32, 40, 5, 300, 10),
-                                            (torch.float16, 20, 32, 3, 3), (torch.float16, 16, 2, 3000, 6)])
+                                            (torch.float16, 20, 32, 3, 3), (torch.float16, 16, 2, 3000, 6),
+                                            (torch.bfloat16, 32, 32, 2500, 16)])
 def test_graph_several_entries_per_query(dtype, R, E, ef, k):
     """entries[B, E]: the whole batch against the oracle started from the same lists, which hold ids that
     are no nodes, repeated ids, and for some queries no usable id at all; through the plain and the
