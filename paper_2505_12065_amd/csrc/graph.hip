@@ -31,12 +31,12 @@ GraphLds graph_lds_layout(int d, int elem_bytes, int R, int ef) {
     };
     // Long lists on graphs of at most 32 slots per node: the two-level list.  The large part has one
     // buffer of ef entries, the small part two of GRAPH_DELTA; the adjacency rows read ahead take 32
-    // slots each; the words of um double as the position marks of a rebuild.
-    auto lay2 = [&](uint32_t bits) {
+    // slots each; the words of um double as the position marks of a rebuild; there is no id cache.
+    auto lay2 = [&] {
         GraphLds L{};
         uint32_t off = 0;
         L.rp = ROWS_PER_PASS;
-        L.cache_bits = bits;
+        L.cache_bits = 0;                                  // no id cache: the visited set is asked first
         L.two_level = 1;
         L.q = off; off = up(off + (uint32_t)d * elem_bytes);
         L.ms = off; off = up(off + 4u * (uint32_t)ef);
@@ -48,7 +48,7 @@ GraphLds graph_lds_layout(int d, int elem_bytes, int R, int ef) {
         L.cs = off; off = up(off + 4u * L.rp);
         L.ci = off; off = up(off + 4u * L.rp);
         L.cpos = off; off = up(off + 4u * L.rp);
-        L.cache = off; off = up(off + (4u << bits));
+        L.cache = off;
         L.ctl = off; off = up(off + 16u);
         L.adj = off; off = up(off + 2u * 4u * 32u);
         L.um = off; off = up(off + 8u * (((uint32_t)ef + 63u) / 64u) + 32u);
@@ -57,11 +57,7 @@ GraphLds graph_lds_layout(int d, int elem_bytes, int R, int ef) {
         return L;
     };
     if (ef > GRAPH_EF_TWO_LEVEL && R <= ROWS_PER_PASS) {
-        uint32_t bits = 14;
-        if (lay2(11).total <= LDS_MAX / 2)
-            while (bits > 11 && lay2(bits).total > LDS_MAX / 2) --bits;
-        while (bits > 10 && lay2(bits).total > LDS_MAX) --bits;
-        const GraphLds L2 = lay2(bits);
+        const GraphLds L2 = lay2();
         if (L2.total <= LDS_MAX) return L2;
     }
     // cache slots: a few times the number of nodes a search scores (about 10 ef), at most 2^14;

@@ -208,7 +208,8 @@ __global__ __launch_bounds__(GRAPH_THREADS, QREG ? 2 : 3) void graph_search_kern
 
     for (int c = tid; c < nch; c += GRAPH_THREADS)
         qs[c] = load_chunk(static_cast<const char *>(Q) + ((size_t)b * nch + c) * 16);
-    for (int i = tid; i < (1 << L.cache_bits); i += GRAPH_THREADS) cache[i] = -1;
+    if constexpr (!LONG)
+        for (int i = tid; i < (1 << L.cache_bits); i += GRAPH_THREADS) cache[i] = -1;
     // list scores start as -inf up to the next multiple of 64 entries (see group_lower_bound_fast)
     constexpr int DCAP = GRAPH_DELTA;                     // LONG: entries of the small part of the list
     for (int i = tid; i < (LONG ? DCAP : ((ef + 63) & ~63)); i += GRAPH_THREADS) { ls(0)[i] = -INFINITY; ls(1)[i] = -INFINITY; }
@@ -337,7 +338,7 @@ __global__ __launch_bounds__(GRAPH_THREADS, QREG ? 2 : 3) void graph_search_kern
         }
         if (wave == 0 && c_valid) {
             if (c_ok && r < ef) { ls(0)[r] = c_s; li(0)[r] = (uint32_t)c_v; }
-            cache[((uint32_t)c_v * 2654435761u) >> cache_shift] = c_v;
+            if constexpr (!LONG) cache[((uint32_t)c_v * 2654435761u) >> cache_shift] = c_v;
             if (NS) atomicOr(&seen_bits[c_v >> 5], 1u << (c_v & 31));
         }
         if (tid < 2) adj_id[tid] = -1;                    // adj[s] may hold the adjacency row of node adj_id[s]
@@ -423,6 +424,21 @@ __global__ __launch_bounds__(GRAPH_THREADS, QREG ? 2 : 3) void graph_search_kern
 #pragma unroll
         for (int t = 0; t < 4; ++t) dup |= (int)(sub * 4 + t < min(slot, R)) & (int)(o4[t] == v);
         if (((unsigned)(__builtin_amdgcn_ballot_w64(dup != 0) >> gbase) & 0xffu) != 0) v = -1;
+        if constexpr (LONG) {
+            // Long lists score tens of thousands of nodes, far more than an id cache in LDS remembers,
+            // and a row fetched for a node that turns out to be scored already is wasted traffic.  Here
+            // only the word of the exact visited set is requested; the rows of the nodes it shows as
+            // new are requested when it has arrived (issue_rows, after the merge and its barrier,
+            // which take about as long as the round trip), and arrive under the list work that
+            // precedes the products.
+            // (When the adjacency row itself had to come from the graph, requesting the rows of all
+            // neighbours together with the word was measured as well: not faster, and it brings back
+            // the wasted rows.)
+            fresh = (int)((unsigned)v < (unsigned)N);
+            if (fresh && sub == 0)
+                seen = __hip_atomic_load(&seen_bits[v >> 5], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            return;
+        }
         bool first_time = false;
         if ((unsigned)v < (unsigned)N && sub == 0)
             first_time = atomicExch(&cache[((uint32_t)v * 2654435761u) >> cache_shift], v) != v;
@@ -436,6 +452,13 @@ __global__ __launch_bounds__(GRAPH_THREADS, QREG ? 2 : 3) void graph_search_kern
     };
     request_row(node);
     request_rest();
+    // LONG: rows of the neighbours the visited set shows as new (the marks of every earlier expansion
+    // were complete before the barrier that preceded the request of the word)
+    auto issue_rows = [&] {
+        const bool unseen = sub == 0 && fresh && !((seen >> (v & 31)) & 1u);
+        fresh = (int)((__builtin_amdgcn_ballot_w64(unseen) >> gbase) & 1u);
+        if (fresh) row_issue(v, x);
+    };
 
     // ---- LONG: the two-level list ------------------------------------------------------------------
     // A list of thousands of entries is not moved for every insertion.  It is kept as a large part M
@@ -597,6 +620,7 @@ __global__ __launch_bounds__(GRAPH_THREADS, QREG ? 2 : 3) void graph_search_kern
 
     for (;;) {
         if constexpr (LONG) {
+            issue_rows();
             if (pend > 0) cut_tails();
             if (stale_worst) find_worst();                // (the tails change only when entries go in)
             stale_worst = false;
@@ -674,8 +698,10 @@ __global__ __launch_bounds__(GRAPH_THREADS, QREG ? 2 : 3) void graph_search_kern
         float s = 0.f;
         if (fresh) s = row_dots(v, x);
         if (NS) {                                         // the cache may have forgotten v: the bitset has not
-            const bool was_seen = sub == 0 && fresh && ((seen >> (v & 31)) & 1u);
-            if ((__builtin_amdgcn_ballot_w64(was_seen) >> gbase) & 1u) fresh = 0;
+            if constexpr (!LONG) {                        // (LONG: only unseen nodes were requested)
+                const bool was_seen = sub == 0 && fresh && ((seen >> (v & 31)) & 1u);
+                if ((__builtin_amdgcn_ballot_w64(was_seen) >> gbase) & 1u) fresh = 0;
+            }
             if (fresh && sub == 0) atomicOr(&seen_bits[v >> 5], 1u << (v & 31));
         }
         int pos = -1;
@@ -706,7 +732,7 @@ __global__ __launch_bounds__(GRAPH_THREADS, QREG ? 2 : 3) void graph_search_kern
             if (tid < R) adj[into * ADJ + tid] = ahead;
             if (into == 0) aid0 = node2; else aid1 = node2;
         }
-        __syncthreads();
+        __syncthreads();                                  // (also waits for the marks set above)
 
         // LONG: D needs room for the entries of one expansion.  The rebuild runs here, where no rows
         // are in flight (their registers are free); it leaves D empty, so the position in D of every
