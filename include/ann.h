@@ -21,10 +21,10 @@
  *     when the library-owned workspace has to grow (first call, or a larger
  *     B*k than any call before on this device).
  *   - One workspace per device: calls that use it (the flat search, the graph
- *     search with ef > 2048, the non-stall graph search) are safe one after the
+ *     search with ef > 512, the non-stall graph search) are safe one after the
  *     other on one stream, or on several streams if the caller orders them; two
  *     of them running at once on one device race on the workspace.  The plain
- *     graph search with ef <= 2048 uses no workspace and may overlap anything.
+ *     graph search with ef <= 512 uses no workspace and may overlap anything.
  *   - corpus  [N, d] row-major, contiguous, 16-byte aligned base.
  *     queries [B, d] row-major, same element type as the corpus.
  *     graph   [N, R] row-major int32; a slot < 0 or >= N is empty and skipped.
@@ -157,11 +157,12 @@ int ann_flat_search_static(const void *corpus, int64_t N, int32_t d, int32_t dty
  *   entry   node id in [0, N), by value, shared by all queries
  *   k, ef   1 <= k <= ef <= ANN_EF_MAX
  *
- * One workgroup serves one query; the candidate list lives in LDS.  Up to ef = 2048
- * the visited filter does too and no workspace is used; longer lists score so many
- * nodes that an exact visited bitset in global memory is used instead (the workspace of
- * ann_graph_search_nonstall_typed, same size and rules).  d, R and ef together must fit
- * the 160 KB of LDS (ef = 16384 fits with d <= 1024 at 16 bits), else ANN_ERR_INVALID.
+ * One workgroup serves one query; the candidate list lives in LDS.  Up to ef = 512
+ * (2048 when R > 32) the visited filter does too and no workspace is used; longer lists
+ * score so many nodes that an exact visited bitset in global memory is used instead (the
+ * workspace of ann_graph_search_nonstall_typed, same size and rules).  d, R and ef together
+ * must fit the 160 KB of LDS (ef = 16384 fits with d <= 1024 at 16 bits), else
+ * ANN_ERR_INVALID.
  */
 int ann_graph_search_typed(const void *corpus, int64_t N, int32_t d, int32_t dtype,
                            const int32_t *graph, int32_t R, int32_t entry,

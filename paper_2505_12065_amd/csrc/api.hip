@@ -670,9 +670,9 @@ int ann_graph_search_nonstall_typed(const void *corpus, int64_t N, int32_t d, in
                                                      scores, L, ns, s));
 }
 
-// Plain search.  Lists longer than GRAPH_EF_DOUBLE score far more nodes than the LDS id cache
-// remembers, so they run on the kernel variant with the exact visited bitset, with an exit
-// threshold no average can exceed.
+// Plain search.  Long lists (the two-level list, or more than GRAPH_EF_DOUBLE entries) score far
+// more nodes than an id cache in LDS remembers, so they run on the kernel variant with the exact
+// visited bitset, with an exit threshold no average can exceed.
 static int graph_search_any(const void *corpus, int64_t N, int32_t d, int32_t dtype, const int32_t *graph, int32_t R,
                             int32_t entry, const int32_t *entries, int32_t n_entries, const void *queries, int32_t B, int32_t k,
                             int32_t ef, int32_t *ids, float *scores, const GraphLds &L, hipStream_t s) {
