@@ -468,7 +468,7 @@ __global__ __launch_bounds__(GRAPH_THREADS, QREG ? 2 : 3) void graph_search_kern
     // merged into M in one pass over M (once in some tens of expansions).
     //   * the worst entry of the list is the worse of the two tails.  A merge of new entries into D
     //     that takes the total past ef is followed, before the next expansion looks at the list, by
-    //     dropping that many entries from the two tails, worst first (`pend`, `cut_tails`);
+    //     dropping that many entries from the two tails, worst first (`pend`, `trim_tails`);
     //   * the best unexpanded entry is the better of D's (the scan below) and M's first unexpanded
     //     one, found through one bit per entry of M (um) and held in registers until it is
     //     expanded itself;
@@ -508,30 +508,36 @@ __global__ __launch_bounds__(GRAPH_THREADS, QREG ? 2 : 3) void graph_search_kern
             m1_v = __builtin_amdgcn_readfirstlane((int)(Mi[m1] & ~EXPANDED));
         }
     };
-    // The `pend` worst entries of M and D together leave: lane j asks whether M's j-th entry from the
-    // end is among them, i.e. whether fewer than pend - j entries of D are worse than it.
-    auto cut_tails = [&] {
-        bool c = false;
+    // After a merge into D: the `pend` worst entries of M and D together leave, and the worst entry
+    // that remains is read again, in one round trip.  Lane j reads M's and D's j-th entries from the
+    // end; lane j < pend asks whether M's is among the pend worst, i.e. whether fewer than pend - j
+    // entries of D are worse than it (it reads that entry of D as well); the count of such lanes is
+    // what M loses, D loses the rest, and the new worst is the worse of the first entries that stay.
+    auto trim_tails = [&] {
         const int lane_ = opaque(lane);
-        if (lane_ < pend) {
-            const int ia = mlen - 1 - lane_, ib = len - pend + lane_;
-            if (ia >= 0)
-                c = ib < 0 || precedes(ls(cur)[ib], (int)(li(cur)[ib] & ~EXPANDED), Ms[ia], (int)(Mi[ia] & ~EXPANDED));
-        }
-        const int tm = __builtin_popcountll(__builtin_amdgcn_ballot_w64(c));
+        const float *dsc = ls(cur);
+        const uint32_t *did = li(cur);
+        const int ia = mlen - 1 - lane_, it = len - 1 - lane_, ix = len - pend + lane_;
+        const float a_s = Ms[max(ia, 0)];
+        const int a_v = (int)(Mi[max(ia, 0)] & ~EXPANDED);
+        const float t_s = dsc[max(it, 0)];
+        const int t_v = (int)(did[max(it, 0)] & ~EXPANDED);
+        const int ixc = min(max(ix, 0), DCAP - 1);
+        const float x_s = dsc[ixc];
+        const int x_v = (int)(did[ixc] & ~EXPANDED);
+        const bool c = lane_ < pend && ia >= 0 && (ix < 0 || precedes(x_s, x_v, a_s, a_v));
+        const int tm = __builtin_popcountll(__builtin_amdgcn_ballot_w64(c)), td = pend - tm;
         mlen -= tm;
-        len -= pend - tm;
+        len -= td;
         pend = 0;
         if (m1 >= mlen) m1 = -1;
-    };
-    auto find_worst = [&] {
-        float a_s = 0.f, d_s = 0.f;
-        int a_v = -1, d_v = -1;
-        if (mlen > 0) { a_s = Ms[mlen - 1]; a_v = (int)(Mi[mlen - 1] & ~EXPANDED); }
-        if (len > 0) { d_s = ls(cur)[len - 1]; d_v = (int)(li(cur)[len - 1] & ~EXPANDED); }
-        const bool take_d = d_v >= 0 && (a_v < 0 || precedes(a_s, a_v, d_s, d_v));
-        w_s = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(take_d ? d_s : a_s)));
-        w_v = __builtin_amdgcn_readfirstlane(take_d ? d_v : a_v);
+        const float wa_s = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(a_s), tm));
+        const int wa_v = __builtin_amdgcn_readlane(a_v, tm);
+        const float wt_s = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(t_s), td));
+        const int wt_v = __builtin_amdgcn_readlane(t_v, td);
+        const bool take_d = len > 0 && (mlen <= 0 || precedes(wa_s, wa_v, wt_s, wt_v));
+        w_s = take_d ? wt_s : wa_s;
+        w_v = take_d ? wt_v : (mlen > 0 ? wa_v : -1);
     };
     // M <- merge of M and D, in place; D <- empty.  Thread t places D's entry t: its final position
     // is (entries of M that precede it) + t.  Those positions are marked in a bit per final position
@@ -621,14 +627,35 @@ __global__ __launch_bounds__(GRAPH_THREADS, QREG ? 2 : 3) void graph_search_kern
     for (;;) {
         if constexpr (LONG) {
             issue_rows();
-            if (pend > 0) cut_tails();
-            if (stale_worst) find_worst();                // (the tails change only when entries go in)
+            if (stale_worst) trim_tails();                // (the tails change only when entries go in)
             stale_worst = false;
         }
         // the runner-up: first unexpanded entry other than p (everything before p is expanded)
         int p2 = -1, node2 = -1;
         float s2 = 0.f;
-        {
+        if constexpr (LONG) {
+            // D has at most 256 entries (and its buffers hold 256): every wave reads all four blocks of
+            // 64 without conditions, takes one ballot per block, picks the first block with a
+            // candidate by scalar selects and reads the pair out of one lane.
+            const float *dsc = ls(cur);
+            const uint32_t *did = li(cur);
+            const uint32_t e0 = did[lane], e1 = did[lane + 64], e2 = did[lane + 128], e3 = did[lane + 192];
+            const float f0 = dsc[lane], f1 = dsc[lane + 64], f2 = dsc[lane + 128], f3 = dsc[lane + 192];
+            const uint64_t m0 = __builtin_amdgcn_ballot_w64(lane < len && lane != p && !(e0 & EXPANDED));
+            const uint64_t m1 = __builtin_amdgcn_ballot_w64(lane + 64 < len && lane + 64 != p && !(e1 & EXPANDED));
+            const uint64_t m2 = __builtin_amdgcn_ballot_w64(lane + 128 < len && lane + 128 != p && !(e2 & EXPANDED));
+            const uint64_t m3 = __builtin_amdgcn_ballot_w64(lane + 192 < len && lane + 192 != p && !(e3 & EXPANDED));
+            const int blk = m0 ? 0 : (m1 ? 1 : (m2 ? 2 : 3));
+            const uint64_t mb = m0 ? m0 : (m1 ? m1 : (m2 ? m2 : m3));
+            if (mb != 0) {
+                const int l = __builtin_ctzll(mb);
+                const uint32_t eb = blk == 0 ? e0 : (blk == 1 ? e1 : (blk == 2 ? e2 : e3));
+                const float fb = blk == 0 ? f0 : (blk == 1 ? f1 : (blk == 2 ? f2 : f3));
+                p2 = blk * 64 + l;
+                node2 = __builtin_amdgcn_readlane((int)eb, l);
+                s2 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(fb), l));
+            }
+        } else {
             // Every wave looks itself at the 256 entries from the block of 64 that holds p + 1 on:
             // ids and scores in one round trip, the runner-up's own pair then comes out of a lane.
             // No exchange between the waves and no barrier, whatever the length of the list.
@@ -977,7 +1004,7 @@ __global__ __launch_bounds__(GRAPH_THREADS, QREG ? 2 : 3) void graph_search_kern
         p = next_p;
     }
     if constexpr (LONG) {                                 // (both exits follow the barrier that ends a merge)
-        if (pend > 0) cut_tails();
+        if (pend > 0) trim_tails();
         if (len > 0) rebuild();
     }
     } else {
