@@ -34,26 +34,18 @@ GraphLds graph_lds_layout(int d, int elem_bytes, int R, int ef) {
     // slots each; the words of um double as the position marks of a rebuild; there is no id cache.
     auto lay2 = [&] {
         GraphLds L{};
-        uint32_t off = 0;
         L.rp = ROWS_PER_PASS;
         L.cache_bits = 0;                                  // no id cache: the visited set is asked first
         L.two_level = 1;
-        L.q = off; off = up(off + (uint32_t)d * elem_bytes);
-        L.ms = off; off = up(off + 4u * (uint32_t)ef);
-        L.mi = off; off = up(off + 4u * (uint32_t)ef);
-        L.ls0 = off; off = up(off + 4u * GRAPH_DELTA);
-        L.li0 = off; off = up(off + 4u * GRAPH_DELTA);
-        L.ls1 = off; off = up(off + 4u * GRAPH_DELTA);
-        L.li1 = off; off = up(off + 4u * GRAPH_DELTA);
-        L.cs = off; off = up(off + 4u * L.rp);
-        L.ci = off; off = up(off + 4u * L.rp);
-        L.cpos = off; off = up(off + 4u * L.rp);
-        L.cache = off;
-        L.ctl = off; off = up(off + 16u);
-        L.adj = off; off = up(off + 2u * 4u * 32u);
-        L.um = off; off = up(off + 8u * (((uint32_t)ef + 63u) / 64u) + 32u);
-        L.rq = L.co = L.um;                                // (used by the plain loop only)
-        L.total = off;
+        L.ls0 = TL_LS0; L.li0 = TL_LI0; L.ls1 = TL_LS1; L.li1 = TL_LI1;
+        L.cs = TL_CS; L.ci = TL_CI; L.cpos = TL_CPOS;
+        L.ctl = L.cache = TL_CTL;
+        L.adj = TL_ADJ;
+        L.um = L.rq = L.co = TL_UM;                        // (rq, co: used by the plain loop only)
+        L.ms = TL_MS;
+        L.mi = up(L.ms + 4u * (uint32_t)ef);
+        L.q = up(L.mi + 4u * (uint32_t)ef);
+        L.total = up(L.q + (uint32_t)d * elem_bytes);
         return L;
     };
     if (ef > GRAPH_EF_TWO_LEVEL && R <= ROWS_PER_PASS) {

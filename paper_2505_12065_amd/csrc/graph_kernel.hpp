@@ -181,17 +181,22 @@ __global__ __launch_bounds__(GRAPH_THREADS, QREG ? 2 : 3) void graph_search_kern
     u4 *qs = reinterpret_cast<u4 *>(smem + L.q);
     // the two list buffers, selected by offset arithmetic on the LDS base (an array of pointers
     // indexed at run time would turn every list access into a generic-address load)
-    auto ls = [&](int which) { return reinterpret_cast<float *>(smem + (which ? L.ls1 : L.ls0)); };
-    auto li = [&](int which) { return reinterpret_cast<uint32_t *>(smem + (which ? L.li1 : L.li0)); };
-    float *cs = reinterpret_cast<float *>(smem + L.cs);
-    int *ci = reinterpret_cast<int *>(smem + L.ci);
-    int *cpos = reinterpret_cast<int *>(smem + L.cpos);
+    // (LONG: the small regions sit at fixed offsets, see TL_LS0 ..)
+    auto ls = [&](int which) {
+        return reinterpret_cast<float *>(smem + (LONG ? (which ? TL_LS1 : TL_LS0) : (which ? L.ls1 : L.ls0)));
+    };
+    auto li = [&](int which) {
+        return reinterpret_cast<uint32_t *>(smem + (LONG ? (which ? TL_LI1 : TL_LI0) : (which ? L.li1 : L.li0)));
+    };
+    float *cs = reinterpret_cast<float *>(smem + (LONG ? TL_CS : L.cs));
+    int *ci = reinterpret_cast<int *>(smem + (LONG ? TL_CI : L.ci));
+    int *cpos = reinterpret_cast<int *>(smem + (LONG ? TL_CPOS : L.cpos));
     int *cache = reinterpret_cast<int *>(smem + L.cache);
     static_assert(!LONG || (NS && RPT == 32 && QREG), "the two-level list needs the exact visited set and R <= 32");
     constexpr int ADJ = LONG ? 32 : RMAX_LDS;             // row stride of the adjacency rows read ahead
-    int *adj = reinterpret_cast<int *>(smem + L.adj);     // [2][ADJ] adjacency rows read ahead
-    int *adj_id = reinterpret_cast<int *>(smem + L.ctl);  // [2] whose rows they are
-    uint64_t *um = reinterpret_cast<uint64_t *>(smem + L.um);   // [ef/64] "unexpanded" bit masks
+    int *adj = reinterpret_cast<int *>(smem + (LONG ? TL_ADJ : L.adj));     // [2][ADJ] adjacency rows read ahead
+    int *adj_id = reinterpret_cast<int *>(smem + (LONG ? TL_CTL : L.ctl));  // [2] whose rows they are
+    uint64_t *um = reinterpret_cast<uint64_t *>(smem + (LONG ? TL_UM : L.um));   // [ef/64] "unexpanded" bit masks
     float *rq = reinterpret_cast<float *>(smem + L.rq);   // RQ of each scored neighbour, NaN = no sample
     int *co = reinterpret_cast<int *>(smem + L.co);       // the valid ids of the adjacency row as read
 
@@ -363,7 +368,7 @@ __global__ __launch_bounds__(GRAPH_THREADS, QREG ? 2 : 3) void graph_search_kern
     float ema = 0.f;                                      // kept by the last wave, copied to the others
     int n_expand = 0, early = 0;
     // LONG: the large part M of the list (the small part D is the list ls / li / len of the code below)
-    float *Ms = reinterpret_cast<float *>(smem + (LONG ? L.ms : L.ls0));
+    float *Ms = reinterpret_cast<float *>(smem + (LONG ? TL_MS : L.ls0));
     uint32_t *Mi = reinterpret_cast<uint32_t *>(smem + (LONG ? L.mi : L.li0));
     int mlen = 0;
     if constexpr (PIPELINED) {
@@ -974,13 +979,13 @@ __global__ __launch_bounds__(GRAPH_THREADS, QREG ? 2 : 3) void graph_search_kern
                 len = min(ef, len + n_new);
             }
         } else if (tid == 0 && !last && p2 >= 0) {
-            li(cur)[p2] |= EXPANDED;                      // the list stays as it is
+            atomicOr(&li(cur)[p2], EXPANDED);             // the list stays as it is (no return value to wait for)
         }
         if constexpr (LONG) {
             if (!last && best_l < 0 && from_m) {          // the next node is M's first unexpanded entry
-                if (tid == 0) {
-                    Mi[m1] |= EXPANDED;
-                    um[m1 >> 6] &= ~(1ull << (m1 & 63));
+                if (tid == 0) {                             // (LDS atomics without return: nothing to wait for)
+                    atomicOr(&Mi[m1], EXPANDED);
+                    atomicAnd(reinterpret_cast<unsigned long long *>(&um[m1 >> 6]), ~(1ull << (m1 & 63)));
                 }
                 m_find(m1 + 1);                           // (looks only at bits above the one just cleared)
             }

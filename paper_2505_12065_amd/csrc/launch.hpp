@@ -83,6 +83,13 @@ struct GraphLds {
     uint32_t two_level, ms, mi;
 };
 constexpr int GRAPH_DELTA = 256;
+// The two-level layout keeps its small regions at fixed byte offsets at the start of LDS (the kernel
+// then addresses them with immediates and needs no register per region); the large part of the
+// list and the query, whose sizes depend on ef and d, follow.
+constexpr uint32_t TL_LS0 = 0, TL_LI0 = 4 * GRAPH_DELTA, TL_LS1 = 8 * GRAPH_DELTA, TL_LI1 = 12 * GRAPH_DELTA;
+constexpr uint32_t TL_CS = 16 * GRAPH_DELTA, TL_CI = TL_CS + 128, TL_CPOS = TL_CI + 128, TL_CTL = TL_CPOS + 128;
+constexpr uint32_t TL_ADJ = TL_CTL + 32, TL_UM = TL_ADJ + 256;
+constexpr uint32_t TL_MS = TL_UM + 8 * (16384 / 64) + 32;   // um: a bit per entry of the longest list, and 4 words
 // Maturity exit of the graph search (Section 3.3, Appendix B.2): leave once the moving
 // average of RQ exceeds tau and *ready != 0 (ready == nullptr: always ready).
 struct NonStall {
