@@ -493,6 +493,22 @@ __global__ __launch_bounds__(GRAPH_THREADS, QREG ? 2 : 3) void graph_search_kern
     auto m_find = [&](int from) {
         m1 = -1;
         const int nw = (mlen + 63) >> 6;
+        // (as a rule the next one is a few entries further on, in the word that holds `from`:
+        // that word alone is read first, by all lanes at once)
+        if ((from >> 6) < nw) {
+            uint64_t word = um[from >> 6] & (~0ull << (from & 63));
+            if ((from >> 6) == nw - 1 && (mlen & 63) != 0) word &= (1ull << (mlen & 63)) - 1ull;
+            const uint32_t lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)word);
+            const uint32_t hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(word >> 32));
+            const uint64_t wu = ((uint64_t)hi << 32) | lo;
+            if (wu != 0) m1 = (from & ~63) + __builtin_ctzll(wu);
+            else from = (from | 63) + 1;
+        }
+        if (m1 >= 0) {
+            m1_s = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(Ms[m1])));
+            m1_v = __builtin_amdgcn_readfirstlane((int)(Mi[m1] & ~EXPANDED));
+            return;
+        }
         const int lane_ = opaque(lane);
         for (int w0 = from >> 6; w0 < nw; w0 += WAVE) {
             const int w = w0 + lane_;
