@@ -387,6 +387,17 @@ def main() -> int:
             qx = q_all.repeat((Bx + B_LARGE - 1) // B_LARGE, 1)[:Bx].contiguous()
             ms = timed(lambda: ann.ann_graph_search_typed(x, graph, entry, qx, K, 64), n=5, w=1)
             sweep["graph_batch"].append({"ef": 64, "B": Bx, "ms": ms, "qps": Bx / ms * 1e3})
+        # the operating point with more queries than one resident round (2 workgroups per compute unit):
+        # a workgroup slot takes the next query when its own ends, so the batch no longer waits for its
+        # slowest query with every other slot idle (queries: copies of the configuration's 512)
+        sweep["graph_navigable_batch"] = []
+        for Bx in (1024, 2048):
+            qx = q_all.repeat(Bx // B_LARGE, 1).contiguous()
+            def nav_search_batch():
+                cid_x, _ = ann.ann_flat_search_typed(rep_rows, qx, 1)
+                return ann.ann_graph_search_entries_typed(x, graph_nav, ann.ann_gather_ids(reps, cid_x.view(-1)), qx, K, ef_op)
+            ms = timed(nav_search_batch, n=1, w=1)
+            sweep["graph_navigable_batch"].append({"ef": ef_op, "B": Bx, "ms": ms, "qps": Bx / ms * 1e3})
         # the rest of the navigable-graph table beyond the operating point, and a variant with little
         # query noise (std 0.05 / sqrt(d): NOT the configuration's queries)
         have = {r["ef"] for r in nav_table}
