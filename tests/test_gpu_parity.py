@@ -409,17 +409,23 @@ def test_graph_ties_go_to_lower_id(ef, R, k):
     assert np.array_equal(st[:, 1], nd) and np.array_equal(st[:, 2], ne)
 
 
-def test_graph_random_configurations():
-    """Thirty seeded draws of (N, d, R, ef, k, dtype, B) with junk ids, repeated ids and repeated vectors in
+@pytest.mark.parametrize("seed,cases,n_max,r_choices,ef_choices", [
+    (2024, 30, 4000, [1, 2, 5, 8, 16, 31, 32, 33, 48], [1, 3, 17, 64, 65, 200, 256, 257, 400, 512, 513, 900]),
+    # the two-level list (search ranges beyond 512, at most 32 slots per node): lists that never fill, lists
+    # that hold most of the graph, rebuilds every few expansions (R = 32) and every few hundred (R = 1, 2)
+    (77, 16, 7000, [1, 2, 5, 16, 32], [513, 600, 770, 1500, 2049, 2500, 5000]),
+])
+def test_graph_random_configurations(seed, cases, n_max, r_choices, ef_choices):
+    """Seeded draws of (N, d, R, ef, k, dtype, B) with junk ids, repeated ids and repeated vectors in
     the inputs: every list length regime (up to 64, up to 256, up to 512, beyond), both loops (R <= 32 and
     R > 32) and both entry points against the oracle, counters of the maturity variant included."""
-    rng = np.random.default_rng(2024)
+    rng = np.random.default_rng(seed)
     total = strict_total = 0
-    for case in range(30):
-        N = int(rng.integers(40, 4000))
+    for case in range(cases):
+        N = int(rng.integers(40, n_max))
         d = int(rng.choice([8, 16, 24, 64, 72, 136, 256, 520]))
-        R = int(rng.choice([1, 2, 5, 8, 16, 31, 32, 33, 48]))
-        ef = int(rng.choice([1, 3, 17, 64, 65, 200, 256, 257, 400, 512, 513, 900]))
+        R = int(rng.choice(r_choices))
+        ef = int(rng.choice(ef_choices))
         k = int(rng.integers(1, min(ef, 20) + 1))
         B = int(rng.integers(1, 12))
         dtype = [torch.float16, torch.bfloat16, torch.float32][int(rng.integers(0, 3))]
