@@ -48,10 +48,9 @@ GraphLds graph_lds_layout(int d, int elem_bytes, int R, int ef) {
         L.total = up(L.q + (uint32_t)d * elem_bytes);
         return L;
     };
-    if (ef > GRAPH_EF_TWO_LEVEL && R <= ROWS_PER_PASS) {
-        const GraphLds L2 = lay2();
-        if (L2.total <= LDS_MAX) return L2;
-    }
+    // (it is the only layout of such lists on such graphs: the software-pipelined loop has no code for
+    // a single list of more than 512 entries; with d <= ANN_D_MAX it always fits)
+    if (ef > GRAPH_EF_TWO_LEVEL && R <= ROWS_PER_PASS) return lay2();
     // cache slots: a few times the number of nodes a search scores (about 10 ef), at most 2^14;
     // fewer when that lets two workgroups share a compute unit, or when the list needs the room
     uint32_t want = 10;

@@ -383,7 +383,6 @@ __global__ __launch_bounds__(GRAPH_THREADS, QREG ? 2 : 3) void graph_search_kern
     // The second barrier waits for LDS traffic only: __syncthreads() would also wait for the rows.
     auto lds_barrier = [] { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); };
     const int gbase = lane & ~(LANES_PER_ROW - 1);
-    const bool inplace = !LONG && L.ls1 == L.ls0;
     int aid0 = -1, aid1 = -1, tog = 0;                    // whose adjacency rows adj[0], adj[1] hold
     int node = entry, p = 0;                              // the node being expanded and its list index
     if (tid == 0) li(0)[0] = (uint32_t)entry | EXPANDED;  // (scans leave entry p out by index as well)
@@ -867,10 +866,6 @@ __global__ __launch_bounds__(GRAPH_THREADS, QREG ? 2 : 3) void graph_search_kern
         // in registers across the merge, next to the rows in flight, would not fit the register file.)
         constexpr int FEW = 6;
         const bool few = n_new <= FEW;
-        unsigned jmin = 0xffffffffu;                      // lowest insertion position (long lists only)
-        if (inplace)
-            for (uint32_t m = new_mask; m != 0; m &= m - 1)
-                jmin = min(jmin, (unsigned)__builtin_amdgcn_readlane(c_p, __builtin_ctz(m)));
         auto shift_of = [&](int j) {
             int shift = 0;
             if (few) {
@@ -921,7 +916,7 @@ __global__ __launch_bounds__(GRAPH_THREADS, QREG ? 2 : 3) void graph_search_kern
                 new_e = (uint32_t)new_v | (grp == best_l ? EXPANDED : 0u);
             }
             const int old_next = best_l < 0 ? p2 : -1;   // an old entry that becomes the next node
-            if (!inplace) {
+            {   // (this loop serves lists of at most 512 entries, and D: always double-buffered)
                 const int nxt = cur ^ 1;
                 if (new_at >= 0) { ls(nxt)[new_at] = new_s; li(nxt)[new_at] = new_e; }
                 for (int j = tid; j < len; j += GRAPH_THREADS) {
@@ -929,63 +924,6 @@ __global__ __launch_bounds__(GRAPH_THREADS, QREG ? 2 : 3) void graph_search_kern
                     if (to < ef) { ls(nxt)[to] = ls(cur)[j]; li(nxt)[to] = li(cur)[j] | (j == old_next ? EXPANDED : 0u); }
                 }
                 cur = nxt;
-            } else {
-                if (tid == 0 && old_next >= 0 && (unsigned)old_next < jmin) li(cur)[old_next] |= EXPANDED;
-                // Entries below jmin stay, the others move up by at most 32 places.  The stretch that moves
-                // is cut into chunks of 256 entries, numbered from the top, and every wave takes a run of
-                // neighbouring chunks, which it moves from the top down on its own: inside a wave a chunk's
-                // targets lie in itself and in the chunk above, which that wave has already read, and LDS
-                // operations of one wave execute in order, so no barrier is needed.  Only the top chunk of
-                // a wave reaches into the lowest 32 entries of the wave above: every wave therefore saves
-                // those 32 entries of its own lowest chunk in registers first (one barrier), and takes them
-                // from there when it gets to that chunk.  Lane l owns entries l, l + 64, l + 128, l + 192 of
-                // a chunk, so that every read and every write of a wave covers 64 neighbouring entries
-                // (no bank conflicts); the next chunk's reads go out before this chunk's writes.
-                constexpr int CH = 4 * WAVE;
-                const int top = (len - 1) & ~(CH - 1);                       // base of chunk 0
-                const int n_chunks = (top - ((int)jmin & ~(CH - 1))) / CH + 1;
-                const int per_wave = (n_chunks + GRAPH_WAVES - 1) / GRAPH_WAVES;
-                const int c_first = wave * per_wave, c_last = min(n_chunks, c_first + per_wave) - 1;
-                float ms[4], nx_s[4], sv_s = 0.f;
-                uint32_t mi[4], nx_i[4], sv_i = 0u;
-                auto read4 = [&](int c, float (&s4)[4], uint32_t (&i4)[4]) {
-#pragma unroll
-                    for (int u = 0; u < 4; ++u) {
-                        const int j = min(top - c * CH + u * WAVE + lane, len - 1);
-                        s4[u] = ls(cur)[j];
-                        i4[u] = li(cur)[j];
-                    }
-                };
-                if (c_first <= c_last) {
-                    const int j = min(top - c_last * CH + lane, len - 1);
-                    sv_s = ls(cur)[j];
-                    sv_i = li(cur)[j];
-                    read4(c_first, ms, mi);
-                }
-                lds_barrier();                            // (LDS only: the rows of the next node stay in flight)
-                for (int c = c_first; c <= c_last; ++c) {
-                    if (c < c_last) read4(c + 1, nx_s, nx_i);
-                    if (c == c_last && lane < 32) { ms[0] = sv_s; mi[0] = sv_i; }
-                    const int j0 = top - c * CH + lane;
-                    int sh[4] = {0, 0, 0, 0};
-                    for (uint32_t m = new_mask; m != 0; m &= m - 1) {
-                        const unsigned g = (unsigned)__builtin_amdgcn_readlane(c_p, __builtin_ctz(m));
-#pragma unroll
-                        for (int u = 0; u < 4; ++u) sh[u] += (int)(g <= (unsigned)(j0 + u * WAVE));
-                    }
-#pragma unroll
-                    for (int u = 0; u < 4; ++u) {
-                        const int j = j0 + u * WAVE, to = j + sh[u];
-                        if (j < len && j >= (int)jmin && to < ef) {
-                            ls(cur)[to] = ms[u];
-                            li(cur)[to] = mi[u] | (j == old_next ? EXPANDED : 0u);
-                        }
-                    }
-#pragma unroll
-                    for (int u = 0; u < 4; ++u) { ms[u] = nx_s[u]; mi[u] = nx_i[u]; }
-                }
-                lds_barrier();                            // every old entry is out of the way
-                if (new_at >= 0) { ls(cur)[new_at] = new_s; li(cur)[new_at] = new_e; }
             }
             if constexpr (LONG) {
                 len += n_new;                             // at most DCAP; what exceeds ef in all leaves next
