@@ -12,11 +12,14 @@ GraphLds graph_lds_layout(int d, int elem_bytes, int R, int ef) {
         L.rp = (uint32_t)((R + ROWS_PER_PASS - 1) / ROWS_PER_PASS * ROWS_PER_PASS);
         L.cache_bits = bits;
         L.q = off; off = up(off + (uint32_t)d * elem_bytes);
-        const uint32_t ef64 = ((uint32_t)ef + 63u) & ~63u;   // score lists are padded to 64 entries
+        // score lists are padded to 64 entries; lists of up to 256 entries get buffers of 256, which
+        // the scan for the next unexpanded entry then reads without conditions
+        const uint32_t ef64 = ef <= GRAPH_DELTA ? (uint32_t)GRAPH_DELTA : ((uint32_t)ef + 63u) & ~63u;
+        const uint32_t efi = ef <= GRAPH_DELTA ? (uint32_t)GRAPH_DELTA : (uint32_t)ef;
         L.ls0 = off; off = up(off + 4u * ef64);
         if (inplace) L.ls1 = L.ls0; else { L.ls1 = off; off = up(off + 4u * ef64); }
-        L.li0 = off; off = up(off + 4u * ef);
-        if (inplace) L.li1 = L.li0; else { L.li1 = off; off = up(off + 4u * ef); }
+        L.li0 = off; off = up(off + 4u * efi);
+        if (inplace) L.li1 = L.li0; else { L.li1 = off; off = up(off + 4u * efi); }
         L.cs = off; off = up(off + 4u * L.rp);
         L.ci = off; off = up(off + 4u * L.rp);
         L.cpos = off; off = up(off + 4u * L.rp);

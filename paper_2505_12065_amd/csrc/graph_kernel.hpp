@@ -653,10 +653,10 @@ __global__ __launch_bounds__(GRAPH_THREADS, QREG ? 2 : 3) void graph_search_kern
         // the runner-up: first unexpanded entry other than p (everything before p is expanded)
         int p2 = -1, node2 = -1;
         float s2 = 0.f;
-        if constexpr (LONG) {
-            // D has at most 256 entries (and its buffers hold 256): every wave reads all four blocks of
-            // 64 without conditions, takes one ballot per block, picks the first block with a
-            // candidate by scalar selects and reads the pair out of one lane.
+        if (LONG || ef <= DCAP) {
+            // A list of at most 256 entries (D always is one) in buffers that hold 256: every wave reads
+            // all four blocks of 64 without conditions, takes one ballot per block, picks the first
+            // block with a candidate by scalar selects and reads the pair out of one lane.
             const float *dsc = ls(cur);
             const uint32_t *did = li(cur);
             const uint32_t e0 = did[lane], e1 = did[lane + 64], e2 = did[lane + 128], e3 = did[lane + 192];
