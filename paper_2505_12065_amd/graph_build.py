@@ -44,18 +44,26 @@ def knn_rows_by_cluster(x: torch.Tensor, labels: torch.Tensor, centroids: torch.
         near[r0:r0 + (1 << 17)] = torch.topk(x[r0:r0 + (1 << 17)].float() @ cn.T, n_near, dim=1).indices
     order = torch.argsort(labels, stable=True)                   # members of a cluster, ids ascending
     counts = torch.bincount(labels, minlength=C)
-    starts = torch.cumsum(counts, 0) - counts
+    starts = (torch.cumsum(counts, 0) - counts).tolist()
+    counts = counts.tolist()
+    # the points whose pool holds cluster b, ids ascending: the (point, cluster) pairs ordered by cluster
+    pair_cluster = near.flatten()
+    pair_order = torch.argsort(pair_cluster, stable=True)
+    ask_counts = torch.bincount(pair_cluster, minlength=C)
+    ask_starts = (torch.cumsum(ask_counts, 0) - ask_counts).tolist()
+    ask_counts = ask_counts.tolist()
+    pair_point = pair_order // n_near                            # (a point names a cluster at most once)
     pages = (R + 1 + ANN_K_MAX - 1) // ANN_K_MAX
     best_s = torch.full((N, R), -math.inf, dtype=torch.float32, device=dev)
     best_i = torch.full((N, R), -1, dtype=torch.int64, device=dev)
     last = time.time()
     for b in range(C):
-        nb = int(counts[b])
+        nb = counts[b]
         if nb == 0:
             continue
-        members = order[int(starts[b]): int(starts[b]) + nb]
+        members = order[starts[b]: starts[b] + nb]
         rows = x[members].contiguous()
-        askers = (near == b).any(dim=1).nonzero().flatten()
+        askers = pair_point[ask_starts[b]: ask_starts[b] + ask_counts[b]]
         if progress and time.time() - last > 20:
             print(f"  graph build: cluster {b}/{C} ({nb} members, {askers.numel()} queries)", file=sys.stderr, flush=True)
             last = time.time()
